@@ -1,0 +1,164 @@
+/*
+ * nestedfp.h -- C ABI of the NestedFP hot path for AMD MI355X (gfx950).
+ *
+ * NestedFP (arxiv 2506.02024) stores every FP16 weight of a linear layer once, as two
+ * byte planes of the weight's shape (Sec. 4 "Overview"): `upper` is a valid E4M3 number
+ * equal to the weight times 2^8 rounded to nearest-even, `lower` is the low mantissa byte
+ * (Sec. 4.1).  A GEMM call then runs in one of two modes on the same planes: FP16 mode
+ * rebuilds the exact FP16 weights on the fly (Sec. 4.2), FP8 mode reads only `upper`.
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers unless the parameter name ends in `_host`.
+ *     The caller owns every buffer; the library never allocates or frees device memory
+ *     and never writes to an input.
+ *   - FP16 data travels as uint16_t bit patterns.  W is [N,K] row-major (K contiguous,
+ *     row stride ldw elements), X is [M,K] (row stride ldx), Y is [M,N] (row stride ldy);
+ *     Y = X * W^T.  Planes and quantised activations are dense row-major bytes.
+ *   - K must be a positive multiple of 16; ldw, ldx must be multiples of 8 and >= K;
+ *     ldy must be a multiple of 4 and >= N when N % 4 == 0, else any ldy >= N is taken
+ *     by a slower store path; W, X, planes, Xq and workspace pointers must be 16-byte
+ *     aligned, Y 8-byte aligned.  M >= 1 and N >= 1 are otherwise arbitrary (no padding
+ *     is asked of the caller).  M == 0 or N == 0 is a no-op that returns NESTEDFP_OK.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream except where stated.
+ *   - Argument errors are found before anything is launched and reported as a status
+ *     code; nothing aborts or throws.
+ */
+#ifndef NESTEDFP_H
+#define NESTEDFP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NESTEDFP_OK = 0,
+    NESTEDFP_ERR_ARG = 1,       /* NULL pointer, negative size, unknown mode            */
+    NESTEDFP_ERR_SHAPE = 2,     /* K % 16 != 0, leading dimension too small, misaligned  */
+    NESTEDFP_ERR_RANGE = 3,     /* some |w| > 1.75, Inf or NaN: layer is not applicable  */
+    NESTEDFP_ERR_WORKSPACE = 4, /* workspace missing or smaller than the size query says */
+    NESTEDFP_ERR_HIP = 5        /* a HIP call or launch failed                           */
+} nestedfp_status;
+
+typedef enum {
+    NESTEDFP_MODE_FP16 = 0,     /* both planes, exact FP16 weights, fp16 MFMA            */
+    NESTEDFP_MODE_FP8 = 1       /* upper plane only, E4M3 x E4M3 MFMA, scale 2^-8        */
+} nestedfp_mode;
+
+int nestedfp_version(void);
+const char *nestedfp_status_string(int status);
+
+/*
+ * Applicability test (Sec. 4.1 "Opportunities", "Handling Exception Layers"): a layer
+ * can be stored in the format iff every weight has |w| <= 1.75 (so the FP16 exponent MSB
+ * is zero and rounding cannot leave E4M3's finite range).  Counts the words that do not
+ * fit (Inf and NaN included) into *out_of_range (device, 8 bytes, overwritten).
+ * If out_of_range_host is non-NULL the call also waits for the stream, copies the count
+ * there and returns NESTEDFP_ERR_RANGE when it is non-zero.
+ */
+int nestedfp_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw,
+                         uint64_t *out_of_range, uint64_t *out_of_range_host, void *stream);
+
+/*
+ * Decomposition (Sec. 4.1 "Our Proposal"), done once, offline: for each weight
+ *   upper = S | RNE_7(E[3:0]|M[1:10] -> E[3:0]|M[1:3])   (carry may enter the exponent)
+ *   lower = M[3:10]
+ * written to the dense [N,K] byte planes `upper` and `lower`.  Words that fail the
+ * applicability test are counted into *out_of_range (device, 8 bytes, overwritten; may
+ * be NULL to skip counting) and their plane entries are written as 0.  With
+ * out_of_range_host non-NULL (needs out_of_range too) the call waits for the stream,
+ * copies the count and returns NESTEDFP_ERR_RANGE if it is non-zero: the caller then
+ * keeps the layer in FP16 (an "exception layer") and runs nestedfp_plain_gemm_fp16.
+ */
+int nestedfp_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw,
+                       uint8_t *upper, uint8_t *lower,
+                       uint64_t *out_of_range, uint64_t *out_of_range_host, void *stream);
+
+/*
+ * Lossless reconstruction (Sec. 4.1 "FP16 Reconstruction", Sec. 4.2 Alg. 1): rebuilds the
+ * FP16 words from the planes; if the LSB of upper differs from the MSB of lower the
+ * rounding is undone first.  Exact inverse of nestedfp_decompose on planes it produced;
+ * for byte pairs that no in-range weight produces the result is unspecified.
+ */
+int nestedfp_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
+                         uint16_t *W, int64_t ldw, void *stream);
+
+/*
+ * Activation quantisation for FP8 mode (Sec. 2.2 "E4M3 Format": dynamic per-token or
+ * static per-tensor scaling; Sec. 5.1 uses per-token).  For each row m of X:
+ *   scale[m] = amax_k |X[m,k]| / 448   (one binary32 division; 1 if the row is all zero)
+ *   Xq[m,k]  = E4M3_RNE_saturating( binary32(X[m,k]) / scale[m] )
+ * With static_scale non-NULL (device, one float) that value is used for every row.
+ * Xq is dense [M,K] bytes, scales is [M] floats.  X must be finite.
+ */
+int nestedfp_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                          const float *static_scale, uint8_t *Xq, float *scales, void *stream);
+
+/*
+ * Bytes of caller-provided scratch that nestedfp_gemm (or a plain baseline, which take
+ * the same query with the corresponding mode) needs for this problem: split-K partial
+ * sums and, in FP8 mode, the quantised activations with their scales.  Grows with M*K and
+ * M*N, never with N*K: no weight copy is ever made.  Returns 0 for invalid arguments.
+ */
+size_t nestedfp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int mode);
+
+/*
+ * The linear layer Y = X * W^T over the two planes (Sec. 4 "Overview", Sec. 4.2).
+ *   FP16 mode: streams both planes, merges them into exact FP16 weights inside the
+ *     kernel, fp16 MFMA with fp32 accumulation, fp16 output.  Bitwise equal to
+ *     nestedfp_plain_gemm_fp16 on the original weights.
+ *   FP8 mode: quantises X per token (or with *act_scale, device float, if non-NULL),
+ *     multiplies E4M3 activations by the upper plane read as E4M3, fp32 accumulation,
+ *     scales by scale[m] * 2^-8 (Sec. 4.1: the upper plane is the weight times 2^8),
+ *     fp16 output.  `lower` is never read and may be NULL.
+ * workspace must hold at least nestedfp_gemm_workspace_size(M,N,K,mode) bytes.
+ */
+int nestedfp_gemm(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                  const uint8_t *upper, const uint8_t *lower, int64_t N,
+                  int mode, const float *act_scale,
+                  uint16_t *Y, int64_t ldy,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Plain baselines of the same kernel family, for the comparison of Sec. 5.2 (NestedFP
+ * FP16 mode against an FP16 GEMM that reads ordinary FP16 weights) and its FP8 analogue.
+ * plain_gemm_fp16: W is ordinary FP16 [N,K].
+ * plain_gemm_fp8:  Wq is any dense E4M3 [N,K] tensor with one host-side float scale;
+ *   Y = scale[m] * w_scale * sum_k e4m3(Xq) * e4m3(Wq).  Feeding it the upper plane with
+ *   w_scale = 2^-8 is, by Sec. 4 "Challenge 2", exactly FP8 mode.
+ */
+int nestedfp_plain_gemm_fp16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                             const uint16_t *W, int64_t N, int64_t ldw,
+                             uint16_t *Y, int64_t ldy,
+                             void *workspace, size_t workspace_bytes, void *stream);
+int nestedfp_plain_gemm_fp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                            const uint8_t *Wq, int64_t N, float w_scale,
+                            const float *act_scale,
+                            uint16_t *Y, int64_t ldy,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * FP8-mode GEMM from activations that are already quantised (Xq dense [M,K] E4M3 bytes,
+ * scales [M] floats), e.g. by nestedfp_quantize_act; lets a caller quantise once and
+ * reuse the result for several linears that share X.  Same arithmetic as FP8 mode.
+ */
+int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64_t M, int64_t K,
+                                   const uint8_t *upper, int64_t N, float w_scale,
+                                   uint16_t *Y, int64_t ldy,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmark sweeps: overrides one launch parameter process-wide
+ * (not thread-safe).  knob names are listed in nestedfp_tune_name(i), i = 0.. until NULL.
+ * value < 0 restores the built-in choice.  Returns NESTEDFP_ERR_ARG for unknown knobs.
+ */
+int nestedfp_tune(const char *knob, int64_t value);
+const char *nestedfp_tune_name(int index);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NESTEDFP_H */

@@ -1,0 +1,231 @@
+"""Python binding of the NestedFP C ABI (include/nestedfp.h): argument marshalling only.
+
+Tensors are torch CUDA tensors (device memory and the current stream come from
+PyTorch); every computation runs in the HIP library.  The library is loaded on first
+use and a missing build is an error -- there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+MODE_FP16 = 0
+MODE_FP8 = 1
+
+OK, ERR_ARG, ERR_SHAPE, ERR_RANGE, ERR_WORKSPACE, ERR_HIP = range(6)
+
+_lib = None
+
+
+class NestedFPError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+def lib():
+    """The loaded libnestedfp.so (ctypes.CDLL)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "NestedFP HIP library not built: %s is missing; run "
+            "`python -c 'import __graft_entry__ as g; g.build()'` first" % path)
+    L = ctypes.CDLL(path)
+    c = ctypes
+    vp, i64, sz, ci, f32 = c.c_void_p, c.c_int64, c.c_size_t, c.c_int, c.c_float
+    L.nestedfp_version.restype = ci
+    L.nestedfp_version.argtypes = []
+    L.nestedfp_status_string.restype = c.c_char_p
+    L.nestedfp_status_string.argtypes = [ci]
+    L.nestedfp_range_check.restype = ci
+    L.nestedfp_range_check.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.nestedfp_decompose.restype = ci
+    L.nestedfp_decompose.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    L.nestedfp_reconstruct.restype = ci
+    L.nestedfp_reconstruct.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    L.nestedfp_quantize_act.restype = ci
+    L.nestedfp_quantize_act.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    L.nestedfp_gemm_workspace_size.restype = sz
+    L.nestedfp_gemm_workspace_size.argtypes = [i64, i64, i64, ci]
+    L.nestedfp_gemm.restype = ci
+    L.nestedfp_gemm.argtypes = [vp, i64, i64, i64, vp, vp, i64, ci, vp, vp, i64, vp, sz, vp]
+    L.nestedfp_plain_gemm_fp16.restype = ci
+    L.nestedfp_plain_gemm_fp16.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, sz, vp]
+    L.nestedfp_plain_gemm_fp8.restype = ci
+    L.nestedfp_plain_gemm_fp8.argtypes = [vp, i64, i64, i64, vp, i64, f32, vp, vp, i64, vp, sz, vp]
+    L.nestedfp_gemm_fp8_prequantized.restype = ci
+    L.nestedfp_gemm_fp8_prequantized.argtypes = [vp, vp, i64, i64, vp, i64, f32, vp, i64, vp, sz, vp]
+    L.nestedfp_tune.restype = ci
+    L.nestedfp_tune.argtypes = [c.c_char_p, i64]
+    L.nestedfp_tune_name.restype = c.c_char_p
+    L.nestedfp_tune_name.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return lib().nestedfp_status_string(int(status)).decode()
+
+
+def version():
+    return lib().nestedfp_version()
+
+
+def tune(knob, value):
+    st = lib().nestedfp_tune(knob.encode(), int(value))
+    if st != OK:
+        raise NestedFPError(st, "nestedfp_tune(%s)" % knob)
+
+
+def _check(st, where):
+    if st != OK:
+        raise NestedFPError(st, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _rowmajor(t, name):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("%s must be 2-D with unit inner stride" % name)
+    return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def range_check(W):
+    """Number of weights of W (fp16 [N,K]) outside the format's range (synchronises)."""
+    N, K, ldw = _rowmajor(W, "W")
+    cnt = torch.empty(1, dtype=torch.int64, device=W.device)
+    host = ctypes.c_uint64(0)
+    st = lib().nestedfp_range_check(_ptr(W), N, K, ldw, _ptr(cnt), ctypes.byref(host), _stream())
+    if st not in (OK, ERR_RANGE):
+        raise NestedFPError(st, "nestedfp_range_check")
+    return int(host.value)
+
+
+def decompose(W, upper=None, lower=None, check=True):
+    """fp16 W [N,K] -> (upper, lower) uint8 planes.  With check=True (default) waits for
+    the result and raises NestedFPError(ERR_RANGE) if the layer is not applicable."""
+    N, K, ldw = _rowmajor(W, "W")
+    if upper is None:
+        upper = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    if lower is None:
+        lower = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    cnt = torch.empty(1, dtype=torch.int64, device=W.device)
+    host = ctypes.c_uint64(0)
+    st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
+                                  ctypes.byref(host) if check else None, _stream())
+    _check(st, "nestedfp_decompose")
+    return upper, lower
+
+
+def decompose_count(W):
+    """Like decompose(check=False) but also returns the out-of-range count (synchronises)."""
+    N, K, ldw = _rowmajor(W, "W")
+    upper = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    lower = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    cnt = torch.empty(1, dtype=torch.int64, device=W.device)
+    host = ctypes.c_uint64(0)
+    st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
+                                  ctypes.byref(host), _stream())
+    if st not in (OK, ERR_RANGE):
+        raise NestedFPError(st, "nestedfp_decompose")
+    return upper, lower, int(host.value)
+
+
+def reconstruct(upper, lower, out=None):
+    N, K, _ = _rowmajor(upper, "upper")
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=upper.device)
+    _, _, ldw = _rowmajor(out, "out")
+    st = lib().nestedfp_reconstruct(_ptr(upper), _ptr(lower), N, K, _ptr(out), ldw, _stream())
+    _check(st, "nestedfp_reconstruct")
+    return out
+
+
+def quantize_act(X, static_scale=None):
+    """fp16 X [M,K] -> (Xq uint8 [M,K] E4M3 codes, scales float32 [M])."""
+    M, K, ldx = _rowmajor(X, "X")
+    Xq = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    scales = torch.empty((M,), dtype=torch.float32, device=X.device)
+    st = lib().nestedfp_quantize_act(_ptr(X), M, K, ldx, _ptr(static_scale), _ptr(Xq), _ptr(scales),
+                                     _stream())
+    _check(st, "nestedfp_quantize_act")
+    return Xq, scales
+
+
+def gemm_workspace_size(M, N, K, mode):
+    return int(lib().nestedfp_gemm_workspace_size(M, N, K, mode))
+
+
+def gemm(X, upper, lower, mode, act_scale=None, out=None, workspace=None):
+    """Y = X @ W^T over the planes, in MODE_FP16 or MODE_FP8 (lower may be None in FP8)."""
+    M, K, ldx = _rowmajor(X, "X")
+    N = upper.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _, _, ldy = _rowmajor(out, "out")
+    if workspace is None:
+        workspace = _workspace(gemm_workspace_size(M, N, K, mode), X.device)
+    st = lib().nestedfp_gemm(_ptr(X), M, K, ldx, _ptr(upper), _ptr(lower), N, int(mode),
+                             _ptr(act_scale), _ptr(out), ldy, _ptr(workspace), workspace.numel(),
+                             _stream())
+    _check(st, "nestedfp_gemm")
+    return out
+
+
+def plain_gemm_fp16(X, W, out=None, workspace=None):
+    M, K, ldx = _rowmajor(X, "X")
+    N, _, ldw = _rowmajor(W, "W")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _, _, ldy = _rowmajor(out, "out")
+    if workspace is None:
+        workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP16), X.device)
+    st = lib().nestedfp_plain_gemm_fp16(_ptr(X), M, K, ldx, _ptr(W), N, ldw, _ptr(out), ldy,
+                                        _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "nestedfp_plain_gemm_fp16")
+    return out
+
+
+def plain_gemm_fp8(X, Wq, w_scale, act_scale=None, out=None, workspace=None):
+    M, K, ldx = _rowmajor(X, "X")
+    N = Wq.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _, _, ldy = _rowmajor(out, "out")
+    if workspace is None:
+        workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP8), X.device)
+    st = lib().nestedfp_plain_gemm_fp8(_ptr(X), M, K, ldx, _ptr(Wq), N, float(w_scale),
+                                       _ptr(act_scale), _ptr(out), ldy, _ptr(workspace),
+                                       workspace.numel(), _stream())
+    _check(st, "nestedfp_plain_gemm_fp8")
+    return out
+
+
+def gemm_fp8_prequantized(Xq, scales, upper, w_scale=2.0 ** -8, out=None, workspace=None):
+    M, K = Xq.shape
+    N = upper.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=Xq.device)
+    _, _, ldy = _rowmajor(out, "out")
+    if workspace is None:
+        workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP8), Xq.device)
+    st = lib().nestedfp_gemm_fp8_prequantized(_ptr(Xq), _ptr(scales), M, K, _ptr(upper), N,
+                                              float(w_scale), _ptr(out), ldy, _ptr(workspace),
+                                              workspace.numel(), _stream())
+    _check(st, "nestedfp_gemm_fp8_prequantized")
+    return out

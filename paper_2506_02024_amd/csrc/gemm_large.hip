@@ -1,0 +1,345 @@
+// LDS-tiled MFMA GEMM for prefill-sized batches: Y = X * W^T, compute-bound.
+//
+// Sec. 4.2 puts the FP16 reconstruction between the shared-memory-to-register copy and
+// the tensor-core instruction of every warp and hides it with a third pipeline stage.
+// Here the planes are merged ONCE per workgroup on their way from HBM to LDS
+// (global -> VGPR -> Alg. 1 -> ds_write of finished FP16), so the MFMA loop that follows
+// is the plain FP16 loop and the merge costs ~2 VALU ops per weight per workgroup instead
+// of per wave.  Global loads for K-tile t+1 are issued before the MFMAs of K-tile t
+// (register prefetch) and land in the other half of a double-buffered LDS tile.
+//
+// Tile: TM tokens x TN weight rows x 128 bytes of K per row (64 halves or 128 E4M3 bytes),
+// 8 waves as 2 (tokens) x 4 (weight rows).  Weight rows are the MFMA "A" operand and
+// tokens the "B" operand, so a lane holds 4 consecutive output columns of one token.
+// LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with the row so that
+// both the 128-bit writes and the MFMA-fragment reads are free of bank conflicts.
+#include "nfp_device.h"
+#include "nfp_host.h"
+
+namespace nfp {
+
+constexpr int kLargeThreads = 512;
+
+struct LargeParams {
+    const uint8_t *X;       // fp16 X (bytes) or E4M3 Xq
+    int64_t x_row_bytes;
+    const float *scales;
+    float w_scale;
+    const uint8_t *W0;
+    const uint8_t *W1;
+    int64_t w_row_bytes;    // bytes per row of W0 (plain: 2*ldw, planes / E4M3: K)
+    int M, N, K;
+    int k_bytes;            // bytes per row along K for 8-chunk operands (2K or K)
+    uint16_t *Y;
+    int64_t ldy;
+    float *partials;
+    int tiles_m, tiles_n;
+    int ktiles_total, ktiles_per_split;
+    int vec_store;
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+template <int KIND, int TM, int TN>
+struct LargeKernel {
+    static constexpr int WAVES_M = 2, WAVES_N = 4;
+    static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
+    static constexpr int FM = WTM / 32, FN = WTN / 32;
+    static constexpr int XP = TM / 64;                 // 8-chunk passes for the token tile
+    static constexpr int WP8 = TN / 64;                // 8-chunk passes for the weight tile
+    static constexpr int WP4 = TN / 128 > 0 ? TN / 128 : 1;   // nested: 4 double-chunks per row
+    static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
+    static constexpr int LDS_BYTES = 2 * STAGE;
+
+    struct Prefetch {
+        u32x4 x[XP];
+        u32x4 w[KIND == kNestedF16 ? 2 * WP4 : WP8];
+    };
+
+    static __device__ __forceinline__ void load_global(Prefetch &pf, const LargeParams &p, int m0,
+                                                       int n0, int kt) {
+        const int t = threadIdx.x;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        const int kb = kt * 128;                       // byte offset along K for 8-chunk operands
+        {
+            const int c = t & 7, r0 = t >> 3;
+            const bool kok = kb + 16 * c < p.k_bytes;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                int row = min(m0 + r0 + 64 * i, p.M - 1);
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(p.X + (int64_t)row * p.x_row_bytes + kb + 16 * c);
+                pf.x[i] = kok ? *src : zero;
+            }
+        }
+        if (KIND == kNestedF16) {
+            const int c4 = t & 3, r0 = t >> 2;
+            const int k = kt * 64 + 16 * c4;           // element (= byte) offset in the planes
+            const bool kok = k < p.K;
+#pragma unroll
+            for (int i = 0; i < WP4; ++i) {
+                int row = min(n0 + r0 + 128 * i, p.N - 1);
+                int64_t off = (int64_t)row * p.w_row_bytes + k;
+                pf.w[2 * i] = kok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W0 + off)) : zero;
+                pf.w[2 * i + 1] = kok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W1 + off)) : zero;
+            }
+        } else {
+            const int c = t & 7, r0 = t >> 3;
+            const bool kok = kb + 16 * c < p.k_bytes;
+#pragma unroll
+            for (int i = 0; i < WP8; ++i) {
+                int row = min(n0 + r0 + 64 * i, p.N - 1);
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(p.W0 + (int64_t)row * p.w_row_bytes + kb + 16 * c);
+                pf.w[i] = kok ? *src : zero;
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void store_lds(const Prefetch &pf, uint8_t *stage) {
+        const int t = threadIdx.x;
+        uint8_t *sW = stage, *sX = stage + TN * 128;
+        {
+            const int c = t & 7, r0 = t >> 3;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                int row = r0 + 64 * i;
+                *reinterpret_cast<u32x4 *>(sX + swz(row, c)) = pf.x[i];
+            }
+        }
+        if (KIND == kNestedF16) {
+            const int c4 = t & 3, r0 = t >> 2;
+#pragma unroll
+            for (int i = 0; i < WP4; ++i) {
+                int row = r0 + 128 * i;
+                if (TN < 128 && row >= TN) continue;
+                u32x4 w_lo, w_hi;
+                merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);   // Sec. 4.2, Alg. 1
+                *reinterpret_cast<u32x4 *>(sW + swz(row, 2 * c4)) = w_lo;
+                *reinterpret_cast<u32x4 *>(sW + swz(row, 2 * c4 + 1)) = w_hi;
+            }
+        } else {
+            const int c = t & 7, r0 = t >> 3;
+#pragma unroll
+            for (int i = 0; i < WP8; ++i) {
+                int row = r0 + 64 * i;
+                *reinterpret_cast<u32x4 *>(sW + swz(row, c)) = pf.w[i];
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void compute(const uint8_t *stage, floatx16 (&acc)[FN][FM],
+                                                   int wm, int wn, int lane) {
+        const uint8_t *sW = stage, *sX = stage + TN * 128;
+        const int r32 = lane & 31, h = lane >> 5;
+        if (KIND == kE4M3) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                intx8 a[FN], b[FM];
+                const int c = 4 * s + 2 * h;
+#pragma unroll
+                for (int i = 0; i < FN; ++i) {
+                    int row = wn * WTN + 32 * i + r32;
+                    intx4 lo = *reinterpret_cast<const intx4 *>(sW + swz(row, c));
+                    intx4 hi = *reinterpret_cast<const intx4 *>(sW + swz(row, c + 1));
+                    a[i] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                }
+#pragma unroll
+                for (int j = 0; j < FM; ++j) {
+                    int row = wm * WTM + 32 * j + r32;
+                    intx4 lo = *reinterpret_cast<const intx4 *>(sX + swz(row, c));
+                    intx4 hi = *reinterpret_cast<const intx4 *>(sX + swz(row, c + 1));
+                    b[j] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                }
+#pragma unroll
+                for (int i = 0; i < FN; ++i)
+#pragma unroll
+                    for (int j = 0; j < FM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0,
+                                                                                    0, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                half8 a[FN], b[FM];
+                const int c = 2 * s + h;
+#pragma unroll
+                for (int i = 0; i < FN; ++i)
+                    a[i] = *reinterpret_cast<const half8 *>(sW + swz(wn * WTN + 32 * i + r32, c));
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+                    b[j] = *reinterpret_cast<const half8 *>(sX + swz(wm * WTM + 32 * j + r32, c));
+#pragma unroll
+                for (int i = 0; i < FN; ++i)
+#pragma unroll
+                    for (int j = 0; j < FM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds) {
+        const int lane = threadIdx.x & 63;
+        const int wave = threadIdx.x >> 6;
+        const int wm = wave & 1, wn = wave >> 1;
+        const int tile = blockIdx.x;
+        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        const int m0 = tm * TM, n0 = tn * TN;
+        const int split = blockIdx.y;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
+
+        floatx16 acc[FN][FM];
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+        Prefetch pf;
+        if (kt_begin < kt_end) {
+            load_global(pf, p, m0, n0, kt_begin);
+            store_lds(pf, lds);
+        }
+        __syncthreads();
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            const int cur = (kt - kt_begin) & 1;
+            const bool more = kt + 1 < kt_end;
+            if (more) load_global(pf, p, m0, n0, kt + 1);
+            compute(lds + cur * STAGE, acc, wm, wn, lane);
+            if (more) store_lds(pf, lds + (cur ^ 1) * STAGE);
+            __syncthreads();
+        }
+
+        // ---- epilogue ---------------------------------------------------------------
+        const int r32 = lane & 31, h = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const int m = m0 + wm * WTM + 32 * j + r32;
+            if (m >= p.M) continue;
+            float s = 1.0f;
+            if (KIND == kE4M3 && gridDim.y == 1) s = p.scales[m] * p.w_scale;
+#pragma unroll
+            for (int i = 0; i < FN; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * WTN + 32 * i + 8 * q + 4 * h;
+                    if (n >= p.N) continue;
+                    float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                  acc[i][j][4 * q + 3]};
+                    if (gridDim.y > 1) {
+                        float *dst = p.partials + ((int64_t)split * p.M + m) * p.N + n;
+                        if ((p.N & 3) == 0) {
+                            *reinterpret_cast<floatx4 *>(dst) = floatx4{v[0], v[1], v[2], v[3]};
+                        } else {
+                            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
+                        }
+                    } else {
+                        uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
+                        if (p.vec_store) {
+                            u32x2 o;
+                            o.x = float2_to_half2_bits(v[0] * s, v[1] * s);
+                            o.y = float2_to_half2_bits(v[2] * s, v[3] * s);
+                            *reinterpret_cast<u32x2 *>(dst) = o;
+                        } else {
+                            for (int e = 0; e < 4 && n + e < p.N; ++e) {
+                                union { _Float16 f; uint16_t u; } c;
+                                c.f = (_Float16)(v[e] * s);
+                                dst[e] = c.u;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <int KIND, int TM, int TN>
+__global__ void __launch_bounds__(kLargeThreads)
+large_gemm_kernel(LargeParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    LargeKernel<KIND, TM, TN>::run(p, lds_raw);
+}
+
+struct LargeConfig { int tm, tn, split; };
+
+static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
+    LargeConfig c;
+    const Tuning &t = tuning();
+    int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    c.tm = c.tn = (tiles256 >= 256) ? 256 : 128;
+    if (t.large_bm == 128 || t.large_bm == 256) c.tm = c.tn = (int)t.large_bm;
+    int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
+    int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
+    c.split = 1;
+    if (tiles < 256) {                                  // fewer tiles than CUs: split K
+        int64_t s = (512 + tiles - 1) / tiles;
+        if (s > 8) s = 8;
+        if (s > kt / 4) s = kt / 4 > 0 ? kt / 4 : 1;
+        c.split = (int)s;
+    }
+    if (t.large_split > 0) c.split = (int)(t.large_split < kt ? t.large_split : kt);
+    return c;
+}
+
+size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
+    LargeConfig c = choose_large(kind, M, N, K);
+    return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+template <int KIND, int TM, int TN>
+static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
+    auto kern = large_gemm_kernel<KIND, TM, TN>;
+    constexpr int lds = LargeKernel<KIND, TM, TN>::LDS_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    kern<<<grid, kLargeThreads, lds, stream>>>(p);
+}
+
+template <int KIND>
+static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
+    if (c.tm == 256) launch_large_t<KIND, 256, 256>(p, grid, stream);
+    else launch_large_t<KIND, 128, 128>(p, grid, stream);
+}
+
+int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
+    LargeConfig c = choose_large(kind, a.M, a.N, a.K);
+    LargeParams p;
+    p.X = static_cast<const uint8_t *>(a.X);
+    p.x_row_bytes = (kind == kE4M3) ? a.ldx : 2 * a.ldx;
+    p.scales = a.scales;
+    p.w_scale = a.w_scale;
+    p.W0 = static_cast<const uint8_t *>(a.W0);
+    p.W1 = static_cast<const uint8_t *>(a.W1);
+    p.w_row_bytes = (kind == kPlainF16) ? 2 * a.ldw : a.K;
+    p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
+    p.k_bytes = (kind == kE4M3) ? (int)a.K : (int)(2 * a.K);
+    p.Y = a.Y;  p.ldy = a.ldy;
+    p.partials = a.partials;
+    p.tiles_m = (int)((a.M + c.tm - 1) / c.tm);
+    p.tiles_n = (int)((a.N + c.tn - 1) / c.tn);
+    p.ktiles_total = (p.k_bytes + 127) / 128;
+    p.ktiles_per_split = (p.ktiles_total + c.split - 1) / c.split;
+    c.split = (p.ktiles_total + p.ktiles_per_split - 1) / p.ktiles_per_split;   // no empty slices
+    p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
+    if (c.split > 1 && (a.partials == nullptr ||
+                        a.partial_bytes < (size_t)c.split * a.M * a.N * sizeof(float)))
+        return kErrWorkspace;
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)c.split);
+    switch (kind) {
+        case kPlainF16: launch_large_k<kPlainF16>(p, c, grid, stream); break;
+        case kNestedF16: launch_large_k<kNestedF16>(p, c, grid, stream); break;
+        default: launch_large_k<kE4M3>(p, c, grid, stream); break;
+    }
+    if (hipGetLastError() != hipSuccess) return kErrHip;
+    if (c.split > 1)
+        return launch_splitk_reduce(a.partials, c.split, a.M, a.N, kind == kE4M3 ? a.scales : nullptr,
+                                    a.w_scale, a.Y, a.ldy, stream);
+    return kOk;
+}
+
+}  // namespace nfp

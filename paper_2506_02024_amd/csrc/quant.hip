@@ -1,0 +1,80 @@
+// Per-token activation quantisation to E4M3 for FP8 mode (Sec. 2.2 "E4M3 Format",
+// Sec. 5.1 "Methodology").  One workgroup per token row: pass 1 finds the row's largest
+// magnitude, pass 2 (the row is still in cache) divides and converts.  HBM-bound:
+// 2 bytes read + 1 byte written per activation.
+#include "nfp_device.h"
+#include "nfp_host.h"
+
+namespace nfp {
+
+constexpr int kQuantThreads = 256;
+
+template <bool HW>
+__device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s) {
+    // binary32 division, correctly rounded (no fast-math): the quotient is what gets rounded
+    float a = clamp448(half_bits_to_float(w01 & 0xffffu) / s);
+    float b = clamp448(half_bits_to_float(w01 >> 16) / s);
+    float c = clamp448(half_bits_to_float(w23 & 0xffffu) / s);
+    float d = clamp448(half_bits_to_float(w23 >> 16) / s);
+    if (HW) return e4m3x4_from_float_hw(a, b, c, d);
+    return e4m3_from_float_sw(a) | (e4m3_from_float_sw(b) << 8) | (e4m3_from_float_sw(c) << 16) |
+           (e4m3_from_float_sw(d) << 24);
+}
+
+template <bool HW>
+__global__ void __launch_bounds__(kQuantThreads)
+quantize_act_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
+                    const float *__restrict__ static_scale, uint8_t *__restrict__ Xq,
+                    float *__restrict__ scales) {
+    const int64_t m = blockIdx.x;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + m * ldx);
+    const int chunks = (int)(K / 8);                 // 8 halves per 16-byte chunk
+    __shared__ uint32_t red[kQuantThreads / 64];
+    float s;
+    if (static_scale) {
+        s = *static_scale;
+    } else {
+        // |x| as an integer compare on the magnitude bits: monotone for finite halves
+        uint32_t amax_bits = 0;
+        for (int c = threadIdx.x; c < chunks; c += kQuantThreads) {
+            u32x4 v = row[c];
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t lo = w[i] & 0x7fffu, hi = (w[i] >> 16) & 0x7fffu;
+                amax_bits = max(amax_bits, max(lo, hi));
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1)
+            amax_bits = max(amax_bits, (uint32_t)__shfl_xor((int)amax_bits, off, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax_bits;
+        __syncthreads();
+        uint32_t all = 0;
+#pragma unroll
+        for (int i = 0; i < kQuantThreads / 64; ++i) all = max(all, red[i]);
+        float amax = half_bits_to_float(all);
+        s = (amax == 0.0f) ? 1.0f : amax / 448.0f;
+    }
+    if (threadIdx.x == 0) scales[m] = s;
+    u32x2 *out = reinterpret_cast<u32x2 *>(Xq + m * K);
+    for (int c = threadIdx.x; c < chunks; c += kQuantThreads) {
+        u32x4 v = row[c];
+        u32x2 q;
+        q.x = quant4<HW>(v.x, v.y, s);
+        q.y = quant4<HW>(v.z, v.w, s);
+        out[c] = q;
+    }
+}
+
+int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                        const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream) {
+    bool hw = tuning().quant_hw != 0;
+    dim3 grid((unsigned)M);
+    if (hw)
+        quantize_act_kernel<true><<<grid, kQuantThreads, 0, stream>>>(X, K, ldx, static_scale, Xq, scales);
+    else
+        quantize_act_kernel<false><<<grid, kQuantThreads, 0, stream>>>(X, K, ldx, static_scale, Xq, scales);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace nfp

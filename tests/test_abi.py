@@ -1,0 +1,92 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments before touching a device (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nestedfp.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2506_02024_amd import binding, build
+
+    if build.is_stale():
+        build.build_library()
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nestedfp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls_of_the_method():
+    names = declared_symbols()
+    for n in ("nestedfp_decompose", "nestedfp_gemm", "nestedfp_reconstruct"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(L):
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+        assert ctypes.cast(getattr(L, name), ctypes.c_void_p).value
+
+
+def test_status_strings(L):
+    seen = set()
+    for st in range(6):
+        s = L.nestedfp_status_string(st).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert L.nestedfp_version() >= 100
+
+
+def test_workspace_query_never_scales_with_weight_count(L):
+    ws = L.nestedfp_gemm_workspace_size
+    for mode in (0, 1):
+        a = ws(16, 4096, 4096, mode)
+        b = ws(16, 4096, 4 * 4096, mode)
+        # grows at most with M*K (quantised activations), never with N*K
+        assert b - a <= 16 * 3 * 4096 + 1024
+        assert ws(16, 4096, 4096, mode) < 4096 * 4096 // 4
+    assert ws(16, 4096, 4100, 0) == 0        # K % 16 != 0
+    assert ws(16, 4096, 4096, 7) == 0        # unknown mode
+    assert ws(-1, 4096, 4096, 0) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch(L):
+    P = ctypes.c_void_p
+    fake = P(0x1000)         # aligned, never dereferenced: every call below fails validation first
+    # NULL pointers
+    assert L.nestedfp_decompose(P(0), 4, 16, 16, fake, fake, P(0), P(0), P(0)) == 1
+    assert L.nestedfp_decompose(fake, 4, 16, 16, P(0), fake, P(0), P(0), P(0)) == 1
+    assert L.nestedfp_reconstruct(P(0), fake, 4, 16, fake, 16, P(0)) == 1
+    # K not a multiple of 16, leading dimension too small, misaligned pointer
+    assert L.nestedfp_decompose(fake, 4, 24, 24, fake, fake, P(0), P(0), P(0)) == 2
+    assert L.nestedfp_decompose(fake, 4, 32, 16, fake, fake, P(0), P(0), P(0)) == 2
+    assert L.nestedfp_decompose(P(0x1004), 4, 32, 32, fake, fake, P(0), P(0), P(0)) == 2
+    # gemm: unknown mode, FP16 mode without the lower plane, K % 16
+    args = lambda mode, lower, K: (fake, 4, K, K, fake, lower, 8, mode, P(0), fake, 8, fake, 1 << 20, P(0))
+    assert L.nestedfp_gemm(*args(5, fake, 32)) == 1
+    assert L.nestedfp_gemm(*args(0, P(0), 32)) == 1
+    assert L.nestedfp_gemm(*args(0, fake, 40)) == 2
+    # workspace missing / too small for FP8 mode (quantised activations live there)
+    assert L.nestedfp_gemm(fake, 4, 32, 32, fake, P(0), 8, 1, P(0), fake, 8, P(0), 0, P(0)) == 4
+    assert L.nestedfp_gemm(fake, 4, 32, 32, fake, P(0), 8, 1, P(0), fake, 8, fake, 8, P(0)) == 4
+    # empty problems are a no-op
+    assert L.nestedfp_gemm(fake, 0, 32, 32, fake, fake, 8, 0, P(0), fake, 8, P(0), 0, P(0)) == 0
+    assert L.nestedfp_reconstruct(fake, fake, 0, 32, fake, 32, P(0)) == 0
+    # tuning hook
+    assert L.nestedfp_tune(b"no_such_knob", 1) == 1
+    assert L.nestedfp_tune(b"small_split", 2) == 0 and L.nestedfp_tune(b"small_split", -1) == 0
+    names = []
+    i = 0
+    while L.nestedfp_tune_name(i):
+        names.append(L.nestedfp_tune_name(i).decode())
+        i += 1
+    assert "small_split" in names and "large_bm" in names

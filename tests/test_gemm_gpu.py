@@ -1,0 +1,256 @@
+"""GPU parity: both GEMM modes against the fp64 oracle, the plain baselines, edge cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_02024_amd import workloads
+from helpers import assert_gemm_close, bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nfp():
+    from paper_2506_02024_amd import binding
+
+    return binding
+
+
+def run_both_modes(nfp, X, W, what, check_plain=True):
+    """Runs decompose + FP16 mode + FP8 mode on the GPU and checks all against the oracle."""
+    Xd, Wd = to_dev(X), to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    up_ref, lo_ref, bad = oracle.decompose(W)
+    assert bad == 0
+    assert np.array_equal(up.cpu().numpy(), up_ref) and np.array_equal(lo.cpu().numpy(), lo_ref)
+    # FP16 mode
+    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+    ref16 = oracle.gemm_fp16(X, W)
+    assert_gemm_close(y16.cpu().numpy(), ref16, what + " FP16 mode")
+    if check_plain:
+        yp = nfp.plain_gemm_fp16(Xd, Wd)
+        assert np.array_equal(bits(yp), bits(y16)), what + ": FP16 mode differs from the plain fp16 GEMM"
+    # FP8 mode: lower plane is not passed at all
+    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
+    Xq, s = oracle.quantize_act(X)
+    ref8 = oracle.gemm_fp8(Xq, s, up_ref)
+    assert_gemm_close(y8.cpu().numpy(), ref8, what + " FP8 mode")
+    if check_plain:
+        yp8 = nfp.plain_gemm_fp8(Xd, up, 2.0 ** -8)
+        assert np.array_equal(bits(yp8), bits(y8)), what + ": FP8 mode differs from the plain fp8 GEMM"
+    return y16, y8
+
+
+def test_config1_single_linear(nfp):
+    # W [1024,1024] sigma 0.02, X [16,1024] sigma 1
+    W = workloads.weight_host(1024, 1024, workloads.SIGMA_W_8B, seed=0)
+    X = workloads.act_host(16, 1024, seed=0)
+    run_both_modes(nfp, X, W, "config 1")
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 15, 16, 17, 31, 32, 33, 48, 63, 64])
+def test_decode_sized_batches(nfp, M):
+    # several 16-row weight tiles, a ragged N tail and a K that is not a multiple of 64 / 128
+    N, K = 16 * 9 + 8, 64 * 5 + 16
+    W = workloads.weight_host(N, K, seed=M)
+    X = workloads.act_host(M, K, seed=M)
+    run_both_modes(nfp, X, W, "M=%d" % M)
+
+
+@pytest.mark.parametrize("N,K", [(4, 16), (16, 16), (20, 32), (1, 4096), (257, 2048), (6, 144)])
+def test_decode_odd_layer_shapes(nfp, N, K):
+    W = workloads.weight_host(N, K, seed=N)
+    X = workloads.act_host(4, K, seed=K)
+    run_both_modes(nfp, X, W, "N=%d K=%d" % (N, K))
+
+
+@pytest.mark.parametrize("knobs", [
+    {"small_waves": 1, "small_split": 1},
+    {"small_waves": 4, "small_split": 1},
+    {"small_waves": 2, "small_split": 3},
+    {"small_waves": 16, "small_split": 2, "small_nt": 1},
+    {"small_nt": 4, "small_waves": 2},
+    {"small_nt": 2, "small_split": 4},
+])
+def test_decode_launch_shapes(nfp, knobs):
+    # every combination of in-workgroup and grid-level K split gives the same answer
+    W = workloads.weight_host(304, 2048 + 64, seed=21)
+    X = workloads.act_host(16, 2048 + 64, seed=21)
+    for k, v in knobs.items():
+        nfp.tune(k, v)
+    try:
+        run_both_modes(nfp, X, W, str(knobs))
+        X2 = workloads.act_host(40, 2048 + 64, seed=22)
+        run_both_modes(nfp, X2, W, str(knobs) + " M=40")
+    finally:
+        for k in knobs:
+            nfp.tune(k, -1)
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (65, 128, 64), (128, 128, 128), (200, 264, 208), (300, 520, 1040), (512, 1024, 1024),
+    (257, 129, 4096), (1024, 300, 528),
+])
+def test_prefill_sized_batches(nfp, M, N, K):
+    W = workloads.weight_host(N, K, seed=M + N)
+    X = workloads.act_host(M, K, seed=K)
+    run_both_modes(nfp, X, W, "M=%d N=%d K=%d" % (M, N, K))
+
+
+@pytest.mark.parametrize("knobs", [
+    {"large_bm": 256, "large_split": 1},
+    {"large_bm": 128, "large_split": 1},
+    {"large_bm": 256, "large_split": 3},
+    {"large_bm": 128, "large_split": 5},
+    {"small_max_m": 0},                       # route a decode-sized batch through the tiled kernel
+])
+def test_prefill_launch_shapes(nfp, knobs):
+    W = workloads.weight_host(520, 1040, seed=31)
+    for k, v in knobs.items():
+        nfp.tune(k, v)
+    try:
+        for M in (24, 300, 777):
+            X = workloads.act_host(M, 1040, seed=M)
+            run_both_modes(nfp, X, W, "%s M=%d" % (knobs, M))
+    finally:
+        for k in knobs:
+            nfp.tune(k, -1)
+
+
+def test_one_hot_tokens_return_weights_exactly(nfp):
+    # FP16 mode with one-hot rows returns the reconstructed weights themselves: checks the
+    # operand layout, the transposition and Alg. 1 bit-exactly inside the GEMM kernels
+    N, K = 200, 192
+    W = workloads.weight_host(N, K, seed=77)
+    X = np.zeros((K, K), np.float16)
+    X[np.arange(K), np.arange(K)] = 1.0
+    Wd = to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    for M in (16, 64, K):                      # streaming and tiled kernels
+        y = nfp.gemm(to_dev(X[:M]), up, lo, nfp.MODE_FP16)
+        assert np.array_equal(bits(y), np.ascontiguousarray(W[:, :M].T).view(np.uint16)), M
+    # FP8 mode: 448 on the diagonal gives scale 1; output = e4m3(upper) * 448 * 2^-8, exact in fp16
+    X8 = (X * np.float16(448.0)).astype(np.float16)
+    up_ref, _, _ = oracle.decompose(W)
+    dec = torch.from_numpy(up_ref).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    want = (dec.T * 448.0 * 2.0 ** -8).astype(np.float16)
+    for M in (16, 64, K):
+        y = nfp.gemm(to_dev(X8[:M]), up, None, nfp.MODE_FP8)
+        assert np.array_equal(bits(y), want[:M].view(np.uint16)), M
+
+
+def test_fp8_mode_never_reads_the_lower_plane(nfp):
+    W = workloads.weight_host(256, 512, seed=5)
+    Wd = to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    for M in (8, 200):
+        X = to_dev(workloads.act_host(M, 512, seed=6))
+        a = nfp.gemm(X, up, None, nfp.MODE_FP8)
+        b = nfp.gemm(X, up, torch.full_like(lo, 0xAB), nfp.MODE_FP8)
+        assert np.array_equal(bits(a), bits(b))
+    with pytest.raises(nfp.NestedFPError):
+        nfp.gemm(X, up, None, nfp.MODE_FP16)
+
+
+def test_static_activation_scale_and_prequantized_entry(nfp):
+    W = workloads.weight_host(96, 256, seed=8)
+    X = workloads.act_host(12, 256, seed=8)
+    Wd, Xd = to_dev(W), to_dev(X)
+    up, lo = nfp.decompose(Wd)
+    up_ref, _, _ = oracle.decompose(W)
+    sc = torch.tensor([0.03125], dtype=torch.float32, device="cuda:0")
+    y = nfp.gemm(Xd, up, None, nfp.MODE_FP8, act_scale=sc)
+    Xq, s = oracle.quantize_act(X, static_scale=0.03125)
+    assert_gemm_close(y.cpu().numpy(), oracle.gemm_fp8(Xq, s, up_ref), "static scale")
+    Xq_d, s_d = nfp.quantize_act(Xd)
+    y2 = nfp.gemm_fp8_prequantized(Xq_d, s_d, up)
+    y3 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
+    assert np.array_equal(bits(y2), bits(y3))
+
+
+def test_strided_activations_and_output(nfp):
+    N, K, M = 144, 320, 20
+    W = workloads.weight_host(N, K, seed=3)
+    Xbig = workloads.act_host(M, K + 64, seed=3)
+    Wd = to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    Xd = to_dev(Xbig)[:, :K]
+    out = torch.full((M, N + 16), 7.0, dtype=torch.float16, device="cuda:0")
+    nfp.gemm(Xd, up, lo, nfp.MODE_FP16, out=out[:, :N])
+    ref = oracle.gemm_fp16(Xbig[:, :K], W)
+    got = out.cpu().numpy()
+    assert_gemm_close(got[:, :N], ref, "strided")
+    assert np.all(got[:, N:] == np.float16(7.0))
+
+
+def test_results_are_deterministic(nfp):
+    W = workloads.weight_host(1024, 4096, seed=4)
+    Wd = to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    for M in (16, 384):
+        X = to_dev(workloads.act_host(M, 4096, seed=4))
+        for mode in (nfp.MODE_FP16, nfp.MODE_FP8):
+            a = bits(nfp.gemm(X, up, lo, mode))
+            b = bits(nfp.gemm(X, up, lo, mode))
+            assert np.array_equal(a, b)
+
+
+def test_mode_switch_keeps_planes_and_memory(nfp):
+    # per-step mode switching: same plane pointers, no allocation growth, planes unchanged
+    layers = []
+    for i in range(4):
+        W = to_dev(workloads.weight_host(512, 1024, seed=40 + i))
+        layers.append(nfp.decompose(W))
+        del W
+    X = to_dev(workloads.act_host(64, 1024, seed=50))
+    out = torch.empty((64, 512), dtype=torch.float16, device="cuda:0")
+    ws = torch.empty(max(nfp.gemm_workspace_size(64, 512, 1024, m) for m in (0, 1)), dtype=torch.uint8,
+                     device="cuda:0")
+    snap = [(u.clone(), l.clone()) for u, l in layers]
+    ptrs = [(u.data_ptr(), l.data_ptr()) for u, l in layers]
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    for step in range(32):
+        mode = nfp.MODE_FP8 if (step // 8) % 2 else nfp.MODE_FP16
+        for u, l in layers:
+            nfp.gemm(X, u, None if mode == nfp.MODE_FP8 else l, mode, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    assert ptrs == [(u.data_ptr(), l.data_ptr()) for u, l in layers]
+    for (u, l), (su, sl) in zip(layers, snap):
+        assert torch.equal(u, su) and torch.equal(l, sl)
+
+
+@pytest.mark.parametrize("name,M", [("qkv", 16), ("down", 4), ("o", 64), ("gate_up", 1)])
+def test_llama8b_decode_shapes_full_output(nfp, name, M):
+    N, K = workloads.LLAMA3_8B[name]
+    W = workloads.weight_host(N, K, seed=N % 97)
+    X = workloads.act_host(M, K, seed=M)
+    run_both_modes(nfp, X, W, "%s M=%d" % (name, M), check_plain=(name != "gate_up"))
+
+
+@pytest.mark.parametrize("name,M", [("qkv", 2048), ("down", 512), ("gate_up", 8192)])
+def test_llama8b_prefill_shapes_sampled(nfp, name, M):
+    # full-size launch as bench.py times it; oracle evaluated on a seeded sample of outputs
+    N, K = workloads.LLAMA3_8B[name]
+    Wd = workloads.weight_device(N, K, seed=11)
+    Xd = workloads.act_device(M, K, seed=12)
+    up, lo = nfp.decompose(Wd)
+    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+    yp = nfp.plain_gemm_fp16(Xd, Wd)
+    assert torch.equal(y16, yp)
+    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
+    rows, cols = workloads.sample_indices(M, N, 24, 96, seed=M)
+    Xs = Xd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    Ws = Wd[torch.from_numpy(cols).cuda()].cpu().numpy()
+    ref16 = oracle.gemm_fp16(Xs, Ws)
+    got16 = y16[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert_gemm_close(got16, ref16, "%s M=%d FP16 sample" % (name, M))
+    up_s, _, bad = oracle.decompose(Ws)
+    assert bad == 0
+    assert np.array_equal(up[torch.from_numpy(cols).cuda()].cpu().numpy(), up_s)
+    Xq, s = oracle.quantize_act(Xs)
+    ref8 = oracle.gemm_fp8(Xq, s, up_s)
+    got8 = y8[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert_gemm_close(got8, ref8, "%s M=%d FP8 sample" % (name, M))

@@ -1,0 +1,73 @@
+"""GPU parity: per-token E4M3 activation quantisation is bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_02024_amd import workloads
+from helpers import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nfp():
+    from paper_2506_02024_amd import binding
+
+    return binding
+
+
+@pytest.mark.parametrize("hw", [1, 0])
+@pytest.mark.parametrize("M,K", [(16, 1024), (1, 16), (7, 4112), (64, 14336)])
+def test_gaussian_rows(nfp, hw, M, K):
+    X = workloads.act_host(M, K, seed=M)
+    if M > 2:
+        X[1] = 0                                   # all-zero row: scale 1, codes 0
+        X[2, 3] = np.float16(65504.0)              # largest finite half as row maximum
+    nfp.tune("quant_hw", hw)
+    try:
+        Xq, s = nfp.quantize_act(to_dev(X))
+        Xq, s = Xq.cpu().numpy(), s.cpu().numpy()
+    finally:
+        nfp.tune("quant_hw", -1)
+    Xq_ref, s_ref = oracle.quantize_act(X)
+    assert np.array_equal(s, s_ref)
+    assert np.array_equal(Xq, Xq_ref)
+
+
+@pytest.mark.parametrize("hw", [1, 0])
+def test_every_finite_half_under_several_row_scales(nfp, hw):
+    # each row holds every finite FP16 word whose magnitude does not exceed the row's maximum;
+    # row maxima chosen to hit ties, E4M3 subnormals and saturation at the top
+    words = workloads.all_fp16_words()
+    vals = words.view(np.float16)
+    finite = np.isfinite(vals.astype(np.float32))
+    rows = []
+    for amax in (65504.0, 448.0, 1.0, 0.3337, 7.0, 2.0 ** -10, 6.1e-5, 240.0):
+        a16 = np.float16(amax)
+        keep = finite & (np.abs(vals.astype(np.float32)) <= np.float32(a16))
+        row = np.full(65536, a16, dtype=np.float16)
+        row[: keep.sum()] = vals[keep]
+        rows.append(row)
+    X = np.stack(rows)
+    nfp.tune("quant_hw", hw)
+    try:
+        Xq, s = nfp.quantize_act(to_dev(X))
+        Xq, s = Xq.cpu().numpy(), s.cpu().numpy()
+    finally:
+        nfp.tune("quant_hw", -1)
+    Xq_ref, s_ref = oracle.quantize_act(X)
+    assert np.array_equal(s, s_ref)
+    mism = np.nonzero(Xq != Xq_ref)
+    assert mism[0].size == 0, "first mismatch row %d col %d: x=%r got %#x want %#x" % (
+        mism[0][0], mism[1][0], X[mism[0][0], mism[1][0]], Xq[mism[0][0], mism[1][0]],
+        Xq_ref[mism[0][0], mism[1][0]])
+
+
+def test_static_per_tensor_scale(nfp):
+    X = workloads.act_host(5, 256, seed=3)
+    sc = torch.tensor([0.0625], dtype=torch.float32, device="cuda:0")
+    Xq, s = nfp.quantize_act(to_dev(X), static_scale=sc)
+    Xq_ref, s_ref = oracle.quantize_act(X, static_scale=0.0625)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    assert np.array_equal(Xq.cpu().numpy(), Xq_ref)
