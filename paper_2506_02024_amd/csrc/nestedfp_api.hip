@@ -137,33 +137,34 @@ int nestedfp_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, u
 int nestedfp_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *upper,
                        uint8_t *lower, uint64_t *out_of_range, uint64_t *out_of_range_host,
                        void *stream) {
-    if (upper == nullptr || lower == nullptr) return NESTEDFP_ERR_ARG;
     if (out_of_range_host != nullptr && out_of_range == nullptr) return NESTEDFP_ERR_ARG;
     int st = check_dims(0, N, K);
     if (st != kOk) return st;
+    if (N == 0) {                                     // empty layer: nothing to read or write
+        hipStream_t s0 = static_cast<hipStream_t>(stream);
+        if (out_of_range && launch_zero_u64(out_of_range, s0) != kOk) return NESTEDFP_ERR_HIP;
+        return finish_count(out_of_range, out_of_range_host, s0);
+    }
+    if (upper == nullptr || lower == nullptr) return NESTEDFP_ERR_ARG;
     st = check_mat(W, N, K, ldw, 8);
     if (st != kOk) return st;
     if (!aligned(upper, 16) || !aligned(lower, 16)) return NESTEDFP_ERR_SHAPE;
     if (out_of_range && !aligned(out_of_range, 8)) return NESTEDFP_ERR_SHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (N > 0) {
-        st = launch_decompose(W, N, K, ldw, upper, lower, out_of_range, s);
-        if (st != kOk) return st;
-    } else if (out_of_range) {
-        if (hipMemsetAsync(out_of_range, 0, 8, s) != hipSuccess) return NESTEDFP_ERR_HIP;
-    }
+    st = launch_decompose(W, N, K, ldw, upper, lower, out_of_range, s);
+    if (st != kOk) return st;
     return finish_count(out_of_range, out_of_range_host, s);
 }
 
 int nestedfp_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K, uint16_t *W,
                          int64_t ldw, void *stream) {
-    if (upper == nullptr || lower == nullptr) return NESTEDFP_ERR_ARG;
     int st = check_dims(0, N, K);
     if (st != kOk) return st;
+    if (N == 0) return NESTEDFP_OK;
+    if (upper == nullptr || lower == nullptr) return NESTEDFP_ERR_ARG;
     st = check_mat(W, N, K, ldw, 8);
     if (st != kOk) return st;
     if (!aligned(upper, 16) || !aligned(lower, 16)) return NESTEDFP_ERR_SHAPE;
-    if (N == 0) return NESTEDFP_OK;
     return launch_reconstruct(upper, lower, N, K, W, ldw, static_cast<hipStream_t>(stream));
 }
 

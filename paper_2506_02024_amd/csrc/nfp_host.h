@@ -47,6 +47,7 @@ int launch_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8
                      uint8_t *lower, uint64_t *counter, hipStream_t stream);
 int launch_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint64_t *counter,
                        hipStream_t stream);
+int launch_zero_u64(uint64_t *p, hipStream_t stream);
 int launch_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
                        uint16_t *W, int64_t ldw, hipStream_t stream);
 int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,

@@ -93,6 +93,11 @@ reconstruct_kernel(const uint8_t *__restrict__ upper, const uint8_t *__restrict_
 
 __global__ void zero_u64_kernel(uint64_t *p) { *p = 0; }
 
+int launch_zero_u64(uint64_t *p, hipStream_t stream) {
+    zero_u64_kernel<<<1, 1, 0, stream>>>(p);
+    return hip_ok(hipGetLastError());
+}
+
 static int plane_grid(int64_t total_chunks) {
     // one chunk per lane for small tensors; up to four per lane (grid-stride) for large ones
     int64_t blocks = (total_chunks + kPlaneThreads - 1) / kPlaneThreads;
