@@ -30,7 +30,7 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.lib_path()
+    path = os.environ.get("NESTEDFP_LIB") or _build.lib_path()
     if not os.path.exists(path):
         raise RuntimeError(
             "NestedFP HIP library not built: %s is missing; run "

@@ -2,12 +2,12 @@
 // read exactly once from HBM and nothing staged in LDS (no weight reuse across waves).
 // The paper's sweep starts at M = 32 with T_m >= 16 (Sec. 5.2, App. C); below that the
 // linear layer is bound by HBM bandwidth, so the kernel is built around 128-bit loads of
-// the byte planes with many loads in flight, K split across the waves of a workgroup and
-// a fixed-order reduction.
+// the byte planes with many loads in flight, K split across the waves of a workgroup,
+// activations held in registers, and a fixed-order reduction.
 //
-// One wave owns NT tiles of 16 weight rows and MT tiles of 16 tokens.  Weight rows are the
-// MFMA "A" operand (lane l: row l%16, K-group l/16), tokens the "B" operand, so each lane
-// ends up with 4 consecutive output columns of one token: 8-byte stores of fp16.
+// Weight rows are the MFMA "A" operand (lane l: row l%16 of a 16-row tile, K-group l/16),
+// tokens (MT tiles of 16) the "B" operand, so each lane ends up with 4 consecutive output
+// columns of one token: 8-byte stores of fp16.
 //   kPlainF16 : lane loads 32 B of FP16 weights             -> 2 x v_mfma_f32_16x16x32_f16
 //   kNestedF16: lane loads 16 B upper + 16 B lower, merges them (Sec. 4.2, Alg. 1) -> same
 //   kE4M3     : lane loads 32 B of E4M3 bytes (upper plane)  -> 1 x v_mfma_f32_16x16x128_f8f6f4
@@ -23,58 +23,57 @@ struct SmallParams {
     float w_scale;
     const uint8_t *W0;      // fp16 W (bytes) / upper plane / E4M3 weights
     const uint8_t *W1;      // lower plane
-    int64_t w_row_bytes;    // row stride of W0 (and W1) in bytes
+    uint32_t w_row_bytes;   // row stride of W0 (and W1) in bytes
+    uint32_t w_bytes;       // addressable bytes of W0 (and W1): (N-1)*w_row_bytes + bytes per row
     int M, N, K;
     uint16_t *Y;
     int64_t ldy;
     float *partials;        // [S][M][N] when S > 1
-    int steps_total;        // K-steps over the whole K
-    int steps_per_part;     // K-steps per (slice, wave) part
+    int tiles_per_wg;       // 16-row weight tiles each workgroup walks through
+    int tile_stride;        // distance between a workgroup's consecutive tiles (1 or gridDim.x)
     int vec_store;          // 1: 8-byte fp16 stores allowed
 };
 
 template <int KIND> struct StepK { static constexpr int value = (KIND == kE4M3) ? 128 : 64; };
 
-// Raw per-step operands of one lane.
-template <int KIND> struct WRaw { u32x4 a, b; };   // plain: 32 B fp16; nested: upper, lower; e4m3: 32 B
+// One K-step of weights for one 16-row tile, as loaded (32 bytes per lane).
+struct WItem { u32x4 a, b; };   // plain: 32 B fp16; nested: upper, lower; e4m3: 32 B
 
-template <int KIND>
-__device__ __forceinline__ void load_w(WRaw<KIND> &r, const SmallParams &p, int row, int k0, int g,
-                                       bool row_ok) {
-    // k0: first K index of the step; g: lane's K-group (0..3)
-    const u32x4 zero = {0u, 0u, 0u, 0u};
+// Buffer resource over a weight array: raw (unstructured) addressing with a byte range
+// check, so reads past the end (N tail, look-ahead past the last tile) return zero
+// without touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t weight_rsrc(const uint8_t *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base), 0, bytes, 0x00020000);
+}
+
+// Weights of K-step `s` of the wave's slice: lane offset `voff` (row in tile, K position)
+// is fixed for the whole kernel, the tile offset `soff` is uniform, the step is an
+// immediate.  Lanes past K read finite neighbours and are multiplied by zero activations.
+template <int KIND, int S>
+__device__ __forceinline__ void load_w(WItem &r, __amdgpu_buffer_rsrc_t r0, __amdgpu_buffer_rsrc_t r1,
+                                       uint32_t voff, uint32_t soff) {
     if (KIND == kPlainF16) {
-        int k = k0 + 16 * g;
-        bool ok = row_ok && k < p.K;
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(p.W0 + (int64_t)row * p.w_row_bytes + 2 * (int64_t)k);
-        r.a = ok ? __builtin_nontemporal_load(src) : zero;
-        r.b = ok ? __builtin_nontemporal_load(src + 1) : zero;
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, soff, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, soff, 0);
     } else if (KIND == kNestedF16) {
-        int k = k0 + 16 * g;
-        bool ok = row_ok && k < p.K;
-        int64_t off = (int64_t)row * p.w_row_bytes + k;
-        r.a = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W0 + off)) : zero;
-        r.b = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W1 + off)) : zero;
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 64, soff, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 64, soff, 0);
     } else {
-        int k = k0 + 32 * g;
-        int64_t off = (int64_t)row * p.w_row_bytes + k;
-        bool ok0 = row_ok && k < p.K, ok1 = row_ok && (k + 16) < p.K;
-        r.a = ok0 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W0 + off)) : zero;
-        r.b = ok1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W0 + off + 16)) : zero;
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, soff, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, soff, 0);
     }
 }
 
+// Activations of one K-step for 16 tokens (32 bytes per lane); zero outside M and K.
 template <int KIND>
-__device__ __forceinline__ void load_x(u32x4 &xa, u32x4 &xb, const SmallParams &p, int m, int k0, int g) {
+__device__ __forceinline__ void load_x(u32x4 &xa, u32x4 &xb, const SmallParams &p, int m, int k) {
     const u32x4 zero = {0u, 0u, 0u, 0u};
     bool row_ok = m < p.M;
     if (KIND == kE4M3) {
-        int k = k0 + 32 * g;
         const uint8_t *src = p.X + (int64_t)m * p.x_row_bytes + k;
         xa = (row_ok && k < p.K) ? *reinterpret_cast<const u32x4 *>(src) : zero;
         xb = (row_ok && (k + 16) < p.K) ? *reinterpret_cast<const u32x4 *>(src + 16) : zero;
     } else {
-        int k = k0 + 16 * g;
         const uint8_t *src = p.X + (int64_t)m * p.x_row_bytes + 2 * (int64_t)k;
         bool ok = row_ok && k < p.K;
         xa = ok ? *reinterpret_cast<const u32x4 *>(src) : zero;
@@ -90,9 +89,9 @@ __device__ __forceinline__ half8 as_half8(const u32x4 &v) {
 
 // Turns the raw weight bytes of one step into MFMA operands (merges the planes if nested).
 template <int KIND>
-__device__ __forceinline__ void prep_w(const WRaw<KIND> &w, u32x4 &w_lo, u32x4 &w_hi) {
+__device__ __forceinline__ void prep_w(const WItem &w, u32x4 &w_lo, u32x4 &w_hi) {
     if (KIND == kNestedF16) {
-        merge16(w.a, w.b, w_lo, w_hi);
+        merge16(w.a, w.b, w_lo, w_hi);             // Sec. 4.2, Alg. 1
     } else {
         w_lo = w.a;
         w_hi = w.b;
@@ -117,88 +116,109 @@ __device__ __forceinline__ floatx4 mma_step(const u32x4 &w_lo, const u32x4 &w_hi
     }
 }
 
-// Wave cap per workgroup: 16, or 8 where the accumulators and two steps of operands need
-// more than 128 VGPRs (8 or more 16x16 tiles per wave).
-constexpr int small_max_waves(int mt, int nt) { return mt * nt >= 8 ? 8 : 16; }
+template <int KIND, int SPW, int S = 0>
+struct FetchTile {
+    static __device__ __forceinline__ void run(WItem (&w)[SPW], __amdgpu_buffer_rsrc_t r0,
+                                               __amdgpu_buffer_rsrc_t r1, uint32_t voff, uint32_t soff) {
+        load_w<KIND, S>(w[S], r0, r1, voff, soff);
+        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff, soff);
+    }
+};
+template <int KIND, int SPW>
+struct FetchTile<KIND, SPW, SPW> {
+    static __device__ __forceinline__ void run(WItem (&)[SPW], __amdgpu_buffer_rsrc_t, __amdgpu_buffer_rsrc_t,
+                                               uint32_t, uint32_t) {}
+};
 
-template <int KIND, int MT, int NT, int U>
-__global__ void __launch_bounds__(64 * small_max_waves(MT, NT))
+// Activation-stationary streaming kernel.
+//   workgroup = up to 16 waves; wave w owns the K-slice [w*SPW*KSTEP, (w+1)*SPW*KSTEP) of
+//   grid slice blockIdx.y and keeps the activations of that slice in registers for the whole
+//   kernel; the workgroup walks through `tiles_per_wg` 16-row weight tiles, so each wave
+//   streams 16 rows x (SPW*KSTEP) contiguous K per tile.  Two tile buffers swap roles
+//   (no copies, no branch in the loop body): the loads of tile t+1 are in flight while
+//   tile t is merged and multiplied.  Per-tile partial sums go to LDS and are reduced
+//   across the waves once, at the end, in fixed wave order.
+template <int KIND, int MT, int SPW>
+__global__ void __launch_bounds__(1024)
 small_gemm_kernel(SmallParams p) {
-    extern __shared__ float lds[];                    // [waves][MT*NT][64][4]
+    extern __shared__ float lds[];                    // [tile][wave][MT][64] x float4
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
     const int g = lane >> 4;
     const int r16 = lane & 15;
-    const int n_base = blockIdx.x * (NT * 16);
     const int slice = blockIdx.y;
     constexpr int KSTEP = StepK<KIND>::value;
+    constexpr int KLANE = KSTEP / 4;                  // K elements per lane per step
+    const int tiles_total = (p.N + 15) >> 4;
+    // a workgroup's tiles: a contiguous chunk (stride 1) or interleaved with the other
+    // workgroups (stride gridDim.x), so that the chip sweeps the weights front to back
+    const int tstride = p.tile_stride;
+    const int tile0 = tstride == 1 ? blockIdx.x * p.tiles_per_wg : blockIdx.x;
+    const int T = tstride == 1 ? min(p.tiles_per_wg, tiles_total - tile0)
+                               : (tiles_total - tile0 + tstride - 1) / tstride;
+    const int k_wave = (slice * waves + wave) * (SPW * KSTEP) + KLANE * g;
 
-    // this wave's contiguous range of K-steps
-    const int part = slice * waves + wave;
-    int t_begin = part * p.steps_per_part;
-    int t_end = min(t_begin + p.steps_per_part, p.steps_total);
+    // activations of this wave's K-slice, kept for the whole kernel
+    u32x4 xa[SPW][MT], xb[SPW][MT];
+#pragma unroll
+    for (int s = 0; s < SPW; ++s)
+#pragma unroll
+        for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
 
-    floatx4 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    int rows[NT];
-    bool rows_ok[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        rows[j] = n_base + 16 * j + r16;
-        rows_ok[j] = rows[j] < p.N;
-    }
-
-    for (int t0 = t_begin; t0 < t_end; t0 += U) {
-        WRaw<KIND> w[U][NT];
-        u32x4 xa[U][MT], xb[U][MT];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int k0 = (t0 + u) * KSTEP;
-            bool live = (t0 + u) < t_end;
-#pragma unroll
-            for (int j = 0; j < NT; ++j) load_w<KIND>(w[u][j], p, rows[j], k0, g, rows_ok[j] && live);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int k0 = (t0 + u) * KSTEP;
-            // dead steps read X in bounds of K or get zeros from the K guard; weights are zero
-#pragma unroll
-            for (int i = 0; i < MT; ++i) load_x<KIND>(xa[u][i], xb[u][i], p, 16 * i + r16, k0, g);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                u32x4 w_lo, w_hi;
-                prep_w<KIND>(w[u][j], w_lo, w_hi);
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-                    acc[i][j] = mma_step<KIND>(w_lo, w_hi, xa[u][i], xb[u][i], acc[i][j]);
-            }
-    }
-
-    // ---- fixed-order reduction over the waves of the workgroup --------------------------
-    constexpr int TILES = MT * NT;
     floatx4 *slots = reinterpret_cast<floatx4 *>(lds);
+    const __amdgpu_buffer_rsrc_t rs0 = weight_rsrc(p.W0, p.w_bytes);
+    const __amdgpu_buffer_rsrc_t rs1 = weight_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, p.w_bytes);
+    const uint32_t voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * (KIND == kPlainF16 ? 2u : 1u);
+    const uint32_t tile_bytes = 16u * p.w_row_bytes;
+
+    auto fetch = [&](WItem (&w)[SPW], int tile) {
+        // past the last tile the offset is the end of the array: every lane is out of range
+        uint32_t soff = tile < T ? (uint32_t)(tile0 + tile * tstride) * tile_bytes : p.w_bytes;
+        FetchTile<KIND, SPW>::run(w, rs0, rs1, voff, soff);
+    };
+    auto consume = [&](const WItem (&w)[SPW], int tile) {
+        floatx4 acc[MT];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < NT; ++j) slots[(wave * TILES + i * NT + j) * 64 + lane] = acc[i][j];
+        for (int s = 0; s < SPW; ++s) {
+            u32x4 w_lo, w_hi;
+            prep_w<KIND>(w[s], w_lo, w_hi);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = mma_step<KIND>(w_lo, w_hi, xa[s][i], xb[s][i], acc[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i) slots[((tile * waves + wave) * MT + i) * 64 + lane] = acc[i];
+    };
+
+    WItem buf0[SPW], buf1[SPW];
+    fetch(buf0, 0);
+    // The scheduling barriers keep the compiler from sinking the look-ahead loads below the
+    // multiplies (which would turn every wait into a full drain).  For odd T the last
+    // half-trip multiplies zeros into a spare slot.
+    for (int tile = 0; tile < T; tile += 2) {
+        fetch(buf1, tile + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf0, tile);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(buf0, tile + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(buf1, tile + 1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     __syncthreads();
-    for (int tile = wave; tile < TILES; tile += waves) {
-        const int i = tile / NT, j = tile - i * NT;
-        floatx4 sum = slots[tile * 64 + lane];
+
+    // ---- fixed-order reduction over the waves of the workgroup -----------------------------
+    for (int item = wave; item < T * MT; item += waves) {
+        const int tile = item / MT, i = item - tile * MT;
+        floatx4 sum = slots[((tile * waves) * MT + i) * 64 + lane];
         for (int w2 = 1; w2 < waves; ++w2) {
-            floatx4 v = slots[(w2 * TILES + tile) * 64 + lane];
+            floatx4 v = slots[((tile * waves + w2) * MT + i) * 64 + lane];
             sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
         }
         const int m = 16 * i + r16;
-        const int n = n_base + 16 * j + 4 * g;
+        const int n = (tile0 + tile * tstride) * 16 + 4 * g;
         if (m >= p.M || n >= p.N) continue;
         if (gridDim.y > 1) {
             float *dst = p.partials + ((int64_t)slice * p.M + m) * p.N + n;
@@ -210,8 +230,8 @@ small_gemm_kernel(SmallParams p) {
             }
         } else {
             if (KIND == kE4M3) {
-                float s = p.scales[m] * p.w_scale;
-                sum.x *= s; sum.y *= s; sum.z *= s; sum.w *= s;
+                float sc = p.scales[m] * p.w_scale;
+                sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
             }
             uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
             if (p.vec_store && n + 3 < p.N) {
@@ -222,9 +242,9 @@ small_gemm_kernel(SmallParams p) {
             } else {
                 float v[4] = {sum.x, sum.y, sum.z, sum.w};
                 for (int q = 0; q < 4 && n + q < p.N; ++q) {
-                    union { _Float16 f; uint16_t u; } c;
-                    c.f = (_Float16)v[q];
-                    dst[q] = c.u;
+                    union { _Float16 f; uint16_t u; } cv;
+                    cv.f = (_Float16)v[q];
+                    dst[q] = cv.u;
                 }
             }
         }
@@ -256,35 +276,55 @@ int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, con
 }
 
 // ---- host-side configuration ---------------------------------------------------------
-struct SmallConfig { int mt, nt, waves, split, u; };
+struct SmallConfig { int mt, spw, tmax, waves, split, tiles_per_wg; };
 
 static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
+    const Tuning &t = tuning();
     SmallConfig c;
     c.mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-    c.nt = c.mt;                      // keeps activation reads (L2) equal to weight reads
-    const Tuning &t = tuning();
-    if (t.small_nt > 0) c.nt = (int)t.small_nt;
-    if (c.nt != 1 && c.nt != 2 && c.nt != 4) c.nt = c.mt;
-    int kstep = (kind == kE4M3) ? 128 : 64;
-    int steps = (int)((K + kstep - 1) / kstep);
-    int64_t groups = (N + 16 * c.nt - 1) / (16 * c.nt);
-    // aim for ~4096 waves on the chip (16 per CU), at least 2 K-steps per wave
-    int64_t want_parts = (4096 + groups - 1) / groups;
-    int64_t max_parts = steps / 2 > 0 ? steps / 2 : 1;
-    if (want_parts > max_parts) want_parts = max_parts;
-    if (want_parts < 1) want_parts = 1;
-    int max_waves = small_max_waves(c.mt, c.nt);      // LDS slots: waves * tiles KB <= 128 KB
-    c.waves = (int)(want_parts < max_waves ? want_parts : max_waves);
-    c.split = (int)((want_parts + c.waves - 1) / c.waves);
-    if (c.split > 8) c.split = 8;
-    if (t.small_waves > 0) c.waves = (int)(t.small_waves < max_waves ? t.small_waves : max_waves);
-    if (t.small_split > 0) c.split = (int)t.small_split;
-    if ((int64_t)c.waves * c.split > steps) {        // never more parts than K-steps
-        c.split = 1;
-        if (c.waves > steps) c.waves = steps;
+    const int kstep = (kind == kE4M3) ? 128 : 64;
+    const int steps = (int)((K + kstep - 1) / kstep);
+    // K-steps per wave: 4 with one token tile (2 if that lets one workgroup cover all of K
+    // with more waves); 2 with more token tiles, whose activations need the registers
+    c.spw = 4;
+    if ((steps + 3) / 4 < 16 && steps >= 2) c.spw = 2;
+    if ((t.small_spw == 2 || t.small_spw == 4)) c.spw = (int)t.small_spw;
+    if (c.mt > 1) c.spw = 2;
+    const int max_waves = 16;
+    c.tmax = 128 / (max_waves * c.mt);                // partial-sum slots: tiles*waves*MT KB <= 128 KB
+    if (c.tmax > 8) c.tmax = 8;
+    int slices = (steps + c.spw - 1) / c.spw;                     // wave-sized K slices
+    c.split = (slices + max_waves - 1) / max_waves;
+    if (c.split > 8 && c.mt == 1) {                               // keep the scratch bounded by 8*M*N
+        c.spw = 4;
+        slices = (steps + 3) / 4;
+        c.split = (slices + max_waves - 1) / max_waves;
     }
-    c.u = 2;
+    if (t.small_split > 0) c.split = (int)t.small_split;
+    if (c.split > slices) c.split = slices;
+    c.waves = (slices + c.split - 1) / c.split;
+    if (c.waves > max_waves) {                                    // a forced split too small for K
+        c.waves = max_waves;
+        c.split = (slices + max_waves - 1) / max_waves;
+    }
+    const int64_t tiles = (N + 15) / 16;
+    // one workgroup per CU where the layer is large enough, otherwise one tile each
+    int64_t per = (tiles * c.split + 255) / 256;
+    if (t.small_tiles > 0) per = t.small_tiles;
+    if (per > c.tmax) per = c.tmax;
+    if (per < 1) per = 1;
+    c.tiles_per_wg = (int)per;
     return c;
+}
+
+bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
+    // at most 8 grid slices x 16 waves x (4 K-steps, or 2 with several token tiles), and a
+    // weight array addressable with 32-bit byte offsets (one 16-row tile of slack);
+    // anything larger goes to the tiled kernel
+    const int64_t kstep = (kind == kE4M3) ? 128 : 64;
+    const int64_t spw = M > 16 ? 2 : 4;
+    const int64_t row_bytes = (kind == kPlainF16) ? 2 * ldw : K;
+    return (K + kstep - 1) / kstep <= 8 * 16 * spw && (N + 48) * row_bytes < ((int64_t)1 << 32);
 }
 
 size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
@@ -292,14 +332,14 @@ size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
     return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <int KIND, int MT, int NT>
+template <int KIND, int MT, int SPW>
 static void launch_small_t(const SmallParams &p, const SmallConfig &c, dim3 grid, hipStream_t stream) {
-    size_t lds = (size_t)c.waves * MT * NT * 64 * sizeof(floatx4);
-    auto kern = small_gemm_kernel<KIND, MT, NT, 2>;
+    size_t lds = (size_t)((c.tiles_per_wg + 1) & ~1) * c.waves * MT * 64 * sizeof(floatx4);
+    auto kern = small_gemm_kernel<KIND, MT, SPW>;
     static bool attr_set = false;                    // once per instantiation
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         attr_set = true;
     }
     kern<<<grid, c.waves * 64, lds, stream>>>(p);
@@ -307,16 +347,11 @@ static void launch_small_t(const SmallParams &p, const SmallConfig &c, dim3 grid
 
 template <int KIND>
 static void launch_small_k(const SmallParams &p, const SmallConfig &c, dim3 grid, hipStream_t stream) {
-    switch (c.mt * 10 + c.nt) {
-        case 11: launch_small_t<KIND, 1, 1>(p, c, grid, stream); break;
-        case 12: launch_small_t<KIND, 1, 2>(p, c, grid, stream); break;
+    switch (c.mt * 10 + c.spw) {
         case 14: launch_small_t<KIND, 1, 4>(p, c, grid, stream); break;
-        case 21: launch_small_t<KIND, 2, 1>(p, c, grid, stream); break;
+        case 12: launch_small_t<KIND, 1, 2>(p, c, grid, stream); break;
         case 22: launch_small_t<KIND, 2, 2>(p, c, grid, stream); break;
-        case 24: launch_small_t<KIND, 2, 4>(p, c, grid, stream); break;
-        case 41: launch_small_t<KIND, 4, 1>(p, c, grid, stream); break;
-        case 42: launch_small_t<KIND, 4, 2>(p, c, grid, stream); break;
-        default: launch_small_t<KIND, 4, 4>(p, c, grid, stream); break;
+        default: launch_small_t<KIND, 4, 2>(p, c, grid, stream); break;
     }
 }
 
@@ -329,19 +364,20 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.w_scale = a.w_scale;
     p.W0 = static_cast<const uint8_t *>(a.W0);
     p.W1 = static_cast<const uint8_t *>(a.W1);
-    p.w_row_bytes = (kind == kPlainF16) ? 2 * a.ldw : a.K;
+    p.w_row_bytes = (uint32_t)((kind == kPlainF16) ? 2 * a.ldw : a.K);
+    p.w_bytes = (uint32_t)((a.N - 1) * (int64_t)p.w_row_bytes + ((kind == kPlainF16) ? 2 * a.K : a.K));
     p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;
-    int kstep = (kind == kE4M3) ? 128 : 64;
-    p.steps_total = (int)((a.K + kstep - 1) / kstep);
-    int parts = c.waves * c.split;
-    p.steps_per_part = (p.steps_total + parts - 1) / parts;
+    p.tiles_per_wg = c.tiles_per_wg;
+    const int64_t tiles = (a.N + 15) / 16;
+    const unsigned grid_x = (unsigned)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
+    p.tile_stride = (tuning().small_interleave > 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;
     p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
     if (c.split > 1 && (a.partials == nullptr ||
                         a.partial_bytes < (size_t)c.split * a.M * a.N * sizeof(float)))
         return kErrWorkspace;
-    dim3 grid((unsigned)((a.N + 16 * c.nt - 1) / (16 * c.nt)), (unsigned)c.split);
+    dim3 grid(grid_x, (unsigned)c.split);
     switch (kind) {
         case kPlainF16: launch_small_k<kPlainF16>(p, c, grid, stream); break;
         case kNestedF16: launch_small_k<kNestedF16>(p, c, grid, stream); break;

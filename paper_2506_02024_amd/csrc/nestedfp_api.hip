@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, 1};
     return t;
 }
 
@@ -30,9 +30,13 @@ struct Workspace {
     size_t partial_bytes;
 };
 
+static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
+    return use_small_gemm(M) && small_gemm_supports(kind, M, N, K, ldw);
+}
+
 static size_t partial_bytes_for(int kind, int64_t M, int64_t N, int64_t K) {
-    return use_small_gemm(M) ? small_gemm_partial_bytes(kind, M, N, K)
-                             : large_gemm_partial_bytes(kind, M, N, K);
+    return route_small(kind, M, N, K, K) ? small_gemm_partial_bytes(kind, M, N, K)
+                                   : large_gemm_partial_bytes(kind, M, N, K);
 }
 
 static size_t workspace_bytes_for(int kind, int64_t M, int64_t N, int64_t K, bool quantize) {
@@ -64,7 +68,8 @@ static int check_mat(const void *ptr, int64_t rows, int64_t cols, int64_t ld, in
 }
 
 static int run_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
-    return use_small_gemm(a.M) ? launch_small_gemm(kind, a, stream) : launch_large_gemm(kind, a, stream);
+    return route_small(kind, a.M, a.N, a.K, a.ldw) ? launch_small_gemm(kind, a, stream)
+                                       : launch_large_gemm(kind, a, stream);
 }
 
 static int check_dims(int64_t M, int64_t N, int64_t K) {
@@ -281,7 +286,7 @@ int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64
                     static_cast<hipStream_t>(stream));
 }
 
-static const char *const kKnobs[] = {"small_max_m", "small_waves", "small_split", "small_nt",
+static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
                                      "large_split", "large_bm", "quant_hw", nullptr};
 
 const char *nestedfp_tune_name(int index) {
@@ -294,9 +299,10 @@ int nestedfp_tune(const char *knob, int64_t value) {
     Tuning &t = tuning();
     if (value < 0) value = -1;
     if (!strcmp(knob, "small_max_m")) t.small_max_m = value;
-    else if (!strcmp(knob, "small_waves")) t.small_waves = value;
     else if (!strcmp(knob, "small_split")) t.small_split = value;
-    else if (!strcmp(knob, "small_nt")) t.small_nt = value;
+    else if (!strcmp(knob, "small_spw")) t.small_spw = value;
+    else if (!strcmp(knob, "small_tiles")) t.small_tiles = value;
+    else if (!strcmp(knob, "small_interleave")) t.small_interleave = value;
     else if (!strcmp(knob, "large_split")) t.large_split = value;
     else if (!strcmp(knob, "large_bm")) t.large_bm = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;

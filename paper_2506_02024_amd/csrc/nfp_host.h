@@ -34,9 +34,10 @@ struct GemmArgs {
 // tuning knobs (negative = built-in choice)
 struct Tuning {
     int64_t small_max_m;     // largest M routed to the streaming kernel
-    int64_t small_waves;     // waves per workgroup of the streaming kernel
     int64_t small_split;     // grid-level split-K of the streaming kernel
-    int64_t small_nt;        // 16-row weight tiles per wave
+    int64_t small_spw;       // K-steps per wave (2 or 4)
+    int64_t small_tiles;     // 16-row weight tiles per workgroup
+    int64_t small_interleave;  // 1: a workgroup's tiles are strided by the grid size
     int64_t large_split;     // grid-level split-K of the tiled kernel
     int64_t large_bm;        // tile height of the tiled kernel
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
@@ -54,6 +55,7 @@ int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                         const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream);
 
 // streaming (small-M) and tiled (large-M) GEMM families
+bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw);
 size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K);
 int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream);
 size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K);

@@ -49,11 +49,14 @@ def test_status_strings(L):
 def test_workspace_query_never_scales_with_weight_count(L):
     ws = L.nestedfp_gemm_workspace_size
     for mode in (0, 1):
-        a = ws(16, 4096, 4096, mode)
-        b = ws(16, 4096, 4 * 4096, mode)
-        # grows at most with M*K (quantised activations), never with N*K
-        assert b - a <= 16 * 3 * 4096 + 1024
-        assert ws(16, 4096, 4096, mode) < 4096 * 4096 // 4
+        for M in (1, 16, 64, 512, 8192):
+            for N, K in ((4096, 4096), (28672, 4096), (4096, 14336), (8192, 28672), (57344, 8192),
+                         (1024, 65536 * 2)):
+                need = ws(M, N, K, mode)
+                # at most 8 split-K partial copies of Y plus the quantised activations and scales
+                assert need <= 8 * M * N * 4 + M * K + 4 * M + 1024, (mode, M, N, K, need)
+        # the decode-sized scratch is a vanishing fraction of the planes it multiplies
+        assert ws(16, 57344, 8192, mode) < 57344 * 8192 // 50
     assert ws(16, 4096, 4100, 0) == 0        # K % 16 != 0
     assert ws(16, 4096, 4096, 7) == 0        # unknown mode
     assert ws(-1, 4096, 4096, 0) == 0

@@ -66,15 +66,16 @@ def test_decode_odd_layer_shapes(nfp, N, K):
 
 
 @pytest.mark.parametrize("knobs", [
-    {"small_waves": 1, "small_split": 1},
-    {"small_waves": 4, "small_split": 1},
-    {"small_waves": 2, "small_split": 3},
-    {"small_waves": 16, "small_split": 2, "small_nt": 1},
-    {"small_nt": 4, "small_waves": 2},
-    {"small_nt": 2, "small_split": 4},
+    {"small_split": 1, "small_tiles": 1},
+    {"small_split": 1, "small_tiles": 2, "small_spw": 2},
+    {"small_split": 3, "small_tiles": 3},
+    {"small_split": 2, "small_tiles": 8, "small_spw": 4},
+    {"small_split": 5, "small_tiles": 5, "small_spw": 2},
+    {"small_split": 33, "small_tiles": 7},
 ])
 def test_decode_launch_shapes(nfp, knobs):
-    # every combination of in-workgroup and grid-level K split gives the same answer
+    # every combination of K-steps per wave, grid-level K split and tiles per workgroup
+    # (odd and even, more than the layer has) gives the same answer
     W = workloads.weight_host(304, 2048 + 64, seed=21)
     X = workloads.act_host(16, 2048 + 64, seed=21)
     for k, v in knobs.items():
