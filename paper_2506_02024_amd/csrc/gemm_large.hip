@@ -22,7 +22,7 @@ constexpr int kLargeThreads = 512;
 
 struct LargeParams {
     const uint8_t *X;       // fp16 X (bytes) or E4M3 Xq
-    int64_t x_row_bytes;
+    int64_t x_row_bytes;    // < 2^24 (checked on the host): tile-local offsets fit in 31 bits
     const float *scales;
     float w_scale;
     const uint8_t *W0;
@@ -38,7 +38,19 @@ struct LargeParams {
     int vec_store;
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+// LDS tiles are rows of 128 bytes; the 16-byte chunk index is XOR-ed with (row >> 1) & 7.
+// gfx950 serves ds_read_b128 at 256 B/clk only if 16 consecutive lanes hit 64 distinct
+// 4-byte banks: rows r, r+1 then share a swizzle and fill one 256-byte bank line, and the
+// pairs of 16 consecutive rows take the 8 different swizzles.  The 128-bit writes of the
+// global->LDS copy (8 lanes per row) are conflict-free under the same map.
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint8_t *base, int64_t row0, int rows,
+                                                            int64_t row_bytes, int k_bytes) {
+    // raw buffer over the rows of one tile; anything past the last valid byte reads as zero
+    uint32_t bytes = rows > 0 ? (uint32_t)((rows - 1) * row_bytes + k_bytes) : 0u;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + row0 * row_bytes), 0, bytes, 0x00020000);
+}
 
 template <int KIND, int TM, int TN>
 struct LargeKernel {
@@ -50,47 +62,70 @@ struct LargeKernel {
     static constexpr int WP4 = TN / 128 > 0 ? TN / 128 : 1;   // nested: 4 double-chunks per row
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
     static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int SUBSTEPS = (KIND == kE4M3) ? 2 : 4;
 
     struct Prefetch {
         u32x4 x[XP];
         u32x4 w[KIND == kNestedF16 ? 2 * WP4 : WP8];
     };
 
-    static __device__ __forceinline__ void load_global(Prefetch &pf, const LargeParams &p, int m0,
-                                                       int n0, int kt) {
+    // per-thread byte offsets inside the tile's buffers, fixed for the whole K loop
+    struct Offsets {
+        uint32_t x[XP];
+        uint32_t w[KIND == kNestedF16 ? WP4 : WP8];
+        uint32_t x_lim, w_lim;                          // first K byte past the row, per operand
+        uint32_t x_kpos, w_kpos;                        // this thread's K byte position in a K-tile
+    };
+
+    static __device__ __forceinline__ void make_offsets(Offsets &o, const LargeParams &p) {
         const int t = threadIdx.x;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        const int kb = kt * 128;                       // byte offset along K for 8-chunk operands
         {
             const int c = t & 7, r0 = t >> 3;
-            const bool kok = kb + 16 * c < p.k_bytes;
 #pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                int row = min(m0 + r0 + 64 * i, p.M - 1);
-                const u32x4 *src = reinterpret_cast<const u32x4 *>(p.X + (int64_t)row * p.x_row_bytes + kb + 16 * c);
-                pf.x[i] = kok ? *src : zero;
-            }
+            for (int i = 0; i < XP; ++i) o.x[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.x_row_bytes + 16u * c;
+            o.x_kpos = 16u * c;
+            o.x_lim = (uint32_t)p.k_bytes;
         }
         if (KIND == kNestedF16) {
             const int c4 = t & 3, r0 = t >> 2;
-            const int k = kt * 64 + 16 * c4;           // element (= byte) offset in the planes
-            const bool kok = k < p.K;
 #pragma unroll
-            for (int i = 0; i < WP4; ++i) {
-                int row = min(n0 + r0 + 128 * i, p.N - 1);
-                int64_t off = (int64_t)row * p.w_row_bytes + k;
-                pf.w[2 * i] = kok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W0 + off)) : zero;
-                pf.w[2 * i + 1] = kok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.W1 + off)) : zero;
-            }
+            for (int i = 0; i < WP4; ++i) o.w[i] = (uint32_t)(r0 + 128 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
+            o.w_kpos = 16u * c4;
+            o.w_lim = (uint32_t)p.K;                    // planes: one byte per weight
         } else {
             const int c = t & 7, r0 = t >> 3;
-            const bool kok = kb + 16 * c < p.k_bytes;
 #pragma unroll
-            for (int i = 0; i < WP8; ++i) {
-                int row = min(n0 + r0 + 64 * i, p.N - 1);
-                const u32x4 *src = reinterpret_cast<const u32x4 *>(p.W0 + (int64_t)row * p.w_row_bytes + kb + 16 * c);
-                pf.w[i] = kok ? *src : zero;
+            for (int i = 0; i < WP8; ++i) o.w[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.w_row_bytes + 16u * c;
+            o.w_kpos = 16u * c;
+            o.w_lim = (uint32_t)p.k_bytes;
+        }
+    }
+
+    // Issues the loads of K-tile kt.  Chunks past the end of K are redirected out of the
+    // buffer's range (they read as zero), so no branch and no select on the data.
+    static __device__ __forceinline__ void load_global(Prefetch &pf, const Offsets &o,
+                                                       __amdgpu_buffer_rsrc_t rx, __amdgpu_buffer_rsrc_t rw0,
+                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
+        const uint32_t oob = 0x80000000u;
+        {
+            const uint32_t kb = (uint32_t)kt * 128u;
+            const uint32_t kill = (kb + o.x_kpos < o.x_lim) ? 0u : oob;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) pf.x[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (o.x[i] + kb) | kill, 0, 0);
+        }
+        if (KIND == kNestedF16) {
+            const uint32_t kb = (uint32_t)kt * 64u;
+            const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : oob;
+#pragma unroll
+            for (int i = 0; i < WP4; ++i) {
+                pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
+                pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
             }
+        } else {
+            const uint32_t kb = (uint32_t)kt * 128u;
+            const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : oob;
+#pragma unroll
+            for (int i = 0; i < WP8; ++i) pf.w[i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
         }
     }
 
@@ -126,53 +161,48 @@ struct LargeKernel {
         }
     }
 
-    static __device__ __forceinline__ void compute(const uint8_t *stage, floatx16 (&acc)[FN][FM],
-                                                   int wm, int wn, int lane) {
+    // MFMAs of one K substep (16 halves / 64 E4M3 bytes per row) from one LDS stage
+    static __device__ __forceinline__ void compute_substep(const uint8_t *stage, floatx16 (&acc)[FN][FM],
+                                                           int wm, int wn, int lane, int s) {
         const uint8_t *sW = stage, *sX = stage + TN * 128;
         const int r32 = lane & 31, h = lane >> 5;
         if (KIND == kE4M3) {
+            intx8 a[FN], b[FM];
+            const int c = 4 * s + 2 * h;
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                intx8 a[FN], b[FM];
-                const int c = 4 * s + 2 * h;
-#pragma unroll
-                for (int i = 0; i < FN; ++i) {
-                    int row = wn * WTN + 32 * i + r32;
-                    intx4 lo = *reinterpret_cast<const intx4 *>(sW + swz(row, c));
-                    intx4 hi = *reinterpret_cast<const intx4 *>(sW + swz(row, c + 1));
-                    a[i] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                }
-#pragma unroll
-                for (int j = 0; j < FM; ++j) {
-                    int row = wm * WTM + 32 * j + r32;
-                    intx4 lo = *reinterpret_cast<const intx4 *>(sX + swz(row, c));
-                    intx4 hi = *reinterpret_cast<const intx4 *>(sX + swz(row, c + 1));
-                    b[j] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                }
-#pragma unroll
-                for (int i = 0; i < FN; ++i)
-#pragma unroll
-                    for (int j = 0; j < FM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0,
-                                                                                    0, 0, 0, 0);
+            for (int i = 0; i < FN; ++i) {
+                int row = wn * WTN + 32 * i + r32;
+                intx4 lo = *reinterpret_cast<const intx4 *>(sW + swz(row, c));
+                intx4 hi = *reinterpret_cast<const intx4 *>(sW + swz(row, c + 1));
+                a[i] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
             }
-        } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                half8 a[FN], b[FM];
-                const int c = 2 * s + h;
+            for (int j = 0; j < FM; ++j) {
+                int row = wm * WTM + 32 * j + r32;
+                intx4 lo = *reinterpret_cast<const intx4 *>(sX + swz(row, c));
+                intx4 hi = *reinterpret_cast<const intx4 *>(sX + swz(row, c + 1));
+                b[j] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
 #pragma unroll
-                for (int i = 0; i < FN; ++i)
-                    a[i] = *reinterpret_cast<const half8 *>(sW + swz(wn * WTN + 32 * i + r32, c));
+            for (int i = 0; i < FN; ++i)
 #pragma unroll
                 for (int j = 0; j < FM; ++j)
-                    b[j] = *reinterpret_cast<const half8 *>(sX + swz(wm * WTM + 32 * j + r32, c));
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0,
+                                                                                0, 0);
+        } else {
+            half8 a[FN], b[FM];
+            const int c = 2 * s + h;
 #pragma unroll
-                for (int i = 0; i < FN; ++i)
+            for (int i = 0; i < FN; ++i)
+                a[i] = *reinterpret_cast<const half8 *>(sW + swz(wn * WTN + 32 * i + r32, c));
 #pragma unroll
-                    for (int j = 0; j < FM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-            }
+            for (int j = 0; j < FM; ++j)
+                b[j] = *reinterpret_cast<const half8 *>(sX + swz(wm * WTM + 32 * j + r32, c));
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
     }
 
@@ -195,18 +225,32 @@ struct LargeKernel {
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
+        const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
+        const int w_row_k = (KIND == kNestedF16) ? p.K : p.k_bytes;
+        const __amdgpu_buffer_rsrc_t rw0 = tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
+        const __amdgpu_buffer_rsrc_t rw1 =
+            tile_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
+        Offsets off;
+        make_offsets(off, p);
+
+        // Pipeline: the registers hold K-tile kt+1 while K-tile kt is multiplied out of LDS;
+        // half-way through the MFMAs of kt the registers are written to the other LDS stage
+        // and refilled with the loads of kt+2, so global latency has a whole K-tile to hide in
+        // and the LDS writes overlap with MFMAs of the other wave on the SIMD.
         Prefetch pf;
-        if (kt_begin < kt_end) {
-            load_global(pf, p, m0, n0, kt_begin);
-            store_lds(pf, lds);
-        }
+        load_global(pf, off, rx, rw0, rw1, kt_begin);
+        store_lds(pf, lds);
+        load_global(pf, off, rx, rw0, rw1, kt_begin + 1);       // past kt_end: reads as zero
         __syncthreads();
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             const int cur = (kt - kt_begin) & 1;
-            const bool more = kt + 1 < kt_end;
-            if (more) load_global(pf, p, m0, n0, kt + 1);
-            compute(lds + cur * STAGE, acc, wm, wn, lane);
-            if (more) store_lds(pf, lds + (cur ^ 1) * STAGE);
+            const uint8_t *stage = lds + cur * STAGE;
+#pragma unroll
+            for (int s = 0; s < SUBSTEPS / 2; ++s) compute_substep(stage, acc, wm, wn, lane, s);
+            store_lds(pf, lds + (cur ^ 1) * STAGE);
+            load_global(pf, off, rx, rw0, rw1, kt + 2);
+#pragma unroll
+            for (int s = SUBSTEPS / 2; s < SUBSTEPS; ++s) compute_substep(stage, acc, wm, wn, lane, s);
             __syncthreads();
         }
 

@@ -46,21 +46,22 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t weight_rsrc(const uint8_t *bas
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base), 0, bytes, 0x00020000);
 }
 
-// Weights of K-step `s` of the wave's slice: lane offset `voff` (row in tile, K position)
-// is fixed for the whole kernel, the tile offset `soff` is uniform, the step is an
-// immediate.  Lanes past K read finite neighbours and are multiplied by zero activations.
+// Weights of K-step `s` of the wave's slice: `voff` = lane offset (row in tile, K position,
+// fixed for the whole kernel) + tile offset; the step is an immediate.  The whole offset is
+// in the range-checked VGPR part of the address (the scalar offset is not range-checked).
+// Lanes past K read finite neighbours and are multiplied by zero activations.
 template <int KIND, int S>
 __device__ __forceinline__ void load_w(WItem &r, __amdgpu_buffer_rsrc_t r0, __amdgpu_buffer_rsrc_t r1,
-                                       uint32_t voff, uint32_t soff) {
+                                       uint32_t voff) {
     if (KIND == kPlainF16) {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, soff, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, soff, 0);
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, 0, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, 0, 0);
     } else if (KIND == kNestedF16) {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 64, soff, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 64, soff, 0);
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 64, 0, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 64, 0, 0);
     } else {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, soff, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, soff, 0);
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, 0, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, 0, 0);
     }
 }
 
@@ -119,15 +120,15 @@ __device__ __forceinline__ floatx4 mma_step(const u32x4 &w_lo, const u32x4 &w_hi
 template <int KIND, int SPW, int S = 0>
 struct FetchTile {
     static __device__ __forceinline__ void run(WItem (&w)[SPW], __amdgpu_buffer_rsrc_t r0,
-                                               __amdgpu_buffer_rsrc_t r1, uint32_t voff, uint32_t soff) {
-        load_w<KIND, S>(w[S], r0, r1, voff, soff);
-        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff, soff);
+                                               __amdgpu_buffer_rsrc_t r1, uint32_t voff) {
+        load_w<KIND, S>(w[S], r0, r1, voff);
+        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff);
     }
 };
 template <int KIND, int SPW>
 struct FetchTile<KIND, SPW, SPW> {
     static __device__ __forceinline__ void run(WItem (&)[SPW], __amdgpu_buffer_rsrc_t, __amdgpu_buffer_rsrc_t,
-                                               uint32_t, uint32_t) {}
+                                               uint32_t) {}
 };
 
 // Activation-stationary streaming kernel.
@@ -174,8 +175,8 @@ small_gemm_kernel(SmallParams p) {
 
     auto fetch = [&](WItem (&w)[SPW], int tile) {
         // past the last tile the offset is the end of the array: every lane is out of range
-        uint32_t soff = tile < T ? (uint32_t)(tile0 + tile * tstride) * tile_bytes : p.w_bytes;
-        FetchTile<KIND, SPW>::run(w, rs0, rs1, voff, soff);
+        uint32_t toff = tile < T ? (uint32_t)(tile0 + tile * tstride) * tile_bytes : p.w_bytes;
+        FetchTile<KIND, SPW>::run(w, rs0, rs1, voff + toff);
     };
     auto consume = [&](const WItem (&w)[SPW], int tile) {
         floatx4 acc[MT];
