@@ -52,14 +52,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint8_t *base,
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + row0 * row_bytes), 0, bytes, 0x00020000);
 }
 
-template <int KIND, int TM, int TN>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 struct LargeKernel {
-    static constexpr int WAVES_M = 2, WAVES_N = 4;
+    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
     static constexpr int FM = WTM / 32, FN = WTN / 32;
-    static constexpr int XP = TM / 64;                 // 8-chunk passes for the token tile
-    static constexpr int WP8 = TN / 64;                // 8-chunk passes for the weight tile
-    static constexpr int WP4 = TN / 128 > 0 ? TN / 128 : 1;   // nested: 4 double-chunks per row
+    static constexpr int R8 = THREADS / 8;             // rows per pass, 8 chunks per row
+    static constexpr int R4 = THREADS / 4;             // rows per pass, 4 double-chunks per row
+    static constexpr int XP = TM / R8;                 // 8-chunk passes for the token tile
+    static constexpr int WP8 = TN / R8;                // 8-chunk passes for the weight tile
+    static constexpr int WP4 = TN / R4 > 0 ? TN / R4 : 1;   // nested: 4 double-chunks per row
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
     static constexpr int LDS_BYTES = 2 * STAGE;
     static constexpr int SUBSTEPS = (KIND == kE4M3) ? 2 : 4;
@@ -82,20 +84,20 @@ struct LargeKernel {
         {
             const int c = t & 7, r0 = t >> 3;
 #pragma unroll
-            for (int i = 0; i < XP; ++i) o.x[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.x_row_bytes + 16u * c;
+            for (int i = 0; i < XP; ++i) o.x[i] = (uint32_t)(r0 + R8 * i) * (uint32_t)p.x_row_bytes + 16u * c;
             o.x_kpos = 16u * c;
             o.x_lim = (uint32_t)p.k_bytes;
         }
         if (KIND == kNestedF16) {
             const int c4 = t & 3, r0 = t >> 2;
 #pragma unroll
-            for (int i = 0; i < WP4; ++i) o.w[i] = (uint32_t)(r0 + 128 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
+            for (int i = 0; i < WP4; ++i) o.w[i] = (uint32_t)(r0 + R4 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
             o.w_kpos = 16u * c4;
             o.w_lim = (uint32_t)p.K;                    // planes: one byte per weight
         } else {
             const int c = t & 7, r0 = t >> 3;
 #pragma unroll
-            for (int i = 0; i < WP8; ++i) o.w[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.w_row_bytes + 16u * c;
+            for (int i = 0; i < WP8; ++i) o.w[i] = (uint32_t)(r0 + R8 * i) * (uint32_t)p.w_row_bytes + 16u * c;
             o.w_kpos = 16u * c;
             o.w_lim = (uint32_t)p.k_bytes;
         }
@@ -136,7 +138,7 @@ struct LargeKernel {
             const int c = t & 7, r0 = t >> 3;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                int row = r0 + 64 * i;
+                int row = r0 + R8 * i;
                 *reinterpret_cast<u32x4 *>(sX + swz(row, c)) = pf.x[i];
             }
         }
@@ -144,8 +146,8 @@ struct LargeKernel {
             const int c4 = t & 3, r0 = t >> 2;
 #pragma unroll
             for (int i = 0; i < WP4; ++i) {
-                int row = r0 + 128 * i;
-                if (TN < 128 && row >= TN) continue;
+                int row = r0 + R4 * i;
+                if (TN < R4 && row >= TN) continue;
                 u32x4 w_lo, w_hi;
                 merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);   // Sec. 4.2, Alg. 1
                 *reinterpret_cast<u32x4 *>(sW + swz(row, 2 * c4)) = w_lo;
@@ -155,61 +157,61 @@ struct LargeKernel {
             const int c = t & 7, r0 = t >> 3;
 #pragma unroll
             for (int i = 0; i < WP8; ++i) {
-                int row = r0 + 64 * i;
+                int row = r0 + R8 * i;
                 *reinterpret_cast<u32x4 *>(sW + swz(row, c)) = pf.w[i];
             }
         }
     }
 
-    // MFMAs of one K substep (16 halves / 64 E4M3 bytes per row) from one LDS stage
-    static __device__ __forceinline__ void compute_substep(const uint8_t *stage, floatx16 (&acc)[FN][FM],
-                                                           int wm, int wn, int lane, int s) {
+    // MFMA operand fragments of one K substep (16 halves / 64 E4M3 bytes per row)
+    struct Frags {
+        intx4 a[FN][KIND == kE4M3 ? 2 : 1];
+        intx4 b[FM][KIND == kE4M3 ? 2 : 1];
+    };
+
+    static __device__ __forceinline__ void read_frags(Frags &f, const uint8_t *stage, int wm, int wn,
+                                                      int lane, int s) {
         const uint8_t *sW = stage, *sX = stage + TN * 128;
         const int r32 = lane & 31, h = lane >> 5;
-        if (KIND == kE4M3) {
-            intx8 a[FN], b[FM];
-            const int c = 4 * s + 2 * h;
+        constexpr int NC = KIND == kE4M3 ? 2 : 1;          // 16-byte chunks per lane per substep
+        const int c = NC * (2 * s + h);
 #pragma unroll
-            for (int i = 0; i < FN; ++i) {
-                int row = wn * WTN + 32 * i + r32;
-                intx4 lo = *reinterpret_cast<const intx4 *>(sW + swz(row, c));
-                intx4 hi = *reinterpret_cast<const intx4 *>(sW + swz(row, c + 1));
-                a[i] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            }
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int q = 0; q < NC; ++q)
+                f.a[i][q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + 32 * i + r32, c + q));
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+#pragma unroll
+            for (int q = 0; q < NC; ++q)
+                f.b[j][q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * j + r32, c + q));
+    }
+
+    static __device__ __forceinline__ void mfmas(const Frags &f, floatx16 (&acc)[FN][FM]) {
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
 #pragma unroll
             for (int j = 0; j < FM; ++j) {
-                int row = wm * WTM + 32 * j + r32;
-                intx4 lo = *reinterpret_cast<const intx4 *>(sX + swz(row, c));
-                intx4 hi = *reinterpret_cast<const intx4 *>(sX + swz(row, c + 1));
-                b[j] = intx8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                if (KIND == kE4M3) {
+                    intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w,
+                               f.a[i][NC1].x, f.a[i][NC1].y, f.a[i][NC1].z, f.a[i][NC1].w};
+                    intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w,
+                               f.b[j][NC1].x, f.b[j][NC1].y, f.b[j][NC1].z, f.b[j][NC1].w};
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
+                } else {
+                    union { intx4 v; half8 h; } a, b;
+                    a.v = f.a[i][0];
+                    b.v = f.b[j][0];
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, acc[i][j], 0, 0, 0);
+                }
             }
-#pragma unroll
-            for (int i = 0; i < FN; ++i)
-#pragma unroll
-                for (int j = 0; j < FM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0,
-                                                                                0, 0);
-        } else {
-            half8 a[FN], b[FM];
-            const int c = 2 * s + h;
-#pragma unroll
-            for (int i = 0; i < FN; ++i)
-                a[i] = *reinterpret_cast<const half8 *>(sW + swz(wn * WTN + 32 * i + r32, c));
-#pragma unroll
-            for (int j = 0; j < FM; ++j)
-                b[j] = *reinterpret_cast<const half8 *>(sX + swz(wm * WTM + 32 * j + r32, c));
-#pragma unroll
-            for (int i = 0; i < FN; ++i)
-#pragma unroll
-                for (int j = 0; j < FM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
     }
+    static constexpr int NC1 = KIND == kE4M3 ? 1 : 0;
 
     static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds) {
         const int lane = threadIdx.x & 63;
         const int wave = threadIdx.x >> 6;
-        const int wm = wave & 1, wn = wave >> 1;
+        const int wm = wave % WAVES_M, wn = wave / WAVES_M;
         const int tile = blockIdx.x;
         const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
         const int m0 = tm * TM, n0 = tn * TN;
@@ -242,15 +244,37 @@ struct LargeKernel {
         store_lds(pf, lds);
         load_global(pf, off, rx, rw0, rw1, kt_begin + 1);       // past kt_end: reads as zero
         __syncthreads();
+        constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);   // LDS reads per substep
+        constexpr int MFMAS = FN * FM;
+        Frags fr[2];
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             const int cur = (kt - kt_begin) & 1;
             const uint8_t *stage = lds + cur * STAGE;
+            read_frags(fr[0], stage, wm, wn, lane, 0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int s = 0; s < SUBSTEPS / 2; ++s) compute_substep(stage, acc, wm, wn, lane, s);
-            store_lds(pf, lds + (cur ^ 1) * STAGE);
-            load_global(pf, off, rx, rw0, rw1, kt + 2);
+            for (int s = 0; s < SUBSTEPS; ++s) {
+                const bool mid = (s == SUBSTEPS / 2 - 1);
+                if (s + 1 < SUBSTEPS) read_frags(fr[(s + 1) & 1], stage, wm, wn, lane, s + 1);
+                if (mid) {
+                    store_lds(pf, lds + (cur ^ 1) * STAGE);
+                    load_global(pf, off, rx, rw0, rw1, kt + 2);
+                }
+                mfmas(fr[s & 1], acc);
+                // Scheduling recipe for this region: after each MFMA one LDS read of the next
+                // substep's fragments and, in the middle substep, one LDS write and one global
+                // load; whatever is left (address arithmetic, the plane merge) fills the gaps.
+                constexpr int kWrites = XP + (KIND == kNestedF16 ? 2 * WP4 : WP8);
+                constexpr int kLoads = XP + (KIND == kNestedF16 ? 2 * WP4 : WP8);
 #pragma unroll
-            for (int s = SUBSTEPS / 2; s < SUBSTEPS; ++s) compute_substep(stage, acc, wm, wn, lane, s);
+                for (int q = 0; q < MFMAS; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
+                    if (s + 1 < SUBSTEPS && q < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+                    if (mid && q < kWrites) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
+                    if (mid && q < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    // VMEM read
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             __syncthreads();
         }
 
@@ -298,14 +322,14 @@ struct LargeKernel {
     }
 };
 
-template <int KIND, int TM, int TN>
-__global__ void __launch_bounds__(kLargeThreads)
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 large_gemm_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    LargeKernel<KIND, TM, TN>::run(p, lds_raw);
+    LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::run(p, lds_raw);
 }
 
-struct LargeConfig { int tm, tn, split; };
+struct LargeConfig { int tm, tn, split, waves; };
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -315,6 +339,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     if (t.large_bm == 128 || t.large_bm == 256) c.tm = c.tn = (int)t.large_bm;
     int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
     int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
+    c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
     c.split = 1;
     if (tiles < 256) {                                  // fewer tiles than CUs: split K
         int64_t s = (512 + tiles - 1) / tiles;
@@ -331,23 +356,24 @@ size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
     return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <int KIND, int TM, int TN>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = large_gemm_kernel<KIND, TM, TN>;
-    constexpr int lds = LargeKernel<KIND, TM, TN>::LDS_BYTES;
+    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N>;
+    constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         attr_set = true;
     }
-    kern<<<grid, kLargeThreads, lds, stream>>>(p);
+    kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256) launch_large_t<KIND, 256, 256>(p, grid, stream);
-    else launch_large_t<KIND, 128, 128>(p, grid, stream);
+    if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
+    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
 }
 
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {

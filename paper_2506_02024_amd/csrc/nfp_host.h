@@ -40,6 +40,7 @@ struct Tuning {
     int64_t small_interleave;  // 1: a workgroup's tiles are strided by the grid size
     int64_t large_split;     // grid-level split-K of the tiled kernel
     int64_t large_bm;        // tile height of the tiled kernel
+    int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
 };
 Tuning &tuning();
