@@ -311,6 +311,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const int64_t tiles = (N + 15) / 16;
     // one workgroup per CU where the layer is large enough, otherwise one tile each
     int64_t per = (tiles * c.split + 255) / 256;
+    if (per >= 6) per = 8;        // measured: fewer, longer workgroups win once the layer is large
     if (t.small_tiles > 0) per = t.small_tiles;
     if (per > c.tmax) per = c.tmax;
     if (per < 1) per = 1;
@@ -373,7 +374,7 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.tiles_per_wg = c.tiles_per_wg;
     const int64_t tiles = (a.N + 15) / 16;
     const unsigned grid_x = (unsigned)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
-    p.tile_stride = (tuning().small_interleave > 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;
+    p.tile_stride = (tuning().small_interleave != 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;
     p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
     if (c.split > 1 && (a.partials == nullptr ||
                         a.partial_bytes < (size_t)c.split * a.M * a.N * sizeof(float)))

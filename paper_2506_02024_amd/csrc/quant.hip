@@ -66,9 +66,80 @@ quantize_act_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
     }
 }
 
+// Single-pass variant for rows that fit in registers (K <= 32768): every lane keeps its
+// 16-byte chunks between the maximum and the conversion, so the row is read once and the
+// kernel is one load latency shorter -- what matters for decode-sized batches, where this
+// kernel is pure latency.
+template <int CPT, bool HW>
+__global__ void __launch_bounds__(1024)
+quantize_act_onepass_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
+                            const float *__restrict__ static_scale, uint8_t *__restrict__ Xq,
+                            float *__restrict__ scales) {
+    const int64_t m = blockIdx.x;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + m * ldx);
+    const int chunks = (int)(K / 8);
+    __shared__ uint32_t red[16];
+    u32x4 v[CPT];
+    uint32_t amax_bits = 0;
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        int c = threadIdx.x + i * blockDim.x;
+        v[i] = c < chunks ? row[c] : u32x4{0u, 0u, 0u, 0u};
+        uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) amax_bits = max(amax_bits, max(w[q] & 0x7fffu, (w[q] >> 16) & 0x7fffu));
+    }
+    float s;
+    if (static_scale) {
+        s = *static_scale;
+    } else {
+        for (int off = 32; off > 0; off >>= 1)
+            amax_bits = max(amax_bits, (uint32_t)__shfl_xor((int)amax_bits, off, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax_bits;
+        __syncthreads();
+        uint32_t all = 0;
+        const int waves = blockDim.x >> 6;
+        for (int i = 0; i < waves; ++i) all = max(all, red[i]);
+        float amax = half_bits_to_float(all);
+        s = (amax == 0.0f) ? 1.0f : amax / 448.0f;
+    }
+    if (threadIdx.x == 0) scales[m] = s;
+    u32x2 *out = reinterpret_cast<u32x2 *>(Xq + m * K);
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        int c = threadIdx.x + i * blockDim.x;
+        if (c < chunks) {
+            u32x2 q;
+            q.x = quant4<HW>(v[i].x, v[i].y, s);
+            q.y = quant4<HW>(v[i].z, v[i].w, s);
+            out[c] = q;
+        }
+    }
+}
+
+template <int CPT>
+static void launch_onepass(bool hw, int threads, const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                           const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream) {
+    dim3 grid((unsigned)M);
+    if (hw)
+        quantize_act_onepass_kernel<CPT, true><<<grid, threads, 0, stream>>>(X, K, ldx, static_scale, Xq, scales);
+    else
+        quantize_act_onepass_kernel<CPT, false><<<grid, threads, 0, stream>>>(X, K, ldx, static_scale, Xq, scales);
+}
+
 int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                         const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream) {
     bool hw = tuning().quant_hw != 0;
+    const int64_t chunks = K / 8;
+    if (M <= 256 && chunks <= 4096) {
+        // decode-sized: one pass, as many lanes as the row has chunks (up to 1024, 4 chunks each)
+        int cpt = chunks <= 1024 ? 1 : (chunks <= 2048 ? 2 : 4);
+        int threads = (int)(((chunks + cpt - 1) / cpt + 63) / 64 * 64);
+        if (cpt == 1) launch_onepass<1>(hw, threads, X, M, K, ldx, static_scale, Xq, scales, stream);
+        else if (cpt == 2) launch_onepass<2>(hw, threads, X, M, K, ldx, static_scale, Xq, scales, stream);
+        else launch_onepass<4>(hw, threads, X, M, K, ldx, static_scale, Xq, scales, stream);
+        return hip_ok(hipGetLastError());
+    }
     dim3 grid((unsigned)M);
     if (hw)
         quantize_act_kernel<true><<<grid, kQuantThreads, 0, stream>>>(X, K, ldx, static_scale, Xq, scales);

@@ -18,7 +18,8 @@ def nfp():
 
 
 @pytest.mark.parametrize("hw", [1, 0])
-@pytest.mark.parametrize("M,K", [(16, 1024), (1, 16), (7, 4112), (64, 14336)])
+@pytest.mark.parametrize("M,K", [(16, 1024), (1, 16), (7, 4112), (64, 14336), (3, 20480), (300, 512),
+                                 (2, 32768), (2, 32784)])
 def test_gaussian_rows(nfp, hw, M, K):
     X = workloads.act_host(M, K, seed=M)
     if M > 2:
