@@ -29,6 +29,7 @@ struct SmallParams {
     uint16_t *Y;
     int64_t ldy;
     float *partials;        // [S][M][N] when S > 1
+    int k_passes;           // K slices each wave walks through in turn
     int tiles_per_wg;       // 16-row weight tiles each workgroup walks through
     int tile_stride;        // distance between a workgroup's consecutive tiles (1 or gridDim.x)
     int vec_store;          // 1: 8-byte fp16 stores allowed
@@ -139,8 +140,8 @@ struct FetchTile<KIND, SPW, SPW> {
 //   (no copies, no branch in the loop body): the loads of tile t+1 are in flight while
 //   tile t is merged and multiplied.  Per-tile partial sums go to LDS and are reduced
 //   across the waves once, at the end, in fixed wave order.
-template <int KIND, int MT, int SPW>
-__global__ void __launch_bounds__(1024)
+template <int KIND, int MT, int SPW, bool MULTIPASS>
+__global__ void __launch_bounds__(MT == 4 ? 512 : 1024)
 small_gemm_kernel(SmallParams p) {
     extern __shared__ float lds[];                    // [tile][wave][MT][64] x float4
     const int lane = threadIdx.x & 63;
@@ -158,20 +159,24 @@ small_gemm_kernel(SmallParams p) {
     const int tile0 = tstride == 1 ? blockIdx.x * p.tiles_per_wg : blockIdx.x;
     const int T = tstride == 1 ? min(p.tiles_per_wg, tiles_total - tile0)
                                : (tiles_total - tile0 + tstride - 1) / tstride;
-    const int k_wave = (slice * waves + wave) * (SPW * KSTEP) + KLANE * g;
-
-    // activations of this wave's K-slice, kept for the whole kernel
-    u32x4 xa[SPW][MT], xb[SPW][MT];
-#pragma unroll
-    for (int s = 0; s < SPW; ++s)
-#pragma unroll
-        for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
-
     floatx4 *slots = reinterpret_cast<floatx4 *>(lds);
     const __amdgpu_buffer_rsrc_t rs0 = weight_rsrc(p.W0, p.w_bytes);
     const __amdgpu_buffer_rsrc_t rs1 = weight_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, p.w_bytes);
-    const uint32_t voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * (KIND == kPlainF16 ? 2u : 1u);
     const uint32_t tile_bytes = 16u * p.w_row_bytes;
+
+    // with several K passes this wave's partial tiles live in LDS and start at zero
+    // (the spare slot of an odd T included)
+    if (MULTIPASS)
+        for (int tile = 0; tile < ((T + 1) & ~1); ++tile)
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                slots[((tile * waves + wave) * MT + i) * 64 + lane] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // Long rows take several passes: in pass q the wave owns K-slice (slice*passes + q)*waves
+    // + wave, reloads the activations of that slice and walks the same tiles again, adding
+    // to its partial tiles in LDS.
+    u32x4 xa[SPW][MT], xb[SPW][MT];
+    uint32_t voff = 0;
 
     auto fetch = [&](WItem (&w)[SPW], int tile) {
         // past the last tile the offset is the end of the array: every lane is out of range
@@ -181,7 +186,8 @@ small_gemm_kernel(SmallParams p) {
     auto consume = [&](const WItem (&w)[SPW], int tile) {
         floatx4 acc[MT];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < MT; ++i)
+            acc[i] = MULTIPASS ? slots[((tile * waves + wave) * MT + i) * 64 + lane] : floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
             u32x4 w_lo, w_hi;
@@ -194,19 +200,28 @@ small_gemm_kernel(SmallParams p) {
     };
 
     WItem buf0[SPW], buf1[SPW];
-    fetch(buf0, 0);
-    // The scheduling barriers keep the compiler from sinking the look-ahead loads below the
-    // multiplies (which would turn every wait into a full drain).  For odd T the last
-    // half-trip multiplies zeros into a spare slot.
-    for (int tile = 0; tile < T; tile += 2) {
-        fetch(buf1, tile + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf0, tile);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(buf0, tile + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        consume(buf1, tile + 1);
-        __builtin_amdgcn_sched_barrier(0);
+    const int passes = MULTIPASS ? p.k_passes : 1;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int k_wave = ((slice * passes + pass) * waves + wave) * (SPW * KSTEP) + KLANE * g;
+#pragma unroll
+        for (int s = 0; s < SPW; ++s)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
+        voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * (KIND == kPlainF16 ? 2u : 1u);
+        fetch(buf0, 0);
+        // The scheduling barriers keep the compiler from sinking the look-ahead loads below the
+        // multiplies (which would turn every wait into a full drain).  For odd T the last
+        // half-trip multiplies zeros into a spare slot.
+        for (int tile = 0; tile < T; tile += 2) {
+            fetch(buf1, tile + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(buf0, tile);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(buf0, tile + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(buf1, tile + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     __syncthreads();
 
@@ -277,7 +292,7 @@ int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, con
 }
 
 // ---- host-side configuration ---------------------------------------------------------
-struct SmallConfig { int mt, spw, tmax, waves, split, tiles_per_wg; };
+struct SmallConfig { int mt, spw, waves, split, passes, tiles_per_wg; };
 
 static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const Tuning &t = tuning();
@@ -285,48 +300,51 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     c.mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
     const int kstep = (kind == kE4M3) ? 128 : 64;
     const int steps = (int)((K + kstep - 1) / kstep);
-    // K-steps per wave: 4 with one token tile (2 if that lets one workgroup cover all of K
-    // with more waves); 2 with more token tiles, whose activations need the registers
+    const int max_waves = c.mt == 4 ? 8 : 16;     // four token tiles need 256 VGPRs per wave
+    const int64_t tiles = (N + 15) / 16;
+    // K-steps per wave: 2 with several token tiles (their activations need the registers) and
+    // for large layers (measured: two passes of short slices beat one pass of long ones);
+    // otherwise 4, or 2 if that still lets one workgroup cover all of K
     c.spw = 4;
     if ((steps + 3) / 4 < 16 && steps >= 2) c.spw = 2;
+    if (tiles >= 1024) c.spw = 2;
     if ((t.small_spw == 2 || t.small_spw == 4)) c.spw = (int)t.small_spw;
     if (c.mt > 1) c.spw = 2;
-    const int max_waves = 16;
-    c.tmax = 128 / (max_waves * c.mt);                // partial-sum slots: tiles*waves*MT KB <= 128 KB
-    if (c.tmax > 8) c.tmax = 8;
-    int slices = (steps + c.spw - 1) / c.spw;                     // wave-sized K slices
-    c.split = (slices + max_waves - 1) / max_waves;
-    if (c.split > 8 && c.mt == 1) {                               // keep the scratch bounded by 8*M*N
-        c.spw = 4;
-        slices = (steps + 3) / 4;
-        c.split = (slices + max_waves - 1) / max_waves;
-    }
-    if (t.small_split > 0) c.split = (int)t.small_split;
-    if (c.split > slices) c.split = slices;
-    c.waves = (slices + c.split - 1) / c.split;
-    if (c.waves > max_waves) {                                    // a forced split too small for K
+    const int slices = (steps + c.spw - 1) / c.spw;               // wave-sized K slices
+    // Grid-level split of K (fp32 partials + a second kernel): small layers run faster as
+    // about a thousand short workgroups than as a few hundred wide ones, so K is split by
+    // the largest power of two that keeps tiles*split <= 1024 (at most 8: the scratch stays
+    // below 8*M*N floats).  What 16 waves x split do not cover is walked in passes.
+    const int rounds = (slices + max_waves - 1) / max_waves;
+    // E4M3 layers move half the bytes: half as many workgroups, unless K needs passes anyway
+    const int64_t wg_target = (kind == kE4M3 && rounds == 1) ? 512 : 1024;
+    int split = 1;
+    while (split < 8 && tiles * (split * 2) <= wg_target) split *= 2;
+    if (t.small_split > 0) split = (int)t.small_split;
+    if (split > slices) split = slices;
+    c.split = split;
+    c.passes = (rounds + split - 1) / split;
+    c.waves = (slices + split * c.passes - 1) / (split * c.passes);
+    if (c.waves > max_waves) {                                    // cannot happen; keep the launch legal
         c.waves = max_waves;
-        c.split = (slices + max_waves - 1) / max_waves;
+        c.passes = (slices + split * max_waves - 1) / (split * max_waves);
     }
-    const int64_t tiles = (N + 15) / 16;
     // one workgroup per CU where the layer is large enough, otherwise one tile each
     int64_t per = (tiles * c.split + 255) / 256;
     if (per >= 6) per = 8;        // measured: fewer, longer workgroups win once the layer is large
     if (t.small_tiles > 0) per = t.small_tiles;
-    if (per > c.tmax) per = c.tmax;
+    const int tmax = 128 / (max_waves * c.mt) > 8 ? 8 : 128 / (max_waves * c.mt);   // LDS slots <= 128 KB
+    if (per > tmax) per = tmax;
     if (per < 1) per = 1;
     c.tiles_per_wg = (int)per;
     return c;
 }
 
 bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
-    // at most 8 grid slices x 16 waves x (4 K-steps, or 2 with several token tiles), and a
-    // weight array addressable with 32-bit byte offsets (one 16-row tile of slack);
-    // anything larger goes to the tiled kernel
-    const int64_t kstep = (kind == kE4M3) ? 128 : 64;
-    const int64_t spw = M > 16 ? 2 : 4;
+    // the weight array must be addressable with 32-bit byte offsets (a few tiles of slack)
+    (void)M;
     const int64_t row_bytes = (kind == kPlainF16) ? 2 * ldw : K;
-    return (K + kstep - 1) / kstep <= 8 * 16 * spw && (N + 48) * row_bytes < ((int64_t)1 << 32);
+    return (N + 48) * row_bytes < ((int64_t)1 << 32);
 }
 
 size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
@@ -337,14 +355,18 @@ size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
 template <int KIND, int MT, int SPW>
 static void launch_small_t(const SmallParams &p, const SmallConfig &c, dim3 grid, hipStream_t stream) {
     size_t lds = (size_t)((c.tiles_per_wg + 1) & ~1) * c.waves * MT * 64 * sizeof(floatx4);
-    auto kern = small_gemm_kernel<KIND, MT, SPW>;
+    auto kern1 = small_gemm_kernel<KIND, MT, SPW, false>;
+    auto kernp = small_gemm_kernel<KIND, MT, SPW, true>;
     static bool attr_set = false;                    // once per instantiation
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern1),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernp),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         attr_set = true;
     }
-    kern<<<grid, c.waves * 64, lds, stream>>>(p);
+    if (c.passes > 1) kernp<<<grid, c.waves * 64, lds, stream>>>(p);
+    else kern1<<<grid, c.waves * 64, lds, stream>>>(p);
 }
 
 template <int KIND>
@@ -372,6 +394,7 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;
     p.tiles_per_wg = c.tiles_per_wg;
+    p.k_passes = c.passes;
     const int64_t tiles = (a.N + 15) / 16;
     const unsigned grid_x = (unsigned)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
     p.tile_stride = (tuning().small_interleave != 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;

@@ -58,7 +58,8 @@ def test_decode_sized_batches(nfp, M):
     run_both_modes(nfp, X, W, "M=%d" % M)
 
 
-@pytest.mark.parametrize("N,K", [(4, 16), (16, 16), (20, 32), (1, 4096), (257, 2048), (6, 144)])
+@pytest.mark.parametrize("N,K", [(4, 16), (16, 16), (20, 32), (1, 4096), (257, 2048), (6, 144),
+                                 (48, 8256), (20, 14352), (300, 28672)])
 def test_decode_odd_layer_shapes(nfp, N, K):
     W = workloads.weight_host(N, K, seed=N)
     X = workloads.act_host(4, K, seed=K)
