@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the compute-bound extras")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB elementwise copy (known traffic) so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
     return ap.parse_args()
 
 
@@ -221,7 +224,13 @@ def main():
         "algorithmic_bytes_per_launch": step_bytes["fp16"] / n_calls,
     }
 
-    mem_before = torch.cuda.memory_allocated()
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.float32, device=dev)       # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_prefill:
         del replay, legs
         extra["prefill"] = prefill_extras(torch, nfp, workloads, planes, plain_w, dev)

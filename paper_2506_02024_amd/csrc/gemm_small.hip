@@ -268,26 +268,54 @@ small_gemm_kernel(SmallParams p) {
 }
 
 // Sums the S split-K partials in slice order, applies the FP8-mode scale, writes fp16.
+// VEC: four consecutive columns per lane (needs N % 4 == 0 and 8-byte aligned output rows).
+template <bool VEC>
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(const float *__restrict__ partials, int S, int M, int N, const float *scales,
                      float w_scale, uint16_t *__restrict__ Y, int64_t ldy) {
-    int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    int64_t total = (int64_t)M * N;
+    constexpr int W = VEC ? 4 : 1;
+    const int64_t total = (int64_t)M * N;
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * W;
     if (idx >= total) return;
-    int m = (int)(idx / N), n = (int)(idx - (int64_t)m * N);
-    float sum = partials[idx];
-    for (int s = 1; s < S; ++s) sum += partials[(int64_t)s * total + idx];
-    if (scales) sum *= scales[m] * w_scale;
-    union { _Float16 f; uint16_t u; } c;
-    c.f = (_Float16)sum;
-    Y[(int64_t)m * ldy + n] = c.u;
+    const int m = (int)(idx / N), n = (int)(idx - (int64_t)m * N);
+    float v[W];
+    if (VEC) {
+        floatx4 t = *reinterpret_cast<const floatx4 *>(partials + idx);
+        v[0] = t.x; v[W > 1 ? 1 : 0] = t.y; v[W > 2 ? 2 : 0] = t.z; v[W > 3 ? 3 : 0] = t.w;
+        for (int s = 1; s < S; ++s) {
+            floatx4 u = *reinterpret_cast<const floatx4 *>(partials + (int64_t)s * total + idx);
+            v[0] += u.x; v[W > 1 ? 1 : 0] += u.y; v[W > 2 ? 2 : 0] += u.z; v[W > 3 ? 3 : 0] += u.w;
+        }
+    } else {
+        v[0] = partials[idx];
+        for (int s = 1; s < S; ++s) v[0] += partials[(int64_t)s * total + idx];
+    }
+    const float sc = scales ? scales[m] * w_scale : 1.0f;
+    uint16_t *dst = Y + (int64_t)m * ldy + n;
+    if (VEC) {
+        u32x2 o;
+        o.x = float2_to_half2_bits(scales ? v[0] * sc : v[0], scales ? v[W > 1 ? 1 : 0] * sc : v[W > 1 ? 1 : 0]);
+        o.y = float2_to_half2_bits(scales ? v[W > 2 ? 2 : 0] * sc : v[W > 2 ? 2 : 0],
+                                   scales ? v[W > 3 ? 3 : 0] * sc : v[W > 3 ? 3 : 0]);
+        *reinterpret_cast<u32x2 *>(dst) = o;
+    } else {
+        union { _Float16 f; uint16_t u; } c;
+        c.f = (_Float16)(scales ? v[0] * sc : v[0]);
+        dst[0] = c.u;
+    }
 }
 
 int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, const float *scales,
                          float w_scale, uint16_t *Y, int64_t ldy, hipStream_t stream) {
-    int64_t total = M * N;
-    splitk_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(partials, S, (int)M, (int)N,
-                                                                              scales, w_scale, Y, ldy);
+    const int64_t total = M * N;
+    const bool vec = (N & 3) == 0 && (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(Y) & 7) == 0 &&
+                     (reinterpret_cast<uintptr_t>(partials) & 15) == 0;
+    if (vec)
+        splitk_reduce_kernel<true><<<(unsigned)((total / 4 + 255) / 256), 256, 0, stream>>>(
+            partials, S, (int)M, (int)N, scales, w_scale, Y, ldy);
+    else
+        splitk_reduce_kernel<false><<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
+            partials, S, (int)M, (int)N, scales, w_scale, Y, ldy);
     return hip_ok(hipGetLastError());
 }
 

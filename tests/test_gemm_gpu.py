@@ -258,3 +258,35 @@ def test_llama8b_prefill_shapes_sampled(nfp, name, M):
     ref8 = oracle.gemm_fp8(Xq, s, up_s)
     got8 = y8[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
     assert_gemm_close(got8, ref8, "%s M=%d FP8 sample" % (name, M))
+
+
+def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
+    """Full-size launch; planes and both GEMM modes checked on a seeded sample of rows/columns."""
+    Wd = workloads.weight_device(N, K, sigma, seed=seed)
+    Xd = workloads.act_device(M, K, seed=seed + 1)
+    up, lo = nfp.decompose(Wd)
+    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+    assert torch.equal(y16, nfp.plain_gemm_fp16(Xd, Wd)), tag + ": FP16 mode differs from plain fp16"
+    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
+    rows, cols = workloads.sample_indices(M, N, 16, 64, seed=seed)
+    ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    Xs, Ws = Xd[ri].cpu().numpy(), Wd[ci].cpu().numpy()
+    up_s, lo_s, bad = oracle.decompose(Ws)
+    assert bad == 0
+    assert np.array_equal(up[ci].cpu().numpy(), up_s) and np.array_equal(lo[ci].cpu().numpy(), lo_s)
+    assert_gemm_close(y16[ri][:, ci].cpu().numpy(), oracle.gemm_fp16(Xs, Ws), tag + " FP16 sample")
+    Xq, s = oracle.quantize_act(Xs)
+    assert_gemm_close(y8[ri][:, ci].cpu().numpy(), oracle.gemm_fp8(Xq, s, up_s), tag + " FP8 sample")
+
+
+@pytest.mark.parametrize("name,M", [("qkv", 1), ("down", 16), ("gate_up", 64), ("o", 4096), ("down", 2)])
+def test_llama70b_shapes_sampled(nfp, name, M):
+    # configs[3]: the unsharded 70B linears on one GPU, sigma 0.015
+    N, K = workloads.LLAMA3_70B[name]
+    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_70B, "70B %s M=%d" % (name, M), seed=70 + M)
+
+
+@pytest.mark.parametrize("N,K,M", [(28672, 5120, 96), (65536, 5120, 1024), (35840, 5120, 32)])
+def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, M):
+    # the (N, K) shapes of Sec. 5.2 / Fig. 6, M inside its 32..2048 sweep
+    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_8B, "N=%d K=%d M=%d" % (N, K, M), seed=N % 89)
