@@ -208,6 +208,139 @@ struct LargeKernel {
     }
     static constexpr int NC1 = KIND == kE4M3 ? 1 : 0;
 
+    // ---- direct-to-LDS loads (buffer_load ... lds) -------------------------------------------
+    // One wave instruction fills 1 KB of LDS = 8 tile rows in lane order (lane l -> row l/8,
+    // physical chunk l%8), so the XOR swizzle is applied on the global side: lane l fetches
+    // the logical chunk (l%8) ^ ((row>>1)&7) of its row.  No VGPR staging, no ds_write.
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int XG = TM / 8 / WAVES;          // 8-row groups per wave, token tile
+    static constexpr int WG8 = TN / 8 / WAVES;         // 8-row groups per wave, weight tile
+
+    struct DmaOffsets {
+        uint32_t x[XG], w[WG8];
+        uint32_t kpos;                                 // this lane's K byte position in a K-tile
+    };
+
+    static __device__ __forceinline__ void make_dma_offsets(DmaOffsets &o, const LargeParams &p, int wave, int lane) {
+        const int pc = lane & 7;
+        const int c = pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);     // (row >> 1) & 7 for row = gid*8 + lane/8
+        o.kpos = 16u * c;
+#pragma unroll
+        for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * WAVES + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
+#pragma unroll
+        for (int i = 0; i < WG8; ++i) o.w[i] = (uint32_t)((i * WAVES + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
+    }
+
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    template <int G>
+    static __device__ __forceinline__ void dma_rows(const uint32_t (&off)[G], uint32_t kpos, uint32_t k_lim,
+                                                    __amdgpu_buffer_rsrc_t rs, lds_byte *dst, int wave, int kt) {
+        const uint32_t kb = (uint32_t)kt * 128u;
+        const uint32_t kill = (kb + kpos < k_lim) ? 0u : 0x80000000u;       // past K: out of range, zero fill
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + (i * WAVES + wave) * 1024),
+                                                     16, (off[i] + kb) | kill, 0, 0, 0);
+    }
+
+    static __device__ __forceinline__ void run_dtl(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+        const int tile = blockIdx.x;
+        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        const int m0 = tm * TM, n0 = tn * TN;
+        const int split = blockIdx.y;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
+
+        floatx16 acc[FN][FM];
+#pragma unroll
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+        const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
+        const int w_row_k = (KIND == kNestedF16) ? p.K : p.k_bytes;
+        const __amdgpu_buffer_rsrc_t rw0 = tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
+        const __amdgpu_buffer_rsrc_t rw1 =
+            tile_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
+        DmaOffsets dof;
+        make_dma_offsets(dof, p, wave, lane);
+        Offsets off;                                     // register path (planes only)
+        if (KIND == kNestedF16) make_offsets(off, p);
+        Prefetch pf;
+
+        // Tokens (and plain / E4M3 weights) go straight from global memory into the LDS stage
+        // of the next K-tile while the current one is multiplied; the planes take the register
+        // path (they have to pass through the merge) and are written to LDS half-way through.
+        auto issue = [&](int kt, int stage_idx) {
+            dma_rows<XG>(dof.x, dof.kpos, (uint32_t)p.k_bytes, rx, lds3 + stage_idx * STAGE + TN * 128, wave, kt);
+            if (KIND == kNestedF16) load_planes(pf, off, rw0, rw1, kt);
+            else dma_rows<WG8>(dof.w, dof.kpos, (uint32_t)p.k_bytes, rw0, lds3 + stage_idx * STAGE, wave, kt);
+        };
+        issue(kt_begin, 0);
+        if (KIND == kNestedF16) store_planes(pf, lds);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);
+        constexpr int MFMAS = FN * FM;
+        Frags fr[2];
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            const int cur = (kt - kt_begin) & 1;
+            const uint8_t *stage = lds + cur * STAGE;
+            issue(kt + 1, cur ^ 1);
+            read_frags(fr[0], stage, wm, wn, lane, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < SUBSTEPS; ++s) {
+                const bool mid = (KIND == kNestedF16) && (s == SUBSTEPS / 2);
+                if (s + 1 < SUBSTEPS) read_frags(fr[(s + 1) & 1], stage, wm, wn, lane, s + 1);
+                if (mid) store_planes(pf, lds + (cur ^ 1) * STAGE);
+                mfmas(fr[s & 1], acc);
+#pragma unroll
+                for (int q = 0; q < MFMAS; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (s + 1 < SUBSTEPS && q < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (mid && q < 2 * WP4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+        epilogue(p, acc, m0, n0, wm, wn, lane, split);
+    }
+
+    // register path of the planes only (direct-to-LDS variant)
+    static __device__ __forceinline__ void load_planes(Prefetch &pf, const Offsets &o, __amdgpu_buffer_rsrc_t rw0,
+                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
+        const uint32_t kb = (uint32_t)kt * 64u;
+        const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : 0x80000000u;
+#pragma unroll
+        for (int i = 0; i < WP4; ++i) {
+            pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
+            pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
+        }
+    }
+
+    static __device__ __forceinline__ void store_planes(const Prefetch &pf, uint8_t *stage) {
+        const int t = threadIdx.x;
+        const int c4 = t & 3, r0 = t >> 2;
+#pragma unroll
+        for (int i = 0; i < WP4; ++i) {
+            int row = r0 + R4 * i;
+            if (TN < R4 && row >= TN) continue;
+            u32x4 w_lo, w_hi;
+            merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);       // Sec. 4.2, Alg. 1
+            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4)) = w_lo;
+            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + 1)) = w_hi;
+        }
+    }
+
     static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds) {
         const int lane = threadIdx.x & 63;
         const int wave = threadIdx.x >> 6;
@@ -278,7 +411,11 @@ struct LargeKernel {
             __syncthreads();
         }
 
-        // ---- epilogue ---------------------------------------------------------------
+        epilogue(p, acc, m0, n0, wm, wn, lane, split);
+    }
+
+    static __device__ __forceinline__ void epilogue(const LargeParams &p, floatx16 (&acc)[FN][FM], int m0, int n0,
+                                                    int wm, int wn, int lane, int split) {
         const int r32 = lane & 31, h = lane >> 5;
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
@@ -322,14 +459,16 @@ struct LargeKernel {
     }
 };
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, bool DTL>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 large_gemm_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::run(p, lds_raw);
+    typedef LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N> Kern;
+    if (DTL) Kern::run_dtl(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
+    else Kern::run(p, lds_raw);
 }
 
-struct LargeConfig { int tm, tn, split, waves; };
+struct LargeConfig { int tm, tn, split, waves, dtl; };
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -340,6 +479,9 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
     int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
     c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
+    // measured: direct-to-LDS loads help the plain and E4M3 kinds a little; the planes have to
+    // pass through registers for the merge anyway and run faster wholly on the register path
+    c.dtl = t.large_dtl >= 0 ? (t.large_dtl != 0) : (kind != kNestedF16);
     c.split = 1;
     if (tiles < 256) {                                  // fewer tiles than CUs: split K
         int64_t s = (512 + tiles - 1) / tiles;
@@ -356,9 +498,9 @@ size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
     return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, bool DTL>
 static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N>;
+    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N, DTL>;
     constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
@@ -371,9 +513,12 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
-    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
-    else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
+    if (c.tm == 256 && c.waves == 4 && c.dtl) launch_large_t<KIND, 256, 256, 2, 2, true>(p, grid, stream);
+    else if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2, false>(p, grid, stream);
+    else if (c.tm == 256 && c.dtl) launch_large_t<KIND, 256, 256, 2, 4, true>(p, grid, stream);
+    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4, false>(p, grid, stream);
+    else if (c.dtl) launch_large_t<KIND, 128, 128, 2, 4, true>(p, grid, stream);
+    else launch_large_t<KIND, 128, 128, 2, 4, false>(p, grid, stream);
 }
 
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
