@@ -175,16 +175,51 @@ struct LargeKernel {
         const int r32 = lane & 31, h = lane >> 5;
         constexpr int NC = KIND == kE4M3 ? 2 : 1;          // 16-byte chunks per lane per substep
         const int c = NC * (2 * s + h);
+        // issued in the order the MFMAs of the substep need them: a[0], b[0..FM-1], a[1..]
 #pragma unroll
-        for (int i = 0; i < FN; ++i)
+        for (int i = 0; i < FN; ++i) {
 #pragma unroll
             for (int q = 0; q < NC; ++q)
                 f.a[i][q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + 32 * i + r32, c + q));
+            if (i == 0) {
 #pragma unroll
-        for (int j = 0; j < FM; ++j)
+                for (int j = 0; j < FM; ++j)
 #pragma unroll
-            for (int q = 0; q < NC; ++q)
-                f.b[j][q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * j + r32, c + q));
+                    for (int q = 0; q < NC; ++q)
+                        f.b[j][q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * j + r32, c + q));
+            }
+        }
+    }
+
+    // The r-th LDS read of a substep's fragments, in the order the MFMAs need them:
+    // a[0], b[0..FM-1], a[1..FN-1] (NC reads each).
+    template <int R>
+    static __device__ __forceinline__ void read_one(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        constexpr int NC = KIND == kE4M3 ? 2 : 1;
+        constexpr int F = R / NC, Q = R % NC;              // fragment index in issue order, chunk within it
+        const uint8_t *sW = stage, *sX = stage + TN * 128;
+        const int r32 = lane & 31, h = lane >> 5;
+        const int c = NC * (2 * s + h) + Q;
+        if (F == 0) f.a[0][Q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + r32, c));
+        else if (F <= FM) f.b[F - 1][Q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * (F - 1) + r32, c));
+        else f.a[F - FM][Q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + 32 * (F - FM) + r32, c));
+    }
+
+    template <int Q>
+    static __device__ __forceinline__ void mfma_one(const Frags &f, floatx16 (&acc)[FN][FM]) {
+        constexpr int i = Q / FM, j = Q % FM;
+        if (KIND == kE4M3) {
+            intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w,
+                       f.a[i][NC1].x, f.a[i][NC1].y, f.a[i][NC1].z, f.a[i][NC1].w};
+            intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w,
+                       f.b[j][NC1].x, f.b[j][NC1].y, f.b[j][NC1].z, f.b[j][NC1].w};
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
+        } else {
+            union { intx4 v; half8 h; } a, b;
+            a.v = f.a[i][0];
+            b.v = f.b[j][0];
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, acc[i][j], 0, 0, 0);
+        }
     }
 
     static __device__ __forceinline__ void mfmas(const Frags &f, floatx16 (&acc)[FN][FM]) {
@@ -213,8 +248,13 @@ struct LargeKernel {
     // physical chunk l%8), so the XOR swizzle is applied on the global side: lane l fetches
     // the logical chunk (l%8) ^ ((row>>1)&7) of its row.  No VGPR staging, no ds_write.
     static constexpr int WAVES = WAVES_M * WAVES_N;
-    static constexpr int XG = TM / 8 / WAVES;          // 8-row groups per wave, token tile
-    static constexpr int WG8 = TN / 8 / WAVES;         // 8-row groups per wave, weight tile
+    // With two waves per SIMD the older one wins every arbitration and reaches the barrier long
+    // before the younger one.  The loads are therefore issued by the older four waves only:
+    // a load instruction blocks the issue of whatever is behind it while the address queue is
+    // full, and those waves have the time to spare.
+    static constexpr int DW = WAVES == 8 ? 4 : WAVES;  // waves that issue direct-to-LDS loads
+    static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
+    static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
 
     struct DmaOffsets {
         uint32_t x[XG], w[WG8];
@@ -226,9 +266,9 @@ struct LargeKernel {
         const int c = pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);     // (row >> 1) & 7 for row = gid*8 + lane/8
         o.kpos = 16u * c;
 #pragma unroll
-        for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * WAVES + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
+        for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
 #pragma unroll
-        for (int i = 0; i < WG8; ++i) o.w[i] = (uint32_t)((i * WAVES + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
+        for (int i = 0; i < WG8; ++i) o.w[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
     }
 
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
@@ -240,8 +280,146 @@ struct LargeKernel {
         const uint32_t kill = (kb + kpos < k_lim) ? 0u : 0x80000000u;       // past K: out of range, zero fill
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + (i * WAVES + wave) * 1024),
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + (i * DW + wave) * 1024),
                                                      16, (off[i] + kb) | kill, 0, 0, 0);
+    }
+
+    // the i-th of a wave's XG + WG8 direct-to-LDS loads of one K-tile (token rows first);
+    // i is a constant at every call site
+    static __device__ __forceinline__ void dma_one(int i, const DmaOffsets &o, uint32_t x_lim, uint32_t w_lim,
+                                                   __amdgpu_buffer_rsrc_t rx, __amdgpu_buffer_rsrc_t rw,
+                                                   lds_byte *stage, int wave, int kt) {
+        const uint32_t kb = (uint32_t)kt * 128u;
+        if (i < XG) {
+            const uint32_t kill = (kb + o.kpos < x_lim) ? 0u : 0x80000000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(stage + TN * 128 + (i * DW + wave) * 1024),
+                                                     16, (o.x[i] + kb) | kill, 0, 0, 0);
+        } else {
+            const int j = i - XG;
+            const uint32_t kill = (kb + o.kpos < w_lim) ? 0u : 0x80000000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
+                                                     16, (o.w[j] + kb) | kill, 0, 0, 0);
+        }
+    }
+
+    // ---- the K loop as an explicit instruction schedule ---------------------------------------
+    // Every MFMA of a substep is followed by the few other instructions assigned to its slot
+    // and a scheduling fence, so the order below is the order in the binary:
+    //   * LDS reads of the next substep's fragments, one (FP16) or two (E4M3) per MFMA, in the
+    //     order the MFMAs will need them;
+    //   * the direct-to-LDS loads, spread over three substeps so that the eight waves never
+    //     fill the texture-address queue (a wave that cannot issue its load cannot issue the
+    //     MFMA behind it either);
+    //   * for the planes: merge + LDS write + reload, one 16-weight piece at a time.
+    static constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);
+    static constexpr int MFMAS = FN * FM;
+    static constexpr int RPS = (READS + MFMAS - 1) / MFMAS;            // reads per slot
+    static constexpr int DMAS = XG + (KIND == kNestedF16 ? 0 : WG8);   // loads per wave per K-tile
+    static constexpr int DPS = (DMAS + MFMAS - 1) / MFMAS;             // loads per slot of the last substep
+
+    struct Ctx {
+        floatx16 (&acc)[FN][FM];
+        Frags (&fr)[2];
+        Prefetch &pf;
+        const Offsets &off;
+        const DmaOffsets &dof;
+        __amdgpu_buffer_rsrc_t rx, rw0, rw1;
+        uint8_t *lds;
+        lds_byte *lds3;
+        uint32_t x_lim, w_lim;
+        int wave, lane, wm, wn;
+        int kt, cur;
+#ifdef NFP_TRACE
+        uint64_t tr_vm = 0, tr_bar = 0;
+#endif
+    };
+
+    template <int I>
+    static __device__ __forceinline__ void plane_piece(Ctx &c) {
+        // 16 weights of one row: merge (Sec. 4.2, Alg. 1), write the FP16 halves into the stage
+        // that has just been freed (K-tile kt+2), refill the registers with K-tile kt+3
+        const int t = threadIdx.x;
+        const int c4 = t & 3, row = (t >> 2) + R4 * I;
+        uint8_t *stage = c.lds + c.cur * STAGE;
+        if (!(TN < R4 && row >= TN)) {
+            u32x4 w_lo, w_hi;
+            merge16(c.pf.w[2 * I], c.pf.w[2 * I + 1], w_lo, w_hi);
+            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4)) = w_lo;
+            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + 1)) = w_hi;
+        }
+        const uint32_t kb = (uint32_t)(c.kt + 3) * 64u;
+        const uint32_t kill = (kb + c.off.w_kpos < c.off.w_lim) ? 0u : 0x80000000u;
+        c.pf.w[2 * I] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, (c.off.w[I] + kb) | kill, 0, 0);
+        c.pf.w[2 * I + 1] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, (c.off.w[I] + kb) | kill, 0, 0);
+    }
+
+    template <int S, int Q>
+    static __device__ __forceinline__ void slot(Ctx &c) {
+        constexpr bool last = (S == SUBSTEPS - 1);
+        mfma_one<Q>(c.fr[S & 1], c.acc);
+        {   // fragments of the following substep (of the next K-tile after the barrier)
+            const uint8_t *src = c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE;
+            constexpr int s_next = last ? 0 : S + 1;
+            Frags &dst = c.fr[(S + 1) & 1];
+            read_range<Q * RPS, (Q + 1) * RPS < READS ? (Q + 1) * RPS : READS>(dst, src, c.wm, c.wn, c.lane, s_next);
+        }
+        if constexpr (last) {
+            if (c.wave < DW) {                          // wave-uniform
+#pragma unroll
+                for (int d = Q * DPS; d < (Q + 1) * DPS && d < DMAS; ++d)
+                    dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+            }
+            if constexpr (KIND == kNestedF16 && (Q & 1) == 1 && (Q >> 1) < WP4) plane_piece<(Q >> 1)>(c);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (Q + 1 < MFMAS) slot<S, Q + 1>(c);
+    }
+
+    template <int S>
+    static __device__ __forceinline__ void substeps(Ctx &c) {
+        if constexpr (S == SUBSTEPS - 1) {
+            // Everything this wave still needs from the current stage is in registers.  Once all
+            // waves are here and their loads of the next K-tile have landed, the current stage
+            // is free and the next one complete.
+#ifdef NFP_TRACE
+            uint64_t ta = __builtin_readcyclecounter();
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            uint64_t tb = __builtin_readcyclecounter();
+            __syncthreads();
+            uint64_t tc = __builtin_readcyclecounter();
+            c.tr_vm += tb - ta;  c.tr_bar += tc - tb;
+#else
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        slot<S, 0>(c);
+        if constexpr (S + 1 < SUBSTEPS) substeps<S + 1>(c);
+    }
+
+    template <int I, int END>
+    static __device__ __forceinline__ void dma_range(Ctx &c, int stage_idx, int kt) {
+        if constexpr (I < END) {
+            dma_one(I, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + stage_idx * STAGE, c.wave, kt);
+            dma_range<I + 1, END>(c, stage_idx, kt);
+        }
+    }
+
+    template <int R, int END>
+    static __device__ __forceinline__ void read_range(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        if constexpr (R < END) {
+            read_one<R>(f, stage, wm, wn, lane, s);
+            read_range<R + 1, END>(f, stage, wm, wn, lane, s);
+        }
+    }
+
+    template <int R>
+    static __device__ __forceinline__ void read_all(Frags &f, const uint8_t *stage, int wm, int wn, int lane) {
+        if constexpr (R < READS) {
+            read_one<R>(f, stage, wm, wn, lane, 0);
+            read_all<R + 1>(f, stage, wm, wn, lane);
+        }
     }
 
     static __device__ __forceinline__ void run_dtl(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
@@ -273,46 +451,57 @@ struct LargeKernel {
         Offsets off;                                     // register path (planes only)
         if (KIND == kNestedF16) make_offsets(off, p);
         Prefetch pf;
-
-        // Tokens (and plain / E4M3 weights) go straight from global memory into the LDS stage
-        // of the next K-tile while the current one is multiplied; the planes take the register
-        // path (they have to pass through the merge) and are written to LDS half-way through.
-        auto issue = [&](int kt, int stage_idx) {
-            dma_rows<XG>(dof.x, dof.kpos, (uint32_t)p.k_bytes, rx, lds3 + stage_idx * STAGE + TN * 128, wave, kt);
-            if (KIND == kNestedF16) load_planes(pf, off, rw0, rw1, kt);
-            else dma_rows<WG8>(dof.w, dof.kpos, (uint32_t)p.k_bytes, rw0, lds3 + stage_idx * STAGE, wave, kt);
-        };
-        issue(kt_begin, 0);
-        if (KIND == kNestedF16) store_planes(pf, lds);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);
-        constexpr int MFMAS = FN * FM;
         Frags fr[2];
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            const int cur = (kt - kt_begin) & 1;
-            const uint8_t *stage = lds + cur * STAGE;
-            issue(kt + 1, cur ^ 1);
-            read_frags(fr[0], stage, wm, wn, lane, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int s = 0; s < SUBSTEPS; ++s) {
-                const bool mid = (KIND == kNestedF16) && (s == SUBSTEPS / 2);
-                if (s + 1 < SUBSTEPS) read_frags(fr[(s + 1) & 1], stage, wm, wn, lane, s + 1);
-                if (mid) store_planes(pf, lds + (cur ^ 1) * STAGE);
-                mfmas(fr[s & 1], acc);
-#pragma unroll
-                for (int q = 0; q < MFMAS; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    if (s + 1 < SUBSTEPS && q < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                    if (mid && q < 2 * WP4) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+        Ctx c{acc, fr, pf, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes, (uint32_t)p.k_bytes,
+              wave, lane, wm, wn, kt_begin, 0};
+
+        // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
+        // into LDS; the planes take the register path (they have to pass through the merge).
+        // The one barrier per K-tile sits in front of the LAST substep: by then every wave holds
+        // that substep's fragments in registers, so the current stage is free for K-tile kt+2,
+        // and the first fragments of K-tile kt+1 are fetched underneath the last MFMAs.
+#ifdef NFP_TRACE
+        uint64_t tr_start = __builtin_readcyclecounter();
+#endif
+        if (wave < DW) {
+            dma_range<0, DMAS>(c, 0, kt_begin);
+            dma_range<0, DMAS>(c, 1, kt_begin + 1);
         }
+        if (KIND == kNestedF16) {
+            Prefetch pf1;
+            load_planes(pf, off, rw0, rw1, kt_begin);
+            load_planes(pf1, off, rw0, rw1, kt_begin + 1);
+            store_planes(pf, lds);
+            store_planes(pf1, lds + STAGE);
+            load_planes(pf, off, rw0, rw1, kt_begin + 2);
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * WP4) : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
+        }
+        __syncthreads();
+#ifdef NFP_TRACE
+        const uint64_t tr_loop = __builtin_readcyclecounter();
+#endif
+        read_all<0>(fr[0], lds, wm, wn, lane);
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            c.kt = kt;
+            c.cur = (kt - kt_begin) & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            substeps<0>(c);
+        }
+#ifdef NFP_TRACE
+        const uint64_t tr_end_loop = __builtin_readcyclecounter();
+#endif
         epilogue(p, acc, m0, n0, wm, wn, lane, split);
+#ifdef NFP_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const uint64_t tr_end = __builtin_readcyclecounter();
+        if (lane == 0 && p.partials != nullptr) {
+            uint64_t *o = reinterpret_cast<uint64_t *>(p.partials) + 8 * ((uint64_t)blockIdx.x * WAVES + wave);
+            o[0] = tr_loop - tr_start;  o[1] = tr_end_loop - tr_loop;  o[2] = c.tr_vm;  o[3] = c.tr_bar;
+            o[4] = tr_end - tr_end_loop;  o[5] = tr_end - tr_start;  o[6] = tr_start;  o[7] = tr_end;
+        }
+#endif
     }
 
     // register path of the planes only (direct-to-LDS variant)
