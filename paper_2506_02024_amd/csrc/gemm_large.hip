@@ -36,6 +36,7 @@ struct LargeParams {
     int tiles_m, tiles_n;
     int ktiles_total, ktiles_per_split;
     int vec_store;
+    int row_store;          // Y rows can be written 16 bytes per lane (N, ldy multiples of 8, Y 16-byte aligned)
 };
 
 // LDS tiles are rows of 128 bytes; the 16-byte chunk index is XOR-ed with (row >> 1) & 7.
@@ -253,6 +254,20 @@ struct LargeKernel {
     // a load instruction blocks the issue of whatever is behind it while the address queue is
     // full, and those waves have the time to spare.
     static constexpr int DW = WAVES == 8 ? 4 : WAVES;  // waves that issue direct-to-LDS loads
+    // The younger waves of a workgroup with two waves per SIMD do their share of the plane merge
+    // half a K-tile after the older ones, so that a SIMD never has both of its waves in the
+    // merge (and none in the matrix pipe) at the same time.
+    static constexpr bool kTwoRoles = WAVES != DW;
+    // The planes are loaded, merged and written to LDS 16 weights (16 bytes of each plane, two
+    // FP16 chunks) at a time; a weight row is four such pieces.  A group of 256 threads takes
+    // 64 rows per pass.  With two waves per SIMD the older waves have time to spare (see DW)
+    // and take three passes out of four.
+    static constexpr int PASSES = TN / 64;             // 64-row passes over the weight tile
+    static constexpr int NP_OLD = kTwoRoles ? (3 * PASSES + 3) / 4 : PASSES;
+    static constexpr int NP_YNG = kTwoRoles ? PASSES - NP_OLD : 0;
+    static constexpr int PWP = NP_OLD;                 // register pieces per thread (the larger share)
+    struct PlaneRegs { u32x4 w[2 * PWP]; };
+    struct PlaneOffsets { uint32_t w[PWP]; uint32_t kpos, lim; };
     static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
     static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
 
@@ -320,8 +335,9 @@ struct LargeKernel {
     struct Ctx {
         floatx16 (&acc)[FN][FM];
         Frags (&fr)[2];
-        Prefetch &pf;
-        const Offsets &off;
+        PlaneRegs &pf;
+        u32x4 merged;                                   // FP16 chunk being assembled by the plane merge
+        const PlaneOffsets &off;
         const DmaOffsets &dof;
         __amdgpu_buffer_rsrc_t rx, rw0, rw1;
         uint8_t *lds;
@@ -334,26 +350,94 @@ struct LargeKernel {
 #endif
     };
 
-    template <int I>
-    static __device__ __forceinline__ void plane_piece(Ctx &c) {
-        // 16 weights of one row: merge (Sec. 4.2, Alg. 1), write the FP16 halves into the stage
-        // that has just been freed (K-tile kt+2), refill the registers with K-tile kt+3
+    // The merge of a thread's PWP pieces (16 weights each) is cut into quarters of 4 weights
+    // (8 VALU instructions, Sec. 4.2 / Alg. 1) and spread over the MFMA slots of one substep:
+    // a SIMD hides about four plain VALU instructions behind each MFMA and no more.
+    // EARLY: older waves, right after the barrier of K-tile kt (registers hold K-tile kt+2, it
+    // goes into the stage just freed, the registers are refilled with kt+3).  Otherwise: younger
+    // waves, in substep 1 of K-tile kt (registers hold kt+1, which goes into the other stage,
+    // free since the barrier of kt-1; refill with kt+2).
+    template <bool EARLY> static constexpr int quarters() { return 4 * (EARLY ? NP_OLD : NP_YNG); }
+    template <bool EARLY> static constexpr int qps() { return (quarters<EARLY>() + MFMAS - 1) / MFMAS; }
+    // first quarter of slot q: spread evenly when there are fewer quarters than slots
+    template <bool EARLY> static constexpr int quarter_begin(int q) {
+        return quarters<EARLY>() >= MFMAS ? (q * qps<EARLY>() < quarters<EARLY>() ? q * qps<EARLY>() : quarters<EARLY>())
+                                         : (q * quarters<EARLY>() + MFMAS - 1) / MFMAS;
+    }
+
+    template <bool EARLY, int G>
+    static __device__ __forceinline__ void plane_quarter(Ctx &c) {
+        constexpr int I = G / 4, J = G % 4;             // piece, quarter within it
+        const uint32_t u = c.pf.w[2 * I][J], l = c.pf.w[2 * I + 1][J];
+        uint32_t a, b;
+        merge4(u, l, a, b);
+        c.merged[2 * (J & 1)] = a;
+        c.merged[2 * (J & 1) + 1] = b;
+        if constexpr ((J & 1) == 1) {
+            // two quarters = one 16-byte FP16 chunk of the row
+            const int t = threadIdx.x;
+            const int c4 = t & 3, row = (EARLY ? 0 : 64 * NP_OLD) + ((t & 255) >> 2) + 64 * I;
+            uint8_t *stage = c.lds + (EARLY ? c.cur : c.cur ^ 1) * STAGE;
+            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + (J >> 1))) = c.merged;
+        }
+        if constexpr (J == 3) {
+            const uint32_t kb = (uint32_t)(c.kt + (EARLY ? 3 : 2)) * 64u;
+            const uint32_t kill = (kb + c.off.kpos < c.off.lim) ? 0u : 0x80000000u;
+            c.pf.w[2 * I] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, (c.off.w[I] + kb) | kill, 0, 0);
+            c.pf.w[2 * I + 1] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, (c.off.w[I] + kb) | kill, 0, 0);
+        }
+    }
+
+    template <bool EARLY, int G, int END>
+    static __device__ __forceinline__ void plane_quarters(Ctx &c) {
+        if constexpr (G < END) {
+            plane_quarter<EARLY, G>(c);
+            plane_quarters<EARLY, G + 1, END>(c);
+        }
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p) {
+        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
         const int t = threadIdx.x;
-        const int c4 = t & 3, row = (t >> 2) + R4 * I;
-        uint8_t *stage = c.lds + c.cur * STAGE;
-        if (!(TN < R4 && row >= TN)) {
+        const int c4 = t & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + ((t & 255) >> 2);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) o.w[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
+        o.kpos = 16u * c4;
+        o.lim = (uint32_t)p.K;                          // planes: one byte per weight
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void load_planes(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
+                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
+        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
+        const uint32_t kb = (uint32_t)kt * 64u;
+        const uint32_t kill = (kb + o.kpos < o.lim) ? 0u : 0x80000000u;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
+            pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
+        }
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void store_planes(const PlaneRegs &pf, uint8_t *stage) {
+        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
+        const int t = threadIdx.x;
+        const int c4 = t & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + ((t & 255) >> 2);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int row = r0 + 64 * i;
             u32x4 w_lo, w_hi;
-            merge16(c.pf.w[2 * I], c.pf.w[2 * I + 1], w_lo, w_hi);
+            merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);       // Sec. 4.2, Alg. 1
             *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4)) = w_lo;
             *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + 1)) = w_hi;
         }
-        const uint32_t kb = (uint32_t)(c.kt + 3) * 64u;
-        const uint32_t kill = (kb + c.off.w_kpos < c.off.w_lim) ? 0u : 0x80000000u;
-        c.pf.w[2 * I] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, (c.off.w[I] + kb) | kill, 0, 0);
-        c.pf.w[2 * I + 1] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, (c.off.w[I] + kb) | kill, 0, 0);
     }
 
-    template <int S, int Q>
+    // OLDER: one of the DW waves that issue the direct-to-LDS loads.  The K loop exists once per
+    // role so that it has no branches inside.
+    template <bool OLDER, int S, int Q>
     static __device__ __forceinline__ void slot(Ctx &c) {
         constexpr bool last = (S == SUBSTEPS - 1);
         mfma_one<Q>(c.fr[S & 1], c.acc);
@@ -364,18 +448,21 @@ struct LargeKernel {
             read_range<Q * RPS, (Q + 1) * RPS < READS ? (Q + 1) * RPS : READS>(dst, src, c.wm, c.wn, c.lane, s_next);
         }
         if constexpr (last) {
-            if (c.wave < DW) {                          // wave-uniform
+            if constexpr (OLDER) {
 #pragma unroll
                 for (int d = Q * DPS; d < (Q + 1) * DPS && d < DMAS; ++d)
                     dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+                if constexpr (KIND == kNestedF16)
+                    plane_quarters<true, quarter_begin<true>(Q), quarter_begin<true>(Q + 1)>(c);
             }
-            if constexpr (KIND == kNestedF16 && (Q & 1) == 1 && (Q >> 1) < WP4) plane_piece<(Q >> 1)>(c);
+        } else if constexpr (S == 1 && !OLDER && KIND == kNestedF16 && NP_YNG > 0) {
+            plane_quarters<false, quarter_begin<false>(Q), quarter_begin<false>(Q + 1)>(c);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (Q + 1 < MFMAS) slot<S, Q + 1>(c);
+        if constexpr (Q + 1 < MFMAS) slot<OLDER, S, Q + 1>(c);
     }
 
-    template <int S>
+    template <bool OLDER, int S>
     static __device__ __forceinline__ void substeps(Ctx &c) {
         if constexpr (S == SUBSTEPS - 1) {
             // Everything this wave still needs from the current stage is in registers.  Once all
@@ -383,19 +470,31 @@ struct LargeKernel {
             // is free and the next one complete.
 #ifdef NFP_TRACE
             uint64_t ta = __builtin_readcyclecounter();
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             uint64_t tb = __builtin_readcyclecounter();
             __syncthreads();
             uint64_t tc = __builtin_readcyclecounter();
             c.tr_vm += tb - ta;  c.tr_bar += tc - tb;
 #else
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __syncthreads();
 #endif
             __builtin_amdgcn_sched_barrier(0);
         }
-        slot<S, 0>(c);
-        if constexpr (S + 1 < SUBSTEPS) substeps<S + 1>(c);
+        slot<OLDER, S, 0>(c);
+        if constexpr (S + 1 < SUBSTEPS) substeps<OLDER, S + 1>(c);
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            c.kt = kt;
+            c.cur = (kt - kt_begin) & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            substeps<OLDER, 0>(c);
+        }
     }
 
     template <int I, int END>
@@ -448,11 +547,14 @@ struct LargeKernel {
             tile_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
         DmaOffsets dof;
         make_dma_offsets(dof, p, wave, lane);
-        Offsets off;                                     // register path (planes only)
-        if (KIND == kNestedF16) make_offsets(off, p);
-        Prefetch pf;
+        PlaneOffsets off;
+        if (KIND == kNestedF16) {
+            if (!kTwoRoles || wave < DW) make_plane_offsets<true>(off, p);
+            else make_plane_offsets<false>(off, p);
+        }
+        PlaneRegs pf;
         Frags fr[2];
-        Ctx c{acc, fr, pf, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes, (uint32_t)p.k_bytes,
+        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes, (uint32_t)p.k_bytes,
               wave, lane, wm, wn, kt_begin, 0};
 
         // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
@@ -468,14 +570,25 @@ struct LargeKernel {
             dma_range<0, DMAS>(c, 1, kt_begin + 1);
         }
         if (KIND == kNestedF16) {
-            Prefetch pf1;
-            load_planes(pf, off, rw0, rw1, kt_begin);
-            load_planes(pf1, off, rw0, rw1, kt_begin + 1);
-            store_planes(pf, lds);
-            store_planes(pf1, lds + STAGE);
-            load_planes(pf, off, rw0, rw1, kt_begin + 2);
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * WP4) : "memory");
+            if (!kTwoRoles || wave < DW) {
+                PlaneRegs pf1;
+                load_planes<true>(pf, off, rw0, rw1, kt_begin);
+                load_planes<true>(pf1, off, rw0, rw1, kt_begin + 1);
+                store_planes<true>(pf, lds);
+                store_planes<true>(pf1, lds + STAGE);
+                load_planes<true>(pf, off, rw0, rw1, kt_begin + 2);
+                // everything but the last plane loads (the token loads were issued before them)
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NP_OLD) : "memory");
+            } else {
+                // younger waves keep K-tile kt_begin+1 in registers: their share of it is
+                // written in substep 1 of the first K-tile, as in every later one
+                load_planes<false>(pf, off, rw0, rw1, kt_begin);
+                store_planes<false>(pf, lds);
+                load_planes<false>(pf, off, rw0, rw1, kt_begin + 1);
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NP_YNG) : "memory");
+            }
         } else {
+            // the loads of K-tile kt_begin (a wave that issued none passes straight through)
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
         }
         __syncthreads();
@@ -483,16 +596,18 @@ struct LargeKernel {
         const uint64_t tr_loop = __builtin_readcyclecounter();
 #endif
         read_all<0>(fr[0], lds, wm, wn, lane);
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            c.kt = kt;
-            c.cur = (kt - kt_begin) & 1;
-            __builtin_amdgcn_sched_barrier(0);
-            substeps<0>(c);
-        }
+        if (!kTwoRoles || wave < DW) k_loop<true>(c, kt_begin, kt_end);
+        else k_loop<false>(c, kt_begin, kt_end);
 #ifdef NFP_TRACE
         const uint64_t tr_end_loop = __builtin_readcyclecounter();
 #endif
-        epilogue(p, acc, m0, n0, wm, wn, lane, split);
+        if (p.row_store && gridDim.y == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+            __syncthreads();
+            epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
+        } else {
+            epilogue(p, acc, m0, n0, wm, wn, lane, split);
+        }
 #ifdef NFP_TRACE
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const uint64_t tr_end = __builtin_readcyclecounter();
@@ -502,32 +617,6 @@ struct LargeKernel {
             o[4] = tr_end - tr_end_loop;  o[5] = tr_end - tr_start;  o[6] = tr_start;  o[7] = tr_end;
         }
 #endif
-    }
-
-    // register path of the planes only (direct-to-LDS variant)
-    static __device__ __forceinline__ void load_planes(Prefetch &pf, const Offsets &o, __amdgpu_buffer_rsrc_t rw0,
-                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
-        const uint32_t kb = (uint32_t)kt * 64u;
-        const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : 0x80000000u;
-#pragma unroll
-        for (int i = 0; i < WP4; ++i) {
-            pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
-            pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
-        }
-    }
-
-    static __device__ __forceinline__ void store_planes(const Prefetch &pf, uint8_t *stage) {
-        const int t = threadIdx.x;
-        const int c4 = t & 3, r0 = t >> 2;
-#pragma unroll
-        for (int i = 0; i < WP4; ++i) {
-            int row = r0 + R4 * i;
-            if (TN < R4 && row >= TN) continue;
-            u32x4 w_lo, w_hi;
-            merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);       // Sec. 4.2, Alg. 1
-            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4)) = w_lo;
-            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + 1)) = w_hi;
-        }
     }
 
     static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds) {
@@ -600,7 +689,51 @@ struct LargeKernel {
             __syncthreads();
         }
 
-        epilogue(p, acc, m0, n0, wm, wn, lane, split);
+        if (p.row_store && gridDim.y == 1) epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
+        else epilogue(p, acc, m0, n0, wm, wn, lane, split);
+    }
+
+    // Result tile through LDS: the MFMA layout leaves a lane with 4 consecutive outputs of one
+    // token, so direct stores are 8-byte pieces scattered over 32 rows per instruction.  Written
+    // to LDS as FP16 first (16-byte chunks XOR-swizzled with the row), the tile goes out as
+    // whole rows, 16 bytes per lane, every store instruction covering complete 128-byte lines.
+    // The caller guarantees that no wave still reads the operand stages.
+    static constexpr int OCH = TN * 2 / 16;            // 16-byte chunks per output row
+    static_assert(TM * TN * 2 <= LDS_BYTES, "output tile must fit into the operand stages");
+    static __device__ __forceinline__ void epilogue_lds(const LargeParams &p, floatx16 (&acc)[FN][FM], int m0, int n0,
+                                                        int wm, int wn, int lane, int wave, uint8_t *lds) {
+        const int r32 = lane & 31, h = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const int row = wm * WTM + 32 * j + r32;
+            float s = 1.0f;
+            if (KIND == kE4M3) {
+                const int m = m0 + row;
+                s = (m < p.M ? p.scales[m] : 0.f) * p.w_scale;
+            }
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int chunk = wn * (WTN / 8) + 4 * i + q;
+                    u32x2 o;
+                    o.x = float2_to_half2_bits(acc[i][j][4 * q] * s, acc[i][j][4 * q + 1] * s);
+                    o.y = float2_to_half2_bits(acc[i][j][4 * q + 2] * s, acc[i][j][4 * q + 3] * s);
+                    *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * h) = o;
+                }
+        }
+        __syncthreads();
+        constexpr int RPI = 64 / OCH;                  // rows per store instruction
+        constexpr int ROWS = TM / WAVES;               // rows per wave
+        const int chunk = lane % OCH;
+        const int n = n0 + chunk * 8;
+#pragma unroll
+        for (int it = 0; it < ROWS / RPI; ++it) {
+            const int row = wave * ROWS + it * RPI + lane / OCH;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4));
+            const int m = m0 + row;
+            if (m < p.M && n < p.N) *reinterpret_cast<u32x4 *>(p.Y + (int64_t)m * p.ldy + n) = v;
+        }
     }
 
     static __device__ __forceinline__ void epilogue(const LargeParams &p, floatx16 (&acc)[FN][FM], int m0, int n0,
@@ -668,9 +801,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
     int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
     c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
-    // measured: direct-to-LDS loads help the plain and E4M3 kinds a little; the planes have to
-    // pass through registers for the merge anyway and run faster wholly on the register path
-    c.dtl = t.large_dtl >= 0 ? (t.large_dtl != 0) : (kind != kNestedF16);
+    c.dtl = t.large_dtl != 0 ? 1 : 0;
     c.split = 1;
     if (tiles < 256) {                                  // fewer tiles than CUs: split K
         int64_t s = (512 + tiles - 1) / tiles;
@@ -730,6 +861,8 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.ktiles_per_split = (p.ktiles_total + c.split - 1) / c.split;
     c.split = (p.ktiles_total + p.ktiles_per_split - 1) / p.ktiles_per_split;   // no empty slices
     p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
+    p.row_store = ((a.N & 7) == 0 && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) ? 1 : 0;
+    if (tuning().large_epilogue == 0) p.row_store = 0;
     if (c.split > 1 && (a.partials == nullptr ||
                         a.partial_bytes < (size_t)c.split * a.M * a.N * sizeof(float)))
         return kErrWorkspace;

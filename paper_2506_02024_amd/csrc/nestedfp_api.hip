@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
     return t;
 }
 
@@ -287,7 +287,8 @@ int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64
 }
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
-                                     "large_split", "large_bm", "large_waves", "large_dtl", "quant_hw", nullptr};
+                                     "large_split", "large_bm", "large_waves", "large_dtl", "large_epilogue", "quant_hw",
+                                     nullptr};
 
 const char *nestedfp_tune_name(int index) {
     if (index < 0 || index >= (int)(sizeof(kKnobs) / sizeof(kKnobs[0]))) return nullptr;
@@ -307,6 +308,7 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "large_bm")) t.large_bm = value;
     else if (!strcmp(knob, "large_waves")) t.large_waves = value;
     else if (!strcmp(knob, "large_dtl")) t.large_dtl = value;
+    else if (!strcmp(knob, "large_epilogue")) t.large_epilogue = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;
     else return NESTEDFP_ERR_ARG;
     return NESTEDFP_OK;

@@ -42,6 +42,7 @@ struct Tuning {
     int64_t large_bm;        // tile height of the tiled kernel
     int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
     int64_t large_dtl;       // 0: stage tiles through registers instead of direct-to-LDS loads
+    int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
 };
 Tuning &tuning();
