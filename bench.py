@@ -82,8 +82,8 @@ def main():
         for j, name in enumerate(names):
             N, K = shapes[name]
             W = workloads.weight_device(N, K, workloads.SIGMA_W_8B, seed=layer * 4 + j)
-            up = torch.empty((N, K), dtype=torch.uint8, device=dev)
-            lo = torch.empty((N, K), dtype=torch.uint8, device=dev)
+            up = nfp.PackedPlane(N, K, dev)
+            lo = nfp.PackedPlane(N, K, dev)
             if layer == 0:
                 nfp.decompose(W, up, lo, check=True)      # warm + applicability check
             e0.record()

@@ -13,7 +13,16 @@
  *     and never writes to an input.
  *   - FP16 data travels as uint16_t bit patterns.  W is [N,K] row-major (K contiguous,
  *     row stride ldw elements), X is [M,K] (row stride ldx), Y is [M,N] (row stride ldy);
- *     Y = X * W^T.  Planes and quantised activations are dense row-major bytes.
+ *     Y = X * W^T.  Quantised activations are dense row-major bytes.
+ *   - Byte planes (upper, lower, plain E4M3 weights) are stored PACKED for the 64-lane MFMA
+ *     operand layout: with Np = 16*ceil(N/16) and Kp = 64*ceil(K/64) a plane takes Np*Kp
+ *     bytes (nestedfp_plane_bytes) and consists of 1024-byte blocks, one per 16-row by
+ *     64-column sub-matrix; block (i,j) starts at ((i * Kp/64) + j) * 1024 and holds the
+ *     16-byte chunk of row 16i+r, columns 64j+16g .. 64j+16g+15 at chunk index r + 16g
+ *     (r = 0..15, g = 0..3), bytes in column order.  Rows >= N and columns >= K are zero.
+ *     One 128-bit load per lane thus reads a block front to back with every lane holding
+ *     its own operand; FP8 mode still touches nothing but the upper plane.
+ *     nestedfp_pack_plane / nestedfp_unpack_plane convert from and to row-major bytes.
  *   - K must be a positive multiple of 16; ldw, ldx must be multiples of 8 and >= K;
  *     ldy must be a multiple of 4 and >= N when N % 4 == 0, else any ldy >= N is taken
  *     by a slower store path; W, X, planes, Xq and workspace pointers must be 16-byte
@@ -66,7 +75,8 @@ int nestedfp_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw,
  * Decomposition (Sec. 4.1 "Our Proposal"), done once, offline: for each weight
  *   upper = S | RNE_7(E[3:0]|M[1:10] -> E[3:0]|M[1:3])   (carry may enter the exponent)
  *   lower = M[3:10]
- * written to the dense [N,K] byte planes `upper` and `lower`.  Words that fail the
+ * written to the packed byte planes `upper` and `lower` (nestedfp_plane_bytes(N,K) bytes
+ * each, padding included, all of it overwritten).  Words that fail the
  * applicability test are counted into *out_of_range (device, 8 bytes, overwritten; may
  * be NULL to skip counting) and their plane entries are written as 0.  With
  * out_of_range_host non-NULL (needs out_of_range too) the call waits for the stream,
@@ -85,6 +95,18 @@ int nestedfp_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw,
  */
 int nestedfp_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
                          uint16_t *W, int64_t ldw, void *stream);
+
+/*
+ * Packed plane storage (see the conventions above; the layout serves the kernels of
+ * Sec. 4.2, whose lanes each own 16 consecutive weights of one row).
+ * plane_bytes: size of one packed plane of an [N,K] layer; 0 for invalid arguments.
+ * pack_plane:  row-major bytes src[N][ld] (ld >= K, multiple of 16) -> packed dst; use it
+ *   for E4M3 weights that do not come from nestedfp_decompose.  Padding is zeroed.
+ * unpack_plane: packed src -> row-major dst[N][ld].
+ */
+size_t nestedfp_plane_bytes(int64_t N, int64_t K);
+int nestedfp_pack_plane(const uint8_t *src, int64_t N, int64_t K, int64_t ld, uint8_t *dst, void *stream);
+int nestedfp_unpack_plane(const uint8_t *src, int64_t N, int64_t K, uint8_t *dst, int64_t ld, void *stream);
 
 /*
  * Activation quantisation for FP8 mode (Sec. 2.2 "E4M3 Format": dynamic per-token or
@@ -126,7 +148,8 @@ int nestedfp_gemm(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
  * Plain baselines of the same kernel family, for the comparison of Sec. 5.2 (NestedFP
  * FP16 mode against an FP16 GEMM that reads ordinary FP16 weights) and its FP8 analogue.
  * plain_gemm_fp16: W is ordinary FP16 [N,K].
- * plain_gemm_fp8:  Wq is any dense E4M3 [N,K] tensor with one host-side float scale;
+ * plain_gemm_fp8:  Wq is any E4M3 [N,K] tensor in packed plane storage (nestedfp_pack_plane)
+ *   with one host-side float scale;
  *   Y = scale[m] * w_scale * sum_k e4m3(Xq) * e4m3(Wq).  Feeding it the upper plane with
  *   w_scale = 2^-8 is, by Sec. 4 "Challenge 2", exactly FP8 mode.
  */
@@ -141,7 +164,7 @@ int nestedfp_plain_gemm_fp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * FP8-mode GEMM from activations that are already quantised (Xq dense [M,K] E4M3 bytes,
+ * FP8-mode GEMM from activations that are already quantised (Xq dense row-major [M,K] E4M3 bytes,
  * scales [M] floats), e.g. by nestedfp_quantize_act; lets a caller quantise once and
  * reuse the result for several linears that share X.  Same arithmetic as FP8 mode.
  */

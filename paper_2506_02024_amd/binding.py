@@ -48,6 +48,12 @@ def lib():
     L.nestedfp_decompose.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
     L.nestedfp_reconstruct.restype = ci
     L.nestedfp_reconstruct.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    L.nestedfp_plane_bytes.restype = sz
+    L.nestedfp_plane_bytes.argtypes = [i64, i64]
+    L.nestedfp_pack_plane.restype = ci
+    L.nestedfp_pack_plane.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.nestedfp_unpack_plane.restype = ci
+    L.nestedfp_unpack_plane.argtypes = [vp, i64, i64, vp, i64, vp]
     L.nestedfp_quantize_act.restype = ci
     L.nestedfp_quantize_act.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     L.nestedfp_gemm_workspace_size.restype = sz
@@ -116,14 +122,60 @@ def range_check(W):
     return int(host.value)
 
 
+class PackedPlane:
+    """One byte plane of an [N,K] layer in the library's packed storage (1 KB blocks of
+    16 rows x 64 columns, see include/nestedfp.h).  `data` is the flat uint8 device tensor."""
+
+    def __init__(self, N, K, device=None, data=None):
+        self.N, self.K = int(N), int(K)
+        nbytes = plane_bytes(self.N, self.K)
+        if data is None:
+            data = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+        elif data.numel() < nbytes or data.dtype != torch.uint8:
+            raise ValueError("plane buffer too small or not uint8")
+        self.data = data
+
+    shape = property(lambda self: (self.N, self.K))
+    device = property(lambda self: self.data.device)
+
+    def data_ptr(self):
+        return self.data.data_ptr()
+
+    def unpack(self):
+        """Row-major [N,K] uint8 copy of the plane."""
+        out = torch.empty((self.N, self.K), dtype=torch.uint8, device=self.data.device)
+        if self.N > 0:
+            st = lib().nestedfp_unpack_plane(_ptr(self.data), self.N, self.K, _ptr(out), self.K, _stream())
+            _check(st, "nestedfp_unpack_plane")
+        return out
+
+
+def plane_bytes(N, K):
+    return int(lib().nestedfp_plane_bytes(int(N), int(K)))
+
+
+def pack_plane(B):
+    """Row-major uint8 [N,K] (e.g. E4M3 codes) -> PackedPlane."""
+    N, K, ld = _rowmajor(B, "B")
+    P = PackedPlane(N, K, B.device)
+    if N > 0:
+        st = lib().nestedfp_pack_plane(_ptr(B), N, K, ld, _ptr(P.data), _stream())
+        _check(st, "nestedfp_pack_plane")
+    return P
+
+
+def _as_plane(B):
+    return B if isinstance(B, PackedPlane) or B is None else pack_plane(B)
+
+
 def decompose(W, upper=None, lower=None, check=True):
-    """fp16 W [N,K] -> (upper, lower) uint8 planes.  With check=True (default) waits for
+    """fp16 W [N,K] -> (upper, lower) packed planes.  With check=True (default) waits for
     the result and raises NestedFPError(ERR_RANGE) if the layer is not applicable."""
     N, K, ldw = _rowmajor(W, "W")
     if upper is None:
-        upper = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+        upper = PackedPlane(N, K, W.device)
     if lower is None:
-        lower = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+        lower = PackedPlane(N, K, W.device)
     cnt = torch.empty(1, dtype=torch.int64, device=W.device)
     host = ctypes.c_uint64(0)
     st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
@@ -135,8 +187,8 @@ def decompose(W, upper=None, lower=None, check=True):
 def decompose_count(W):
     """Like decompose(check=False) but also returns the out-of-range count (synchronises)."""
     N, K, ldw = _rowmajor(W, "W")
-    upper = torch.empty((N, K), dtype=torch.uint8, device=W.device)
-    lower = torch.empty((N, K), dtype=torch.uint8, device=W.device)
+    upper = PackedPlane(N, K, W.device)
+    lower = PackedPlane(N, K, W.device)
     cnt = torch.empty(1, dtype=torch.int64, device=W.device)
     host = ctypes.c_uint64(0)
     st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
@@ -147,7 +199,7 @@ def decompose_count(W):
 
 
 def reconstruct(upper, lower, out=None):
-    N, K, _ = _rowmajor(upper, "upper")
+    N, K = upper.shape
     if out is None:
         out = torch.empty((N, K), dtype=torch.float16, device=upper.device)
     _, _, ldw = _rowmajor(out, "out")
@@ -172,9 +224,11 @@ def gemm_workspace_size(M, N, K, mode):
 
 
 def gemm(X, upper, lower, mode, act_scale=None, out=None, workspace=None):
-    """Y = X @ W^T over the planes, in MODE_FP16 or MODE_FP8 (lower may be None in FP8)."""
+    """Y = X @ W^T over the packed planes, in MODE_FP16 or MODE_FP8 (lower may be None in FP8)."""
     M, K, ldx = _rowmajor(X, "X")
     N = upper.shape[0]
+    if upper.shape[1] != K:
+        raise ValueError("K of X and of the planes differ")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     _, _, ldy = _rowmajor(out, "out")
@@ -202,7 +256,9 @@ def plain_gemm_fp16(X, W, out=None, workspace=None):
 
 
 def plain_gemm_fp8(X, Wq, w_scale, act_scale=None, out=None, workspace=None):
+    """Wq: PackedPlane of E4M3 codes (a row-major uint8 [N,K] tensor is packed first)."""
     M, K, ldx = _rowmajor(X, "X")
+    Wq = _as_plane(Wq)
     N = Wq.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
@@ -218,6 +274,7 @@ def plain_gemm_fp8(X, Wq, w_scale, act_scale=None, out=None, workspace=None):
 
 def gemm_fp8_prequantized(Xq, scales, upper, w_scale=2.0 ** -8, out=None, workspace=None):
     M, K = Xq.shape
+    upper = _as_plane(upper)
     N = upper.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=Xq.device)

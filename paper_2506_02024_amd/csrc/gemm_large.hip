@@ -30,6 +30,7 @@ struct LargeParams {
     int64_t w_row_bytes;    // bytes per row of W0 (plain: 2*ldw, planes / E4M3: K)
     int M, N, K;
     int k_bytes;            // bytes per row along K for 8-chunk operands (2K or K)
+    int kblocks;            // 64-column blocks per row tile of a packed plane: ceil(K / 64)
     uint16_t *Y;
     int64_t ldy;
     float *partials;
@@ -53,144 +54,27 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint8_t *base,
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + row0 * row_bytes), 0, bytes, 0x00020000);
 }
 
+// raw buffer over the 16-row tiles of a packed plane that hold rows row0 .. row0+rows-1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base, int64_t row0, int rows, int kblocks) {
+    const int64_t tile_bytes = (int64_t)kblocks * 1024;
+    uint32_t bytes = rows > 0 ? (uint32_t)(((rows + 15) >> 4) * tile_bytes) : 0u;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + (row0 >> 4) * tile_bytes), 0, bytes, 0x00020000);
+}
+
 template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 struct LargeKernel {
     static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
     static constexpr int FM = WTM / 32, FN = WTN / 32;
-    static constexpr int R8 = THREADS / 8;             // rows per pass, 8 chunks per row
-    static constexpr int R4 = THREADS / 4;             // rows per pass, 4 double-chunks per row
-    static constexpr int XP = TM / R8;                 // 8-chunk passes for the token tile
-    static constexpr int WP8 = TN / R8;                // 8-chunk passes for the weight tile
-    static constexpr int WP4 = TN / R4 > 0 ? TN / R4 : 1;   // nested: 4 double-chunks per row
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
     static constexpr int LDS_BYTES = 2 * STAGE;
     static constexpr int SUBSTEPS = (KIND == kE4M3) ? 2 : 4;
-
-    struct Prefetch {
-        u32x4 x[XP];
-        u32x4 w[KIND == kNestedF16 ? 2 * WP4 : WP8];
-    };
-
-    // per-thread byte offsets inside the tile's buffers, fixed for the whole K loop
-    struct Offsets {
-        uint32_t x[XP];
-        uint32_t w[KIND == kNestedF16 ? WP4 : WP8];
-        uint32_t x_lim, w_lim;                          // first K byte past the row, per operand
-        uint32_t x_kpos, w_kpos;                        // this thread's K byte position in a K-tile
-    };
-
-    static __device__ __forceinline__ void make_offsets(Offsets &o, const LargeParams &p) {
-        const int t = threadIdx.x;
-        {
-            const int c = t & 7, r0 = t >> 3;
-#pragma unroll
-            for (int i = 0; i < XP; ++i) o.x[i] = (uint32_t)(r0 + R8 * i) * (uint32_t)p.x_row_bytes + 16u * c;
-            o.x_kpos = 16u * c;
-            o.x_lim = (uint32_t)p.k_bytes;
-        }
-        if (KIND == kNestedF16) {
-            const int c4 = t & 3, r0 = t >> 2;
-#pragma unroll
-            for (int i = 0; i < WP4; ++i) o.w[i] = (uint32_t)(r0 + R4 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
-            o.w_kpos = 16u * c4;
-            o.w_lim = (uint32_t)p.K;                    // planes: one byte per weight
-        } else {
-            const int c = t & 7, r0 = t >> 3;
-#pragma unroll
-            for (int i = 0; i < WP8; ++i) o.w[i] = (uint32_t)(r0 + R8 * i) * (uint32_t)p.w_row_bytes + 16u * c;
-            o.w_kpos = 16u * c;
-            o.w_lim = (uint32_t)p.k_bytes;
-        }
-    }
-
-    // Issues the loads of K-tile kt.  Chunks past the end of K are redirected out of the
-    // buffer's range (they read as zero), so no branch and no select on the data.
-    static __device__ __forceinline__ void load_global(Prefetch &pf, const Offsets &o,
-                                                       __amdgpu_buffer_rsrc_t rx, __amdgpu_buffer_rsrc_t rw0,
-                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
-        const uint32_t oob = 0x80000000u;
-        {
-            const uint32_t kb = (uint32_t)kt * 128u;
-            const uint32_t kill = (kb + o.x_kpos < o.x_lim) ? 0u : oob;
-#pragma unroll
-            for (int i = 0; i < XP; ++i) pf.x[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (o.x[i] + kb) | kill, 0, 0);
-        }
-        if (KIND == kNestedF16) {
-            const uint32_t kb = (uint32_t)kt * 64u;
-            const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : oob;
-#pragma unroll
-            for (int i = 0; i < WP4; ++i) {
-                pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
-                pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
-            }
-        } else {
-            const uint32_t kb = (uint32_t)kt * 128u;
-            const uint32_t kill = (kb + o.w_kpos < o.w_lim) ? 0u : oob;
-#pragma unroll
-            for (int i = 0; i < WP8; ++i) pf.w[i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
-        }
-    }
-
-    static __device__ __forceinline__ void store_lds(const Prefetch &pf, uint8_t *stage) {
-        const int t = threadIdx.x;
-        uint8_t *sW = stage, *sX = stage + TN * 128;
-        {
-            const int c = t & 7, r0 = t >> 3;
-#pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                int row = r0 + R8 * i;
-                *reinterpret_cast<u32x4 *>(sX + swz(row, c)) = pf.x[i];
-            }
-        }
-        if (KIND == kNestedF16) {
-            const int c4 = t & 3, r0 = t >> 2;
-#pragma unroll
-            for (int i = 0; i < WP4; ++i) {
-                int row = r0 + R4 * i;
-                if (TN < R4 && row >= TN) continue;
-                u32x4 w_lo, w_hi;
-                merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);   // Sec. 4.2, Alg. 1
-                *reinterpret_cast<u32x4 *>(sW + swz(row, 2 * c4)) = w_lo;
-                *reinterpret_cast<u32x4 *>(sW + swz(row, 2 * c4 + 1)) = w_hi;
-            }
-        } else {
-            const int c = t & 7, r0 = t >> 3;
-#pragma unroll
-            for (int i = 0; i < WP8; ++i) {
-                int row = r0 + R8 * i;
-                *reinterpret_cast<u32x4 *>(sW + swz(row, c)) = pf.w[i];
-            }
-        }
-    }
 
     // MFMA operand fragments of one K substep (16 halves / 64 E4M3 bytes per row)
     struct Frags {
         intx4 a[FN][KIND == kE4M3 ? 2 : 1];
         intx4 b[FM][KIND == kE4M3 ? 2 : 1];
     };
-
-    static __device__ __forceinline__ void read_frags(Frags &f, const uint8_t *stage, int wm, int wn,
-                                                      int lane, int s) {
-        const uint8_t *sW = stage, *sX = stage + TN * 128;
-        const int r32 = lane & 31, h = lane >> 5;
-        constexpr int NC = KIND == kE4M3 ? 2 : 1;          // 16-byte chunks per lane per substep
-        const int c = NC * (2 * s + h);
-        // issued in the order the MFMAs of the substep need them: a[0], b[0..FM-1], a[1..]
-#pragma unroll
-        for (int i = 0; i < FN; ++i) {
-#pragma unroll
-            for (int q = 0; q < NC; ++q)
-                f.a[i][q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + 32 * i + r32, c + q));
-            if (i == 0) {
-#pragma unroll
-                for (int j = 0; j < FM; ++j)
-#pragma unroll
-                    for (int q = 0; q < NC; ++q)
-                        f.b[j][q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * j + r32, c + q));
-            }
-        }
-    }
 
     // The r-th LDS read of a substep's fragments, in the order the MFMAs need them:
     // a[0], b[0..FM-1], a[1..FN-1] (NC reads each).
@@ -201,9 +85,17 @@ struct LargeKernel {
         const uint8_t *sW = stage, *sX = stage + TN * 128;
         const int r32 = lane & 31, h = lane >> 5;
         const int c = NC * (2 * s + h) + Q;
-        if (F == 0) f.a[0][Q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + r32, c));
+        if (F == 0) f.a[0][Q] = *reinterpret_cast<const intx4 *>(sW + w_addr(wn * WTN + r32, s, h, Q));
         else if (F <= FM) f.b[F - 1][Q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * (F - 1) + r32, c));
-        else f.a[F - FM][Q] = *reinterpret_cast<const intx4 *>(sW + swz(wn * WTN + 32 * (F - FM) + r32, c));
+        else f.a[F - FM][Q] = *reinterpret_cast<const intx4 *>(sW + w_addr(wn * WTN + 32 * (F - FM) + r32, s, h, Q));
+    }
+
+    // LDS address of a weight fragment chunk.  FP16 kinds: rows of 128 bytes, XOR-swizzled.
+    // E4M3: the stage holds the packed 1 KB blocks as they are in memory, [row tile][2 blocks];
+    // a substep is one block, and 16 lanes with consecutive rows read 256 consecutive bytes.
+    static __device__ __forceinline__ int w_addr(int row, int s, int h, int q) {
+        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (2 * h + q)) << 4);
+        return swz(row, 2 * s + h);
     }
 
     template <int Q>
@@ -223,25 +115,6 @@ struct LargeKernel {
         }
     }
 
-    static __device__ __forceinline__ void mfmas(const Frags &f, floatx16 (&acc)[FN][FM]) {
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-            for (int j = 0; j < FM; ++j) {
-                if (KIND == kE4M3) {
-                    intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w,
-                               f.a[i][NC1].x, f.a[i][NC1].y, f.a[i][NC1].z, f.a[i][NC1].w};
-                    intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w,
-                               f.b[j][NC1].x, f.b[j][NC1].y, f.b[j][NC1].z, f.b[j][NC1].w};
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
-                } else {
-                    union { intx4 v; half8 h; } a, b;
-                    a.v = f.a[i][0];
-                    b.v = f.b[j][0];
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, acc[i][j], 0, 0, 0);
-                }
-            }
-    }
     static constexpr int NC1 = KIND == kE4M3 ? 1 : 0;
 
     // ---- direct-to-LDS loads (buffer_load ... lds) -------------------------------------------
@@ -274,6 +147,7 @@ struct LargeKernel {
     struct DmaOffsets {
         uint32_t x[XG], w[WG8];
         uint32_t kpos;                                 // this lane's K byte position in a K-tile
+        int wbit;                                      // E4M3: which of a K-tile's two block columns this wave loads
     };
 
     static __device__ __forceinline__ void make_dma_offsets(DmaOffsets &o, const LargeParams &p, int wave, int lane) {
@@ -283,21 +157,20 @@ struct LargeKernel {
 #pragma unroll
         for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
 #pragma unroll
-        for (int i = 0; i < WG8; ++i) o.w[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
+        for (int i = 0; i < WG8; ++i) {
+            if (KIND == kE4M3) {
+                // packed upper plane: load i of wave w is block b = i*DW + w of the stage, i.e. block
+                // column (2*kt + b%2) of row tile b/2; lane l fetches chunk l
+                const int b = i * DW + wave;
+                o.w[i] = (uint32_t)((b >> 1) * p.kblocks + (b & 1)) * 1024u + 16u * lane;
+            } else {
+                o.w[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
+            }
+        }
+        o.wbit = wave & 1;
     }
 
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
-
-    template <int G>
-    static __device__ __forceinline__ void dma_rows(const uint32_t (&off)[G], uint32_t kpos, uint32_t k_lim,
-                                                    __amdgpu_buffer_rsrc_t rs, lds_byte *dst, int wave, int kt) {
-        const uint32_t kb = (uint32_t)kt * 128u;
-        const uint32_t kill = (kb + kpos < k_lim) ? 0u : 0x80000000u;       // past K: out of range, zero fill
-#pragma unroll
-        for (int i = 0; i < G; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(dst + (i * DW + wave) * 1024),
-                                                     16, (off[i] + kb) | kill, 0, 0, 0);
-    }
 
     // the i-th of a wave's XG + WG8 direct-to-LDS loads of one K-tile (token rows first);
     // i is a constant at every call site
@@ -311,9 +184,16 @@ struct LargeKernel {
                                                      16, (o.x[i] + kb) | kill, 0, 0, 0);
         } else {
             const int j = i - XG;
-            const uint32_t kill = (kb + o.kpos < w_lim) ? 0u : 0x80000000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
-                                                     16, (o.w[j] + kb) | kill, 0, 0, 0);
+            if (KIND == kE4M3) {
+                // w_lim = block columns of the plane; past them the load is sent out of range
+                const uint32_t kill = ((uint32_t)(2 * kt + o.wbit) < w_lim) ? 0u : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
+                                                         16, (o.w[j] + (uint32_t)kt * 2048u) | kill, 0, 0, 0);
+            } else {
+                const uint32_t kill = (kb + o.kpos < w_lim) ? 0u : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
+                                                         16, (o.w[j] + kb) | kill, 0, 0, 0);
+            }
         }
     }
 
@@ -381,8 +261,9 @@ struct LargeKernel {
             *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + (J >> 1))) = c.merged;
         }
         if constexpr (J == 3) {
-            const uint32_t kb = (uint32_t)(c.kt + (EARLY ? 3 : 2)) * 64u;
-            const uint32_t kill = (kb + c.off.kpos < c.off.lim) ? 0u : 0x80000000u;
+            const uint32_t ktn = (uint32_t)(c.kt + (EARLY ? 3 : 2));
+            const uint32_t kb = ktn * 1024u;
+            const uint32_t kill = (ktn < c.off.lim) ? 0u : 0x80000000u;
             c.pf.w[2 * I] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, (c.off.w[I] + kb) | kill, 0, 0);
             c.pf.w[2 * I + 1] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, (c.off.w[I] + kb) | kill, 0, 0);
         }
@@ -401,18 +282,23 @@ struct LargeKernel {
         constexpr int NP = OLDER ? NP_OLD : NP_YNG;
         const int t = threadIdx.x;
         const int c4 = t & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + ((t & 255) >> 2);
+        // packed planes: the 16 weights of row r, column group c4 of K-tile kt are chunk
+        // (r % 16) + 16 * c4 of block (r / 16, kt); a wave reads whole 1 KB blocks
 #pragma unroll
-        for (int i = 0; i < NP; ++i) o.w[i] = (uint32_t)(r0 + 64 * i) * (uint32_t)p.w_row_bytes + 16u * c4;
-        o.kpos = 16u * c4;
-        o.lim = (uint32_t)p.K;                          // planes: one byte per weight
+        for (int i = 0; i < NP; ++i) {
+            const int row = r0 + 64 * i;
+            o.w[i] = (uint32_t)((row >> 4) * p.kblocks) * 1024u + (uint32_t)(((row & 15) + 16 * c4) << 4);
+        }
+        o.kpos = 0;
+        o.lim = (uint32_t)p.kblocks;                    // block columns of the plane
     }
 
     template <bool OLDER>
     static __device__ __forceinline__ void load_planes(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
                                                        __amdgpu_buffer_rsrc_t rw1, int kt) {
         constexpr int NP = OLDER ? NP_OLD : NP_YNG;
-        const uint32_t kb = (uint32_t)kt * 64u;
-        const uint32_t kill = (kb + o.kpos < o.lim) ? 0u : 0x80000000u;
+        const uint32_t kb = (uint32_t)kt * 1024u;
+        const uint32_t kill = ((uint32_t)kt < o.lim) ? 0u : 0x80000000u;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
@@ -521,7 +407,7 @@ struct LargeKernel {
         }
     }
 
-    static __device__ __forceinline__ void run_dtl(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
+    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -541,10 +427,10 @@ struct LargeKernel {
                 for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
         const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
-        const int w_row_k = (KIND == kNestedF16) ? p.K : p.k_bytes;
-        const __amdgpu_buffer_rsrc_t rw0 = tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
-        const __amdgpu_buffer_rsrc_t rw1 =
-            tile_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
+        const __amdgpu_buffer_rsrc_t rw0 = KIND == kPlainF16
+            ? tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes)
+            : plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks);
+        const __amdgpu_buffer_rsrc_t rw1 = KIND == kNestedF16 ? plane_rsrc(p.W1, n0, min(TN, p.N - n0), p.kblocks) : rw0;
         DmaOffsets dof;
         make_dma_offsets(dof, p, wave, lane);
         PlaneOffsets off;
@@ -554,7 +440,8 @@ struct LargeKernel {
         }
         PlaneRegs pf;
         Frags fr[2];
-        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes, (uint32_t)p.k_bytes,
+        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes,
+              KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes,
               wave, lane, wm, wn, kt_begin, 0};
 
         // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
@@ -617,80 +504,6 @@ struct LargeKernel {
             o[4] = tr_end - tr_end_loop;  o[5] = tr_end - tr_start;  o[6] = tr_start;  o[7] = tr_end;
         }
 #endif
-    }
-
-    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds) {
-        const int lane = threadIdx.x & 63;
-        const int wave = threadIdx.x >> 6;
-        const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-        const int tile = blockIdx.x;
-        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
-        const int m0 = tm * TM, n0 = tn * TN;
-        const int split = blockIdx.y;
-        const int kt_begin = split * p.ktiles_per_split;
-        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
-
-        floatx16 acc[FN][FM];
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-            for (int j = 0; j < FM; ++j)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-
-        const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
-        const int w_row_k = (KIND == kNestedF16) ? p.K : p.k_bytes;
-        const __amdgpu_buffer_rsrc_t rw0 = tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
-        const __amdgpu_buffer_rsrc_t rw1 =
-            tile_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, w_row_k);
-        Offsets off;
-        make_offsets(off, p);
-
-        // Pipeline: the registers hold K-tile kt+1 while K-tile kt is multiplied out of LDS;
-        // half-way through the MFMAs of kt the registers are written to the other LDS stage
-        // and refilled with the loads of kt+2, so global latency has a whole K-tile to hide in
-        // and the LDS writes overlap with MFMAs of the other wave on the SIMD.
-        Prefetch pf;
-        load_global(pf, off, rx, rw0, rw1, kt_begin);
-        store_lds(pf, lds);
-        load_global(pf, off, rx, rw0, rw1, kt_begin + 1);       // past kt_end: reads as zero
-        __syncthreads();
-        constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);   // LDS reads per substep
-        constexpr int MFMAS = FN * FM;
-        Frags fr[2];
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            const int cur = (kt - kt_begin) & 1;
-            const uint8_t *stage = lds + cur * STAGE;
-            read_frags(fr[0], stage, wm, wn, lane, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int s = 0; s < SUBSTEPS; ++s) {
-                const bool mid = (s == SUBSTEPS / 2 - 1);
-                if (s + 1 < SUBSTEPS) read_frags(fr[(s + 1) & 1], stage, wm, wn, lane, s + 1);
-                if (mid) {
-                    store_lds(pf, lds + (cur ^ 1) * STAGE);
-                    load_global(pf, off, rx, rw0, rw1, kt + 2);
-                }
-                mfmas(fr[s & 1], acc);
-                // Scheduling recipe for this region: after each MFMA one LDS read of the next
-                // substep's fragments and, in the middle substep, one LDS write and one global
-                // load; whatever is left (address arithmetic, the plane merge) fills the gaps.
-                constexpr int kWrites = XP + (KIND == kNestedF16 ? 2 * WP4 : WP8);
-                constexpr int kLoads = XP + (KIND == kNestedF16 ? 2 * WP4 : WP8);
-#pragma unroll
-                for (int q = 0; q < MFMAS; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
-                    if (s + 1 < SUBSTEPS && q < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-                    if (mid && q < kWrites) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // DS write
-                    if (mid && q < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    // VMEM read
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            __syncthreads();
-        }
-
-        if (p.row_store && gridDim.y == 1) epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
-        else epilogue(p, acc, m0, n0, wm, wn, lane, split);
     }
 
     // Result tile through LDS: the MFMA layout leaves a lane with 4 consecutive outputs of one
@@ -781,16 +594,15 @@ struct LargeKernel {
     }
 };
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, bool DTL>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 large_gemm_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     typedef LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N> Kern;
-    if (DTL) Kern::run_dtl(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
-    else Kern::run(p, lds_raw);
+    Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
-struct LargeConfig { int tm, tn, split, waves, dtl; };
+struct LargeConfig { int tm, tn, split, waves; };
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -801,7 +613,6 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
     int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
     c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
-    c.dtl = t.large_dtl != 0 ? 1 : 0;
     c.split = 1;
     if (tiles < 256) {                                  // fewer tiles than CUs: split K
         int64_t s = (512 + tiles - 1) / tiles;
@@ -818,9 +629,9 @@ size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
     return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, bool DTL>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N, DTL>;
+    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N>;
     constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
@@ -833,12 +644,9 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.waves == 4 && c.dtl) launch_large_t<KIND, 256, 256, 2, 2, true>(p, grid, stream);
-    else if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2, false>(p, grid, stream);
-    else if (c.tm == 256 && c.dtl) launch_large_t<KIND, 256, 256, 2, 4, true>(p, grid, stream);
-    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4, false>(p, grid, stream);
-    else if (c.dtl) launch_large_t<KIND, 128, 128, 2, 4, true>(p, grid, stream);
-    else launch_large_t<KIND, 128, 128, 2, 4, false>(p, grid, stream);
+    if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
+    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
 }
 
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
@@ -853,6 +661,7 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.w_row_bytes = (kind == kPlainF16) ? 2 * a.ldw : a.K;
     p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
     p.k_bytes = (kind == kE4M3) ? (int)a.K : (int)(2 * a.K);
+    p.kblocks = (int)((a.K + 63) / 64);
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;
     p.tiles_m = (int)((a.M + c.tm - 1) / c.tm);

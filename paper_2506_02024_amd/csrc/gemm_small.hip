@@ -8,9 +8,11 @@
 // Weight rows are the MFMA "A" operand (lane l: row l%16 of a 16-row tile, K-group l/16),
 // tokens (MT tiles of 16) the "B" operand, so each lane ends up with 4 consecutive output
 // columns of one token: 8-byte stores of fp16.
-//   kPlainF16 : lane loads 32 B of FP16 weights             -> 2 x v_mfma_f32_16x16x32_f16
+//   kPlainF16 : lane loads 32 B of row-major FP16 weights    -> 2 x v_mfma_f32_16x16x32_f16
 //   kNestedF16: lane loads 16 B upper + 16 B lower, merges them (Sec. 4.2, Alg. 1) -> same
-//   kE4M3     : lane loads 32 B of E4M3 bytes (upper plane)  -> 1 x v_mfma_f32_16x16x128_f8f6f4
+//   kE4M3     : lane loads 2 x 16 B of E4M3 bytes (upper plane) -> 1 x v_mfma_f32_16x16x128_f8f6f4
+// The byte planes are stored in 1 KB blocks of 16 rows x 64 columns whose chunk order is the
+// lane order, so every plane load of a wave is one contiguous kilobyte.
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -58,11 +60,14 @@ __device__ __forceinline__ void load_w(WItem &r, __amdgpu_buffer_rsrc_t r0, __am
         r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, 0, 0);
         r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, 0, 0);
     } else if (KIND == kNestedF16) {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 64, 0, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 64, 0, 0);
+        // packed planes: one 1 KB block per K-step, lane l owns chunk l of it
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 1024, 0, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 1024, 0, 0);
     } else {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, 0, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, 0, 0);
+        // packed E4M3: a K-step of 128 is two blocks; the lane takes its chunk of each, so its
+        // 32 operand bytes are columns 16g..16g+15 of the first and of the second block
+        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 2048, 0, 0);
+        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 2048 + 1024, 0, 0);
     }
 }
 
@@ -72,9 +77,10 @@ __device__ __forceinline__ void load_x(u32x4 &xa, u32x4 &xb, const SmallParams &
     const u32x4 zero = {0u, 0u, 0u, 0u};
     bool row_ok = m < p.M;
     if (KIND == kE4M3) {
+        // same column order as the weight operand: 16 columns of each 64-column half
         const uint8_t *src = p.X + (int64_t)m * p.x_row_bytes + k;
         xa = (row_ok && k < p.K) ? *reinterpret_cast<const u32x4 *>(src) : zero;
-        xb = (row_ok && (k + 16) < p.K) ? *reinterpret_cast<const u32x4 *>(src + 16) : zero;
+        xb = (row_ok && (k + 64) < p.K) ? *reinterpret_cast<const u32x4 *>(src + 64) : zero;
     } else {
         const uint8_t *src = p.X + (int64_t)m * p.x_row_bytes + 2 * (int64_t)k;
         bool ok = row_ok && k < p.K;
@@ -151,7 +157,7 @@ small_gemm_kernel(SmallParams p) {
     const int r16 = lane & 15;
     const int slice = blockIdx.y;
     constexpr int KSTEP = StepK<KIND>::value;
-    constexpr int KLANE = KSTEP / 4;                  // K elements per lane per step
+    constexpr int KLANE = 16;                         // first column of lane group g within a step: 16*g
     const int tiles_total = (p.N + 15) >> 4;
     // a workgroup's tiles: a contiguous chunk (stride 1) or interleaved with the other
     // workgroups (stride gridDim.x), so that the chip sweeps the weights front to back
@@ -212,7 +218,8 @@ small_gemm_kernel(SmallParams p) {
         for (int s = 0; s < SPW; ++s)
 #pragma unroll
             for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
-        voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * (KIND == kPlainF16 ? 2u : 1u);
+        if (KIND == kPlainF16) voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * 2u;
+        else voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * 1024u;   // block column of the slice
         fetch(buf0, 0);
         // The scheduling barriers keep the compiler from sinking the look-ahead loads below the
         // multiplies (which would turn every wait into a full drain).  For odd T the last
@@ -395,7 +402,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
 bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
     // the weight array must be addressable with 32-bit byte offsets (a few tiles of slack)
     (void)M;
-    const int64_t row_bytes = (kind == kPlainF16) ? 2 * ldw : K;
+    const int64_t row_bytes = (kind == kPlainF16) ? 2 * ldw : ((K + 63) / 64) * 64;
     return (N + 48) * row_bytes < ((int64_t)1 << 32);
 }
 
@@ -440,8 +447,14 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.w_scale = a.w_scale;
     p.W0 = static_cast<const uint8_t *>(a.W0);
     p.W1 = static_cast<const uint8_t *>(a.W1);
-    p.w_row_bytes = (uint32_t)((kind == kPlainF16) ? 2 * a.ldw : a.K);
-    p.w_bytes = (uint32_t)((a.N - 1) * (int64_t)p.w_row_bytes + ((kind == kPlainF16) ? 2 * a.K : a.K));
+    if (kind == kPlainF16) {
+        p.w_row_bytes = (uint32_t)(2 * a.ldw);
+        p.w_bytes = (uint32_t)((a.N - 1) * (int64_t)p.w_row_bytes + 2 * a.K);
+    } else {
+        // packed planes: 16 rows of a tile take 16 * Kp contiguous bytes (Kp = K rounded up to 64)
+        p.w_row_bytes = (uint32_t)(((a.K + 63) / 64) * 64);
+        p.w_bytes = (uint32_t)plane_bytes(a.N, a.K);
+    }
     p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;

@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
     return t;
 }
 
@@ -103,7 +103,7 @@ using namespace nfp;
 
 extern "C" {
 
-int nestedfp_version(void) { return 100; }
+int nestedfp_version(void) { return 200; }
 
 const char *nestedfp_status_string(int status) {
     switch (status) {
@@ -171,6 +171,29 @@ int nestedfp_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, 
     if (st != kOk) return st;
     if (!aligned(upper, 16) || !aligned(lower, 16)) return NESTEDFP_ERR_SHAPE;
     return launch_reconstruct(upper, lower, N, K, W, ldw, static_cast<hipStream_t>(stream));
+}
+
+size_t nestedfp_plane_bytes(int64_t N, int64_t K) {
+    if (check_dims(0, N, K) != kOk) return 0;
+    return plane_bytes(N, K);
+}
+
+int nestedfp_pack_plane(const uint8_t *src, int64_t N, int64_t K, int64_t ld, uint8_t *dst, void *stream) {
+    int st = check_dims(0, N, K);
+    if (st != kOk) return st;
+    if (N == 0) return NESTEDFP_OK;
+    if (src == nullptr || dst == nullptr) return NESTEDFP_ERR_ARG;
+    if (ld < K || (ld & 15) != 0 || !aligned(src, 16) || !aligned(dst, 16)) return NESTEDFP_ERR_SHAPE;
+    return launch_pack_plane(src, N, K, ld, dst, static_cast<hipStream_t>(stream));
+}
+
+int nestedfp_unpack_plane(const uint8_t *src, int64_t N, int64_t K, uint8_t *dst, int64_t ld, void *stream) {
+    int st = check_dims(0, N, K);
+    if (st != kOk) return st;
+    if (N == 0) return NESTEDFP_OK;
+    if (src == nullptr || dst == nullptr) return NESTEDFP_ERR_ARG;
+    if (ld < K || (ld & 15) != 0 || !aligned(src, 16) || !aligned(dst, 16)) return NESTEDFP_ERR_SHAPE;
+    return launch_unpack_plane(src, N, K, dst, ld, static_cast<hipStream_t>(stream));
 }
 
 int nestedfp_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const float *static_scale,
@@ -287,7 +310,7 @@ int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64
 }
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
-                                     "large_split", "large_bm", "large_waves", "large_dtl", "large_epilogue", "quant_hw",
+                                     "large_split", "large_bm", "large_waves", "large_epilogue", "quant_hw",
                                      nullptr};
 
 const char *nestedfp_tune_name(int index) {
@@ -307,7 +330,6 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "large_split")) t.large_split = value;
     else if (!strcmp(knob, "large_bm")) t.large_bm = value;
     else if (!strcmp(knob, "large_waves")) t.large_waves = value;
-    else if (!strcmp(knob, "large_dtl")) t.large_dtl = value;
     else if (!strcmp(knob, "large_epilogue")) t.large_epilogue = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;
     else return NESTEDFP_ERR_ARG;

@@ -41,7 +41,6 @@ struct Tuning {
     int64_t large_split;     // grid-level split-K of the tiled kernel
     int64_t large_bm;        // tile height of the tiled kernel
     int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
-    int64_t large_dtl;       // 0: stage tiles through registers instead of direct-to-LDS loads
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
 };
@@ -54,6 +53,9 @@ int launch_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uin
 int launch_zero_u64(uint64_t *p, hipStream_t stream);
 int launch_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
                        uint16_t *W, int64_t ldw, hipStream_t stream);
+size_t plane_bytes(int64_t N, int64_t K);
+int launch_pack_plane(const uint8_t *src, int64_t N, int64_t K, int64_t ld, uint8_t *dst, hipStream_t stream);
+int launch_unpack_plane(const uint8_t *src, int64_t N, int64_t K, uint8_t *dst, int64_t ld, hipStream_t stream);
 int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                         const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream);
 

@@ -8,11 +8,25 @@ namespace nfp {
 
 constexpr int kPlaneThreads = 256;
 
-// chunk c (16 weights) -> (row, first column)
-struct ChunkMap {
-    int64_t chunks_per_row;   // K / 16
-    int64_t total;            // N * K / 16
+// Packed plane layout: a plane of an [N,K] byte matrix is a sequence of 1 KB blocks, one per
+// 16-row x 64-column sub-matrix, block (i,j) at ((i * kblocks) + j) * 1024.  Inside a block
+// the 16-byte chunk of row r (0..15), column group g (0..3) sits at chunk index r + 16*g:
+// exactly the order in which the 64 lanes of a wave hold an MFMA operand (row = lane % 16,
+// K group = lane / 16), so one 128-bit load per lane reads the block front to back.
+// Rows past N and columns past K are stored as zeros.
+struct BlockMap {
+    int64_t N, K;
+    int64_t kblocks;          // ceil(K / 64)
+    int64_t blocks;           // ceil(N / 16) * kblocks
 };
+
+static BlockMap block_map(int64_t N, int64_t K) {
+    BlockMap m;
+    m.N = N;  m.K = K;
+    m.kblocks = (K + 63) / 64;
+    m.blocks = ((N + 15) / 16) * m.kblocks;
+    return m;
+}
 
 __device__ __forceinline__ void add_count(uint64_t *counter, uint32_t bad) {
     // wave reduction, then one vector atomic per wave
@@ -21,37 +35,64 @@ __device__ __forceinline__ void add_count(uint64_t *counter, uint32_t bad) {
         atomicAdd(reinterpret_cast<unsigned long long *>(counter), (unsigned long long)bad);
 }
 
+// One wave per block and trip: lane l owns chunk l of the block, i.e. row 16*i + l%16 and
+// columns 64*j + 16*(l/16) .. +15 of the matrix.
+struct LaneChunk {
+    int64_t row, col;
+    int64_t offset;           // byte offset of the chunk in the packed plane
+    bool inside;
+};
+
+__device__ __forceinline__ LaneChunk lane_chunk(const BlockMap &m, int64_t block, int lane) {
+    LaneChunk c;
+    const int64_t i = block / m.kblocks, j = block - i * m.kblocks;
+    c.row = 16 * i + (lane & 15);
+    c.col = 64 * j + 16 * (lane >> 4);
+    c.offset = block * 1024 + lane * 16;
+    c.inside = c.row < m.N && c.col < m.K;
+    return c;
+}
+
 __global__ void __launch_bounds__(kPlaneThreads)
-decompose_kernel(const uint16_t *__restrict__ W, int64_t ldw, ChunkMap map,
+decompose_kernel(const uint16_t *__restrict__ W, int64_t ldw, BlockMap map,
                  uint8_t *__restrict__ upper, uint8_t *__restrict__ lower,
                  uint64_t *__restrict__ counter) {
     uint32_t bad = 0;
-    const int64_t stride = (int64_t)gridDim.x * kPlaneThreads;
-    for (int64_t c = (int64_t)blockIdx.x * kPlaneThreads + threadIdx.x; c < map.total; c += stride) {
-        int64_t row = c / map.chunks_per_row;
-        int64_t col = (c - row * map.chunks_per_row) * 16;
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(W + row * ldw + col);
-        u32x4 a = __builtin_nontemporal_load(src);
-        u32x4 b = __builtin_nontemporal_load(src + 1);
-        uint32_t u[8], l[8];
-        decompose2(a.x, u[0], l[0], bad);
-        decompose2(a.y, u[1], l[1], bad);
-        decompose2(a.z, u[2], l[2], bad);
-        decompose2(a.w, u[3], l[3], bad);
-        decompose2(b.x, u[4], l[4], bad);
-        decompose2(b.y, u[5], l[5], bad);
-        decompose2(b.z, u[6], l[6], bad);
-        decompose2(b.w, u[7], l[7], bad);
-        u32x4 up, lo;
-        up.x = pack_even_bytes(u[0], u[1]);  lo.x = pack_even_bytes(l[0], l[1]);
-        up.y = pack_even_bytes(u[2], u[3]);  lo.y = pack_even_bytes(l[2], l[3]);
-        up.z = pack_even_bytes(u[4], u[5]);  lo.z = pack_even_bytes(l[4], l[5]);
-        up.w = pack_even_bytes(u[6], u[7]);  lo.w = pack_even_bytes(l[6], l[7]);
-        __builtin_nontemporal_store(up, reinterpret_cast<u32x4 *>(upper + c * 16));
-        __builtin_nontemporal_store(lo, reinterpret_cast<u32x4 *>(lower + c * 16));
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kPlaneThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPlaneThreads) >> 6;
+    for (int64_t blk = wave; blk < map.blocks; blk += waves) {
+        const LaneChunk c = lane_chunk(map, blk, lane);
+        u32x4 up = {0, 0, 0, 0}, lo = {0, 0, 0, 0};
+        if (c.inside) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(W + c.row * ldw + c.col);
+            u32x4 a = __builtin_nontemporal_load(src);
+            u32x4 b = __builtin_nontemporal_load(src + 1);
+            uint32_t u[8], l[8];
+            decompose2(a.x, u[0], l[0], bad);
+            decompose2(a.y, u[1], l[1], bad);
+            decompose2(a.z, u[2], l[2], bad);
+            decompose2(a.w, u[3], l[3], bad);
+            decompose2(b.x, u[4], l[4], bad);
+            decompose2(b.y, u[5], l[5], bad);
+            decompose2(b.z, u[6], l[6], bad);
+            decompose2(b.w, u[7], l[7], bad);
+            up.x = pack_even_bytes(u[0], u[1]);  lo.x = pack_even_bytes(l[0], l[1]);
+            up.y = pack_even_bytes(u[2], u[3]);  lo.y = pack_even_bytes(l[2], l[3]);
+            up.z = pack_even_bytes(u[4], u[5]);  lo.z = pack_even_bytes(l[4], l[5]);
+            up.w = pack_even_bytes(u[6], u[7]);  lo.w = pack_even_bytes(l[6], l[7]);
+        }
+        __builtin_nontemporal_store(up, reinterpret_cast<u32x4 *>(upper + c.offset));
+        __builtin_nontemporal_store(lo, reinterpret_cast<u32x4 *>(lower + c.offset));
     }
     if (counter) add_count(counter, bad);
 }
+
+// chunk c (16 weights) of a row-major matrix -> (row, first column)
+struct ChunkMap {
+    int64_t chunks_per_row;   // K / 16
+    int64_t total;            // N * K / 16
+};
 
 __global__ void __launch_bounds__(kPlaneThreads)
 range_check_kernel(const uint16_t *__restrict__ W, int64_t ldw, ChunkMap map,
@@ -76,18 +117,40 @@ range_check_kernel(const uint16_t *__restrict__ W, int64_t ldw, ChunkMap map,
 
 __global__ void __launch_bounds__(kPlaneThreads)
 reconstruct_kernel(const uint8_t *__restrict__ upper, const uint8_t *__restrict__ lower,
-                   ChunkMap map, uint16_t *__restrict__ W, int64_t ldw) {
-    const int64_t stride = (int64_t)gridDim.x * kPlaneThreads;
-    for (int64_t c = (int64_t)blockIdx.x * kPlaneThreads + threadIdx.x; c < map.total; c += stride) {
-        u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(upper + c * 16));
-        u32x4 l = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(lower + c * 16));
+                   BlockMap map, uint16_t *__restrict__ W, int64_t ldw) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kPlaneThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPlaneThreads) >> 6;
+    for (int64_t blk = wave; blk < map.blocks; blk += waves) {
+        const LaneChunk c = lane_chunk(map, blk, lane);
+        if (!c.inside) continue;
+        u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(upper + c.offset));
+        u32x4 l = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(lower + c.offset));
         u32x4 w0, w1;
         merge16(u, l, w0, w1);
-        int64_t row = c / map.chunks_per_row;
-        int64_t col = (c - row * map.chunks_per_row) * 16;
-        u32x4 *dst = reinterpret_cast<u32x4 *>(W + row * ldw + col);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(W + c.row * ldw + c.col);
         __builtin_nontemporal_store(w0, dst);
         __builtin_nontemporal_store(w1, dst + 1);
+    }
+}
+
+// Row-major bytes <-> packed plane (for E4M3 weights that do not come from a decomposition,
+// and for reading a plane back in matrix order).
+template <bool PACK>
+__global__ void __launch_bounds__(kPlaneThreads)
+repack_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst, int64_t ld, BlockMap map) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kPlaneThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPlaneThreads) >> 6;
+    for (int64_t blk = wave; blk < map.blocks; blk += waves) {
+        const LaneChunk c = lane_chunk(map, blk, lane);
+        if (PACK) {
+            u32x4 v = {0, 0, 0, 0};
+            if (c.inside) v = *reinterpret_cast<const u32x4 *>(src + c.row * ld + c.col);
+            *reinterpret_cast<u32x4 *>(dst + c.offset) = v;
+        } else if (c.inside) {
+            *reinterpret_cast<u32x4 *>(dst + c.row * ld + c.col) = *reinterpret_cast<const u32x4 *>(src + c.offset);
+        }
     }
 }
 
@@ -106,12 +169,16 @@ static int plane_grid(int64_t total_chunks) {
     return (int)(blocks > 0x7fffffff ? 0x7fffffff : blocks);
 }
 
+size_t plane_bytes(int64_t N, int64_t K) {
+    return (size_t)(((N + 15) / 16) * 16) * (size_t)(((K + 63) / 64) * 64);
+}
+
 int launch_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *upper,
                      uint8_t *lower, uint64_t *counter, hipStream_t stream) {
-    ChunkMap map{K / 16, N * (K / 16)};
+    BlockMap map = block_map(N, K);
     if (counter) zero_u64_kernel<<<1, 1, 0, stream>>>(counter);
-    decompose_kernel<<<plane_grid(map.total), kPlaneThreads, 0, stream>>>(W, ldw, map, upper, lower,
-                                                                         counter);
+    decompose_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(W, ldw, map, upper, lower,
+                                                                              counter);
     return hip_ok(hipGetLastError());
 }
 
@@ -125,8 +192,20 @@ int launch_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uin
 
 int launch_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
                        uint16_t *W, int64_t ldw, hipStream_t stream) {
-    ChunkMap map{K / 16, N * (K / 16)};
-    reconstruct_kernel<<<plane_grid(map.total), kPlaneThreads, 0, stream>>>(upper, lower, map, W, ldw);
+    BlockMap map = block_map(N, K);
+    reconstruct_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(upper, lower, map, W, ldw);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_pack_plane(const uint8_t *src, int64_t N, int64_t K, int64_t ld, uint8_t *dst, hipStream_t stream) {
+    BlockMap map = block_map(N, K);
+    repack_kernel<true><<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(src, dst, ld, map);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_unpack_plane(const uint8_t *src, int64_t N, int64_t K, uint8_t *dst, int64_t ld, hipStream_t stream) {
+    BlockMap map = block_map(N, K);
+    repack_kernel<false><<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(src, dst, ld, map);
     return hip_ok(hipGetLastError());
 }
 

@@ -34,3 +34,25 @@ def to_dev(a, device="cuda:0"):
 def bits(t):
     """uint16 numpy view of an fp16 torch tensor."""
     return t.detach().cpu().contiguous().numpy().view(np.uint16)
+
+
+def pack_plane_ref(a):
+    """Packed plane storage written out from its definition: 1 KB blocks of 16 rows x 64
+    columns, block (i, j) at (i * Kp/64 + j) * 1024, 16-byte chunk of row r, column group g
+    at chunk index r + 16 g; rows and columns past the matrix are zero."""
+    a = np.asarray(a, dtype=np.uint8)
+    N, K = a.shape
+    Np, Kp = -(-N // 16) * 16, -(-K // 64) * 64
+    p = np.zeros((Np, Kp), dtype=np.uint8)
+    p[:N, :K] = a
+    p = p.reshape(Np // 16, 16, Kp // 64, 4, 16)        # i, r, j, g, byte
+    return np.ascontiguousarray(p.transpose(0, 2, 3, 1, 4)).reshape(-1)
+
+
+def assert_plane_equal(plane, ref):
+    """plane: PackedPlane from the library; ref: row-major uint8 [N,K] from the oracle.
+    Checks the raw packed bytes (padding included) and the library's own unpacking."""
+    want = pack_plane_ref(ref)
+    got = plane.data[:want.size].cpu().numpy()
+    assert np.array_equal(got, want)
+    assert np.array_equal(plane.unpack().cpu().numpy(), np.asarray(ref, dtype=np.uint8))

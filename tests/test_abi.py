@@ -93,3 +93,17 @@ def test_argument_errors_are_reported_before_any_launch(L):
         names.append(L.nestedfp_tune_name(i).decode())
         i += 1
     assert "small_split" in names and "large_bm" in names
+
+
+def test_plane_bytes_is_the_padded_block_count(L):
+    L.nestedfp_plane_bytes.restype = ctypes.c_size_t
+    L.nestedfp_plane_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    # 1 KB per 16-row x 64-column block, rows rounded up to 16 and columns to 64
+    assert L.nestedfp_plane_bytes(16, 64) == 1024
+    assert L.nestedfp_plane_bytes(17, 64) == 2048
+    assert L.nestedfp_plane_bytes(16, 80) == 2048
+    assert L.nestedfp_plane_bytes(4096, 4096) == 4096 * 4096
+    assert L.nestedfp_plane_bytes(300, 1040) == 304 * 1088
+    assert L.nestedfp_plane_bytes(8, 24) == 0          # K must be a multiple of 16
+    assert L.nestedfp_plane_bytes(-1, 64) == 0
+

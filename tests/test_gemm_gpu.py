@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2506_02024_amd import workloads
-from helpers import assert_gemm_close, bits, to_dev
+from helpers import assert_gemm_close, assert_plane_equal, bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -23,7 +23,8 @@ def run_both_modes(nfp, X, W, what, check_plain=True):
     up, lo = nfp.decompose(Wd)
     up_ref, lo_ref, bad = oracle.decompose(W)
     assert bad == 0
-    assert np.array_equal(up.cpu().numpy(), up_ref) and np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
     # FP16 mode
     y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
     ref16 = oracle.gemm_fp16(X, W)
@@ -151,7 +152,8 @@ def test_fp8_mode_never_reads_the_lower_plane(nfp):
     for M in (8, 200):
         X = to_dev(workloads.act_host(M, 512, seed=6))
         a = nfp.gemm(X, up, None, nfp.MODE_FP8)
-        b = nfp.gemm(X, up, torch.full_like(lo, 0xAB), nfp.MODE_FP8)
+        junk = nfp.PackedPlane(lo.N, lo.K, data=torch.full_like(lo.data, 0xAB))
+        b = nfp.gemm(X, up, junk, nfp.MODE_FP8)
         assert np.array_equal(bits(a), bits(b))
     with pytest.raises(nfp.NestedFPError):
         nfp.gemm(X, up, None, nfp.MODE_FP16)
@@ -211,7 +213,7 @@ def test_mode_switch_keeps_planes_and_memory(nfp):
     out = torch.empty((64, 512), dtype=torch.float16, device="cuda:0")
     ws = torch.empty(max(nfp.gemm_workspace_size(64, 512, 1024, m) for m in (0, 1)), dtype=torch.uint8,
                      device="cuda:0")
-    snap = [(u.clone(), l.clone()) for u, l in layers]
+    snap = [(u.data.clone(), l.data.clone()) for u, l in layers]
     ptrs = [(u.data_ptr(), l.data_ptr()) for u, l in layers]
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
@@ -223,7 +225,7 @@ def test_mode_switch_keeps_planes_and_memory(nfp):
     assert torch.cuda.memory_allocated() == before
     assert ptrs == [(u.data_ptr(), l.data_ptr()) for u, l in layers]
     for (u, l), (su, sl) in zip(layers, snap):
-        assert torch.equal(u, su) and torch.equal(l, sl)
+        assert torch.equal(u.data, su) and torch.equal(l.data, sl)
 
 
 @pytest.mark.parametrize("name,M", [("qkv", 16), ("down", 4), ("o", 64), ("gate_up", 1)])
@@ -253,7 +255,7 @@ def test_llama8b_prefill_shapes_sampled(nfp, name, M):
     assert_gemm_close(got16, ref16, "%s M=%d FP16 sample" % (name, M))
     up_s, _, bad = oracle.decompose(Ws)
     assert bad == 0
-    assert np.array_equal(up[torch.from_numpy(cols).cuda()].cpu().numpy(), up_s)
+    assert np.array_equal(up.unpack()[torch.from_numpy(cols).cuda()].cpu().numpy(), up_s)
     Xq, s = oracle.quantize_act(Xs)
     ref8 = oracle.gemm_fp8(Xq, s, up_s)
     got8 = y8[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
@@ -273,7 +275,7 @@ def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
     Xs, Ws = Xd[ri].cpu().numpy(), Wd[ci].cpu().numpy()
     up_s, lo_s, bad = oracle.decompose(Ws)
     assert bad == 0
-    assert np.array_equal(up[ci].cpu().numpy(), up_s) and np.array_equal(lo[ci].cpu().numpy(), lo_s)
+    assert np.array_equal(up.unpack()[ci].cpu().numpy(), up_s) and np.array_equal(lo.unpack()[ci].cpu().numpy(), lo_s)
     assert_gemm_close(y16[ri][:, ci].cpu().numpy(), oracle.gemm_fp16(Xs, Ws), tag + " FP16 sample")
     Xq, s = oracle.quantize_act(Xs)
     assert_gemm_close(y8[ri][:, ci].cpu().numpy(), oracle.gemm_fp8(Xq, s, up_s), tag + " FP8 sample")

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2506_02024_amd import workloads
-from helpers import bits, to_dev
+from helpers import assert_plane_equal, bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -26,8 +26,8 @@ def test_exhaustive_fp16_words(nfp):
     up, lo, bad = nfp.decompose_count(Wd)
     assert bad == bad_ref
     assert nfp.range_check(Wd) == bad_ref
-    assert np.array_equal(up.cpu().numpy(), up_ref)
-    assert np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
     with pytest.raises(nfp.NestedFPError) as e:
         nfp.decompose(Wd)
     assert e.value.status == nfp.ERR_RANGE
@@ -48,8 +48,8 @@ def test_in_range_words_only_pass_the_check(nfp):
     up, lo = nfp.decompose(Wd)
     up_ref, lo_ref, bad = oracle.decompose(good)
     assert bad == 0
-    assert np.array_equal(up.cpu().numpy(), up_ref)
-    assert np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
     assert np.array_equal(bits(nfp.reconstruct(up, lo)), good)
 
 
@@ -60,8 +60,8 @@ def test_gaussian_layers(nfp, N, K):
     up, lo = nfp.decompose(Wd)
     up_ref, lo_ref, bad = oracle.decompose(W)
     assert bad == 0
-    assert np.array_equal(up.cpu().numpy(), up_ref)
-    assert np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
     back = nfp.reconstruct(up, lo)
     assert np.array_equal(bits(back), W.view(np.uint16))
 
@@ -73,8 +73,8 @@ def test_strided_weight_rows(nfp):
     assert Wd.stride(0) == ld
     up, lo = nfp.decompose(Wd)
     up_ref, lo_ref, _ = oracle.decompose(big[:, :K])
-    assert np.array_equal(up.cpu().numpy(), up_ref)
-    assert np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
     out = torch.full((N, ld), -1.0, dtype=torch.float16, device="cuda:0")
     nfp.reconstruct(up, lo, out=out[:, :K])
     got = bits(out)
@@ -95,8 +95,8 @@ def test_planted_outliers_are_counted(nfp):
     up, lo, bad = nfp.decompose_count(Wd)
     assert bad == 4
     up_ref, lo_ref, _ = oracle.decompose(W)
-    assert np.array_equal(up.cpu().numpy(), up_ref)
-    assert np.array_equal(lo.cpu().numpy(), lo_ref)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
 
 
 def test_empty_layer(nfp):
