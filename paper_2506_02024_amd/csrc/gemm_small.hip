@@ -217,7 +217,11 @@ small_gemm_kernel(SmallParams p) {
 #pragma unroll
         for (int s = 0; s < SPW; ++s)
 #pragma unroll
+#ifdef NFP_X_NOX
+            for (int i = 0; i < MT; ++i) { xa[s][i] = u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, (uint32_t)p.M};  xb[s][i] = xa[s][i]; }
+#else
             for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
+#endif
         if (KIND == kPlainF16) voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * 2u;
         else voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * 1024u;   // block column of the slice
         fetch(buf0, 0);
@@ -366,7 +370,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     // otherwise 4, or 2 if that still lets one workgroup cover all of K
     c.spw = 4;
     if ((steps + 3) / 4 < 16 && steps >= 2) c.spw = 2;
-    if (tiles >= 1024) c.spw = 2;
+    if (tiles >= 1024 && kind != kNestedF16) c.spw = 2;
     if ((t.small_spw == 2 || t.small_spw == 4)) c.spw = (int)t.small_spw;
     if (c.mt > 1) c.spw = 2;
     const int slices = (steps + c.spw - 1) / c.spw;               // wave-sized K slices
@@ -379,6 +383,9 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const int64_t wg_target = (kind == kE4M3 && rounds == 1) ? 512 : 1024;
     int split = 1;
     while (split < 8 && tiles * (split * 2) <= wg_target) split *= 2;
+    // measured with packed planes: a single token tile whose K fits one pass is as fast
+    // unsplit once there is a tile per CU, and saves the reduction launch
+    if (c.mt == 1 && rounds == 1 && tiles >= 256) split = 1;
     if (t.small_split > 0) split = (int)t.small_split;
     if (split > slices) split = slices;
     c.split = split;
