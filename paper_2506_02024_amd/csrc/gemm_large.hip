@@ -4,15 +4,15 @@
 // the tensor-core instruction of every warp and hides it with a third pipeline stage.
 // Here the planes are merged ONCE per workgroup on their way from HBM to LDS
 // (global -> VGPR -> Alg. 1 -> ds_write of finished FP16), so the MFMA loop that follows
-// is the plain FP16 loop and the merge costs ~2 VALU ops per weight per workgroup instead
-// of per wave.  Global loads for K-tile t+1 are issued before the MFMAs of K-tile t
-// (register prefetch) and land in the other half of a double-buffered LDS tile.
+// is the plain FP16 loop and the merge costs 2 VALU ops per weight per workgroup instead
+// of per wave.
 //
 // Tile: TM tokens x TN weight rows x 128 bytes of K per row (64 halves or 128 E4M3 bytes),
-// 8 waves as 2 (tokens) x 4 (weight rows).  Weight rows are the MFMA "A" operand and
-// tokens the "B" operand, so a lane holds 4 consecutive output columns of one token.
-// LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with the row so that
-// both the 128-bit writes and the MFMA-fragment reads are free of bank conflicts.
+// two LDS stages, 8 waves as 2 (tokens) x 4 (weight rows).  Weight rows are the MFMA "A"
+// operand and tokens the "B" operand, so a lane holds 4 consecutive output columns of one
+// token.  Tokens and plain / E4M3 weights reach LDS by direct-to-LDS buffer loads; FP16 rows
+// are 128 bytes with the 16-byte chunk index XOR-swizzled with the row so that the MFMA
+// fragment reads are free of bank conflicts, packed E4M3 blocks are copied as they are.
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -133,7 +133,9 @@ struct LargeKernel {
     static constexpr bool kTwoRoles = WAVES != DW;
     // The planes are loaded, merged and written to LDS 16 weights (16 bytes of each plane, two
     // FP16 chunks) at a time; a weight row is four such pieces.  A group of 256 threads takes
-    // 64 rows per pass.  With two waves per SIMD the older waves have time to spare (see DW)
+    // 64 rows per pass; within a wave lane l takes row l % 16, column group l / 16 of a 16-row
+    // tile: the chunk order of the packed blocks, and 16 consecutive lanes then write one
+    // chunk column of 16 consecutive rows, the bank pattern of the fragment reads.  With two waves per SIMD the older waves have time to spare (see DW)
     // and take three passes out of four.
     static constexpr int PASSES = TN / 64;             // 64-row passes over the weight tile
     static constexpr int NP_OLD = kTwoRoles ? (3 * PASSES + 3) / 4 : PASSES;
@@ -256,7 +258,7 @@ struct LargeKernel {
         if constexpr ((J & 1) == 1) {
             // two quarters = one 16-byte FP16 chunk of the row
             const int t = threadIdx.x;
-            const int c4 = t & 3, row = (EARLY ? 0 : 64 * NP_OLD) + ((t & 255) >> 2) + 64 * I;
+            const int c4 = (t >> 4) & 3, row = (EARLY ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15) + 64 * I;
             uint8_t *stage = c.lds + (EARLY ? c.cur : c.cur ^ 1) * STAGE;
             *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + (J >> 1))) = c.merged;
         }
@@ -281,7 +283,7 @@ struct LargeKernel {
     static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p) {
         constexpr int NP = OLDER ? NP_OLD : NP_YNG;
         const int t = threadIdx.x;
-        const int c4 = t & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + ((t & 255) >> 2);
+        const int c4 = (t >> 4) & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15);
         // packed planes: the 16 weights of row r, column group c4 of K-tile kt are chunk
         // (r % 16) + 16 * c4 of block (r / 16, kt); a wave reads whole 1 KB blocks
 #pragma unroll
@@ -310,7 +312,7 @@ struct LargeKernel {
     static __device__ __forceinline__ void store_planes(const PlaneRegs &pf, uint8_t *stage) {
         constexpr int NP = OLDER ? NP_OLD : NP_YNG;
         const int t = threadIdx.x;
-        const int c4 = t & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + ((t & 255) >> 2);
+        const int c4 = (t >> 4) & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15);
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int row = r0 + 64 * i;
