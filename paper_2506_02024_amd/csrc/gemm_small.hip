@@ -217,11 +217,7 @@ small_gemm_kernel(SmallParams p) {
 #pragma unroll
         for (int s = 0; s < SPW; ++s)
 #pragma unroll
-#ifdef NFP_X_NOX
-            for (int i = 0; i < MT; ++i) { xa[s][i] = u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, (uint32_t)p.M};  xb[s][i] = xa[s][i]; }
-#else
             for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
-#endif
         if (KIND == kPlainF16) voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * 2u;
         else voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * 1024u;   // block column of the slice
         fetch(buf0, 0);
