@@ -37,6 +37,15 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the compute-bound extras")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--sweep-70b", action="store_true",
+                    help="extra: roofline curve on the Llama-3-70B shapes, M = 1 ... 8192 (configs[3])")
+    ap.add_argument("--mode-switch", action="store_true",
+                    help="extra: per-step mode switching on the stack at M = 64 and 2048 (configs[4])")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="extra: FP16-mode overhead over the plain FP16 GEMM on the shapes of the "
+                         "paper's kernel benchmark, M = 32 ... 2048 step 32")
+    ap.add_argument("--switch-demo", action="store_true",
+                    help="extra: token-count threshold switching over a synthetic bursty arrival sequence")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB elementwise copy (known traffic) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
@@ -234,7 +243,17 @@ def main():
     if not args.no_prefill:
         del replay, legs
         extra["prefill"] = prefill_extras(torch, nfp, workloads, planes, plain_w, dev)
-    del plain_w
+    if args.mode_switch:
+        extra["mode_switch_steps"] = mode_switch_extras(torch, nfp, workloads, planes, dev)
+    if args.switch_demo:
+        extra["switch_demo"] = switch_demo_extras(torch, nfp, workloads, planes, dev)
+    del plain_w, planes
+    torch.cuda.empty_cache()
+    if args.sweep_70b:
+        extra["sweep_70b"] = sweep_extras(torch, nfp, workloads, dev, workloads.LLAMA3_70B.items(),
+                                          workloads.SIGMA_W_70B, [1 << i for i in range(14)])
+    if args.paper_shapes:
+        extra["paper_shapes"] = paper_shape_extras(torch, nfp, workloads, dev)
 
     cpu = None if args.no_cpu else cpu_baseline(workloads, M)
 
@@ -322,6 +341,169 @@ def prefill_extras(torch, nfp, workloads, planes, plain_w, dev):
             del X, Yb, ws
         out["M=%d" % M] = row
     return out
+
+
+def _time(torch, call, budget_s=0.03, max_reps=64):
+    """Seconds per call: two warm-up calls, then enough back-to-back calls for ~budget_s."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    call(0)
+    torch.cuda.synchronize()
+    a.record()
+    call(1)
+    b.record()
+    torch.cuda.synchronize()
+    one = max(a.elapsed_time(b) * 1e-3, 1e-6)
+    reps = int(min(max_reps, max(3, budget_s / one)))
+    a.record()
+    for i in range(reps):
+        call(2 + i)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / reps
+
+
+def _layer_copies(torch, nfp, workloads, N, K, sigma, dev, seed0):
+    """Enough copies of one layer that neither L2 nor the 256 MB cache can serve the weights."""
+    copies = int(min(8, max(2, -(-600e6 // (2 * N * K)))))
+    Ws = [workloads.weight_device(N, K, sigma, seed=seed0 + i) for i in range(copies)]
+    return Ws, [nfp.decompose(W, check=(i == 0)) for i, W in enumerate(Ws)]
+
+
+def sweep_extras(torch, nfp, workloads, dev, shapes, sigma, Ms):
+    """Roofline curve: both modes and the plain FP16 baseline over M on each shape; the bound of
+    a point is max(algorithmic bytes / 8 TB/s, flops / MFMA peak of the mode)."""
+    out = {}
+    for j, (name, (N, K)) in enumerate(shapes):
+        Ws, planes = _layer_copies(torch, nfp, workloads, N, K, sigma, dev, 300 + 10 * j)
+        R = len(Ws)
+        row = {}
+        for M in Ms:
+            X = workloads.act_device(M, K, seed=90 + j)
+            Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256,
+                             dtype=torch.uint8, device=dev)
+            t16 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], planes[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws))
+            t8 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], None, nfp.MODE_FP8, out=Y, workspace=ws))
+            tp = _time(torch, lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws))
+            fl = 2.0 * M * N * K
+            lb16 = max(gemm_bytes(M, N, K, "fp16") / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_PEAK_TFLOPS["fp16"] * 1e12))
+            lb8 = max(gemm_bytes(M, N, K, "fp8") / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_PEAK_TFLOPS["fp8"] * 1e12))
+            row["M=%d" % M] = {
+                "fp16_us": t16 * 1e6, "fp8_us": t8 * 1e6, "plain_fp16_us": tp * 1e6,
+                "fp16_GBps": gemm_bytes(M, N, K, "fp16") / t16 / 1e9, "fp8_GBps": gemm_bytes(M, N, K, "fp8") / t8 / 1e9,
+                "fp16_TFLOPs": fl / t16 / 1e12, "fp8_TFLOPs": fl / t8 / 1e12,
+                "fp16_frac_roofline": lb16 / t16, "fp8_frac_roofline": lb8 / t8,
+                "fp16_vs_plain": tp / t16}
+            del X, Y, ws
+        out["%s (%d,%d)" % (name, N, K)] = row
+        del Ws, planes
+        torch.cuda.empty_cache()
+    return out
+
+
+def paper_shape_extras(torch, nfp, workloads, dev):
+    """Sec. 5.2 / App. C of the paper sweep M = 32 ... 2048 in steps of 32 on four (N,K) shapes
+    and quote the mean slowdown of FP16 mode against a plain FP16 GEMM; same sweep here."""
+    out = {}
+    for j, (N, K) in enumerate(workloads.PAPER_KERNEL_SHAPES):
+        Ws, planes = _layer_copies(torch, nfp, workloads, N, K, workloads.SIGMA_W_8B, dev, 500 + 10 * j)
+        R = len(Ws)
+        over = []
+        for M in range(32, 2049, 32):
+            X = workloads.act_device(M, K, seed=95 + j)
+            Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            ws = torch.empty(nfp.gemm_workspace_size(M, N, K, 0) + 256, dtype=torch.uint8, device=dev)
+            t16 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], planes[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws), 0.01, 16)
+            tp = _time(torch, lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws), 0.01, 16)
+            over.append((M, t16 / tp - 1.0, 2.0 * M * N * K / t16 / 1e12))
+            del X, Y, ws
+        o = [x[1] for x in over]
+        big = [x[1] for x in over if x[0] > 64]
+        out["(%d,%d)" % (N, K)] = {
+            "mean_overhead": sum(o) / len(o), "min_overhead": min(o), "max_overhead": max(o),
+            "mean_overhead_tiled_kernel_M>64": sum(big) / len(big),
+            "fp16_TFLOPs_at_M=2048": over[-1][2],
+            "overhead_at": {"M=%d" % m: ov for m, ov, _ in over if m in (32, 64, 128, 256, 512, 1024, 2048)}}
+        del Ws, planes
+        torch.cuda.empty_cache()
+    return out
+
+
+def _run_stack(nfp, planes, X, Y, ws, mode):
+    for name, up, lo in planes:
+        nfp.gemm(X[name], up, None if mode == nfp.MODE_FP8 else lo, mode, out=Y[name], workspace=ws)
+
+
+def _stack_buffers(torch, nfp, workloads, M, dev):
+    shapes = workloads.LLAMA3_8B
+    X = {n: workloads.act_device(M, shapes[n][1], seed=60 + j) for j, n in enumerate(shapes)}
+    Y = {n: torch.empty((M, shapes[n][0]), dtype=torch.float16, device=dev) for n in shapes}
+    need = max(nfp.gemm_workspace_size(M, N, K, m) for (N, K) in shapes.values() for m in (0, 1))
+    return X, Y, torch.empty(need + 256, dtype=torch.uint8, device=dev)
+
+
+def mode_switch_extras(torch, nfp, workloads, planes, dev):
+    """Sec. 5.4: the mode is chosen per iteration.  64 steps over the whole stack, the mode
+    flipping every 8 steps, at M = 64 and M = 2048: step time by mode, the first step after a
+    flip against the steady state, allocated device memory before and after."""
+    out = {}
+    for M in (64, 2048):
+        X, Y, ws = _stack_buffers(torch, nfp, workloads, M, dev)
+        for mode in (nfp.MODE_FP16, nfp.MODE_FP8):
+            _run_stack(nfp, planes, X, Y, ws, mode)
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(65)]
+        modes = []
+        ev[0].record()
+        for step in range(64):
+            mode = nfp.MODE_FP8 if (step // 8) % 2 else nfp.MODE_FP16
+            modes.append(mode)
+            _run_stack(nfp, planes, X, Y, ws, mode)
+            ev[step + 1].record()
+        torch.cuda.synchronize()
+        t = [ev[i].elapsed_time(ev[i + 1]) for i in range(64)]
+        first = [t[i] for i in range(8, 64) if i % 8 == 0]
+        steady = {m: [t[i] for i in range(64) if modes[i] == m and i % 8 != 0] for m in (nfp.MODE_FP16, nfp.MODE_FP8)}
+        out["M=%d" % M] = {
+            "fp16_step_ms": sum(steady[nfp.MODE_FP16]) / len(steady[nfp.MODE_FP16]),
+            "fp8_step_ms": sum(steady[nfp.MODE_FP8]) / len(steady[nfp.MODE_FP8]),
+            "first_step_after_switch_ms": first,
+            "allocated_bytes_before": before, "allocated_bytes_after": torch.cuda.memory_allocated()}
+        del X, Y, ws
+    return out
+
+
+def switch_demo_extras(torch, nfp, workloads, planes, dev):
+    """Sec. 5.4's policy on a synthetic arrival sequence (the paper's trace is not available):
+    a step whose token count reaches 1024 runs in FP8 mode, the others in FP16 mode."""
+    import numpy as np
+
+    rng = np.random.default_rng(7)
+    choices = np.array([16, 32, 64, 128, 256, 512, 1024, 2048, 4096])
+    # mostly small decode steps with bursts of large prefill-heavy steps
+    seq = [int(choices[min(8, int(abs(rng.normal(0, 1.6)) + (4 if rng.random() < 0.25 else 0)))]) for _ in range(48)]
+    bufs = {M: _stack_buffers(torch, nfp, workloads, M, dev) for M in sorted(set(seq))}
+    res = {}
+    for policy in ("always_fp16", "always_fp8", "threshold_1024"):
+        def mode_of(M):
+            if policy == "always_fp16":
+                return nfp.MODE_FP16
+            if policy == "always_fp8":
+                return nfp.MODE_FP8
+            return nfp.MODE_FP8 if M >= 1024 else nfp.MODE_FP16
+        for M in bufs:                                   # warm every kernel once
+            _run_stack(nfp, planes, *bufs[M], mode_of(M))
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for M in seq:
+            _run_stack(nfp, planes, *bufs[M], mode_of(M))
+        b.record()
+        torch.cuda.synchronize()
+        res[policy] = {"total_ms": a.elapsed_time(b), "fp8_steps": sum(1 for M in seq if mode_of(M) == nfp.MODE_FP8)}
+    res["tokens_per_step"] = seq
+    return res
 
 
 def cpu_baseline(workloads, M):
