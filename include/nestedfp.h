@@ -174,6 +174,39 @@ int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64
                                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Exception layers (Sec. 4.1 "Handling Exception Layers", App. Table 4): a layer with any
+ * |w| > 1.75 cannot be stored in the format and stays in FP16; it then runs the FP16 GEMM
+ * in BOTH modes while every other layer follows the requested mode.
+ * nestedfp_layer describes one linear either way (a plain struct in HOST memory; the
+ * pointers inside are device pointers owned by the caller).
+ * layer_prepare: decomposes W into upper/lower (packed planes, as nestedfp_decompose), waits
+ *   for the stream and fills *layer: is_exception = 0 with the planes, or, if some weight is
+ *   out of range, is_exception = 1 with W/ldw (the planes then hold nothing useful and may be
+ *   released; W must stay alive instead).  *out_of_range is device scratch (8 bytes).
+ *   Returns NESTEDFP_OK in both cases.
+ * linear_workspace_size / linear: Y = X * W^T for the layer in `mode`; an exception layer
+ *   ignores the mode (and act_scale) and multiplies its FP16 weights.
+ */
+typedef struct {
+    int64_t N, K;
+    int32_t is_exception;
+    int32_t reserved;
+    const uint8_t *upper;       /* packed planes when is_exception == 0 */
+    const uint8_t *lower;
+    const uint16_t *W;          /* row-major FP16 weights when is_exception == 1 */
+    int64_t ldw;
+    uint64_t out_of_range;      /* count found by layer_prepare */
+} nestedfp_layer;
+
+int nestedfp_layer_prepare(const uint16_t *W, int64_t N, int64_t K, int64_t ldw,
+                           uint8_t *upper, uint8_t *lower, uint64_t *out_of_range,
+                           nestedfp_layer *layer_host, void *stream);
+size_t nestedfp_linear_workspace_size(int64_t M, const nestedfp_layer *layer_host, int mode);
+int nestedfp_linear(const uint16_t *X, int64_t M, int64_t ldx, const nestedfp_layer *layer_host,
+                    int mode, const float *act_scale, uint16_t *Y, int64_t ldy,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tuning hook for benchmark sweeps: overrides one launch parameter process-wide
  * (not thread-safe).  knob names are listed in nestedfp_tune_name(i), i = 0.. until NULL.
  * value < 0 restores the built-in choice.  Returns NESTEDFP_ERR_ARG for unknown knobs.

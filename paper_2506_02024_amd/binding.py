@@ -66,6 +66,12 @@ def lib():
     L.nestedfp_plain_gemm_fp8.argtypes = [vp, i64, i64, i64, vp, i64, f32, vp, vp, i64, vp, sz, vp]
     L.nestedfp_gemm_fp8_prequantized.restype = ci
     L.nestedfp_gemm_fp8_prequantized.argtypes = [vp, vp, i64, i64, vp, i64, f32, vp, i64, vp, sz, vp]
+    L.nestedfp_layer_prepare.restype = ci
+    L.nestedfp_layer_prepare.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    L.nestedfp_linear_workspace_size.restype = sz
+    L.nestedfp_linear_workspace_size.argtypes = [i64, vp, ci]
+    L.nestedfp_linear.restype = ci
+    L.nestedfp_linear.argtypes = [vp, i64, i64, vp, ci, vp, vp, i64, vp, sz, vp]
     L.nestedfp_tune.restype = ci
     L.nestedfp_tune.argtypes = [c.c_char_p, i64]
     L.nestedfp_tune_name.restype = c.c_char_p
@@ -286,3 +292,49 @@ def gemm_fp8_prequantized(Xq, scales, upper, w_scale=2.0 ** -8, out=None, worksp
                                               workspace.numel(), _stream())
     _check(st, "nestedfp_gemm_fp8_prequantized")
     return out
+
+
+class _LayerStruct(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int64), ("K", ctypes.c_int64), ("is_exception", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("upper", ctypes.c_void_p), ("lower", ctypes.c_void_p),
+                ("W", ctypes.c_void_p), ("ldw", ctypes.c_int64), ("out_of_range", ctypes.c_uint64)]
+
+
+class Layer:
+    """One linear as the library describes it: NestedFP planes, or the FP16 weights themselves
+    if the layer is an exception (some |w| > 1.75).  Keeps the device buffers alive."""
+
+    def __init__(self, W):
+        N, K, ldw = _rowmajor(W, "W")
+        self.c = _LayerStruct()
+        upper, lower = PackedPlane(N, K, W.device), PackedPlane(N, K, W.device)
+        cnt = torch.empty(1, dtype=torch.int64, device=W.device)
+        st = lib().nestedfp_layer_prepare(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
+                                          ctypes.byref(self.c), _stream())
+        _check(st, "nestedfp_layer_prepare")
+        if self.c.is_exception:
+            self.W, self.upper, self.lower = W, None, None     # planes released
+        else:
+            self.W, self.upper, self.lower = None, upper, lower
+
+    is_exception = property(lambda self: bool(self.c.is_exception))
+    out_of_range = property(lambda self: int(self.c.out_of_range))
+    shape = property(lambda self: (int(self.c.N), int(self.c.K)))
+
+
+def linear(X, layer, mode, act_scale=None, out=None, workspace=None):
+    """Y = X @ W^T for a Layer in the given mode (exception layers always run in FP16)."""
+    M, K, ldx = _rowmajor(X, "X")
+    N = layer.shape[0]
+    if layer.shape[1] != K:
+        raise ValueError("K of X and of the layer differ")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _, _, ldy = _rowmajor(out, "out")
+    if workspace is None:
+        workspace = _workspace(lib().nestedfp_linear_workspace_size(M, ctypes.byref(layer.c), int(mode)), X.device)
+    st = lib().nestedfp_linear(_ptr(X), M, ldx, ctypes.byref(layer.c), int(mode), _ptr(act_scale),
+                               _ptr(out), ldy, _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "nestedfp_linear")
+    return out
+

@@ -309,6 +309,45 @@ int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64
                     static_cast<hipStream_t>(stream));
 }
 
+int nestedfp_layer_prepare(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *upper,
+                           uint8_t *lower, uint64_t *out_of_range, nestedfp_layer *layer_host, void *stream) {
+    if (layer_host == nullptr || out_of_range == nullptr) return NESTEDFP_ERR_ARG;
+    uint64_t count = 0;
+    int st = nestedfp_decompose(W, N, K, ldw, upper, lower, out_of_range, &count, stream);
+    if (st != NESTEDFP_OK && st != NESTEDFP_ERR_RANGE) return st;
+    memset(layer_host, 0, sizeof(*layer_host));
+    layer_host->N = N;
+    layer_host->K = K;
+    layer_host->out_of_range = count;
+    if (st == NESTEDFP_ERR_RANGE) {
+        layer_host->is_exception = 1;
+        layer_host->W = W;
+        layer_host->ldw = ldw;
+    } else {
+        layer_host->upper = upper;
+        layer_host->lower = lower;
+    }
+    return NESTEDFP_OK;
+}
+
+size_t nestedfp_linear_workspace_size(int64_t M, const nestedfp_layer *layer_host, int mode) {
+    if (layer_host == nullptr) return 0;
+    if (layer_host->is_exception) mode = NESTEDFP_MODE_FP16;
+    return nestedfp_gemm_workspace_size(M, layer_host->N, layer_host->K, mode);
+}
+
+int nestedfp_linear(const uint16_t *X, int64_t M, int64_t ldx, const nestedfp_layer *layer_host, int mode,
+                    const float *act_scale, uint16_t *Y, int64_t ldy, void *workspace,
+                    size_t workspace_bytes, void *stream) {
+    if (layer_host == nullptr) return NESTEDFP_ERR_ARG;
+    if (mode != NESTEDFP_MODE_FP16 && mode != NESTEDFP_MODE_FP8) return NESTEDFP_ERR_ARG;
+    const nestedfp_layer &L = *layer_host;
+    if (L.is_exception)
+        return nestedfp_plain_gemm_fp16(X, M, L.K, ldx, L.W, L.N, L.ldw, Y, ldy, workspace, workspace_bytes, stream);
+    return nestedfp_gemm(X, M, L.K, ldx, L.upper, L.lower, L.N, mode, act_scale, Y, ldy, workspace,
+                         workspace_bytes, stream);
+}
+
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
                                      "large_split", "large_bm", "large_waves", "large_epilogue", "quant_hw",
                                      nullptr};

@@ -107,3 +107,17 @@ def test_plane_bytes_is_the_padded_block_count(L):
     assert L.nestedfp_plane_bytes(8, 24) == 0          # K must be a multiple of 16
     assert L.nestedfp_plane_bytes(-1, 64) == 0
 
+
+def test_layer_entry_points_reject_missing_descriptors(L):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    L.nestedfp_linear_workspace_size.restype = ctypes.c_size_t
+    L.nestedfp_linear_workspace_size.argtypes = [ctypes.c_int64, P, ctypes.c_int]
+    assert L.nestedfp_linear_workspace_size(16, P(0), 0) == 0
+    L.nestedfp_linear.argtypes = [P, ctypes.c_int64, ctypes.c_int64, P, ctypes.c_int, P, P, ctypes.c_int64, P,
+                                  ctypes.c_size_t, P]
+    assert L.nestedfp_linear(fake, 4, 32, P(0), 0, P(0), fake, 8, P(0), 0, P(0)) == 1
+    L.nestedfp_layer_prepare.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, P, P, P, P, P]
+    assert L.nestedfp_layer_prepare(fake, 4, 32, 32, fake, fake, fake, P(0), P(0)) == 1
+    assert L.nestedfp_layer_prepare(fake, 4, 32, 32, fake, fake, P(0), fake, P(0)) == 1
+
