@@ -22,6 +22,8 @@ struct SmallParams {
     const uint8_t *X;       // fp16 X (as bytes) or E4M3 Xq
     int64_t x_row_bytes;    // row stride of X in bytes
     const float *scales;    // [M] (kE4M3) or NULL
+    const float *static_scale;  // kE4M3Quant: per-tensor activation scale or NULL (per token)
+    int quant_hw;           // kE4M3Quant: hardware or integer E4M3 encoder
     float w_scale;
     const uint8_t *W0;      // fp16 W (bytes) / upper plane / E4M3 weights
     const uint8_t *W1;      // lower plane
@@ -37,7 +39,7 @@ struct SmallParams {
     int vec_store;          // 1: 8-byte fp16 stores allowed
 };
 
-template <int KIND> struct StepK { static constexpr int value = (KIND == kE4M3) ? 128 : 64; };
+template <int KIND> struct StepK { static constexpr int value = (KIND == kE4M3 || KIND == kE4M3Quant) ? 128 : 64; };
 
 // One K-step of weights for one 16-row tile, as loaded (32 bytes per lane).
 struct WItem { u32x4 a, b; };   // plain: 32 B fp16; nested: upper, lower; e4m3: 32 B
@@ -109,7 +111,7 @@ __device__ __forceinline__ void prep_w(const WItem &w, u32x4 &w_lo, u32x4 &w_hi)
 template <int KIND>
 __device__ __forceinline__ floatx4 mma_step(const u32x4 &w_lo, const u32x4 &w_hi, const u32x4 &xa,
                                             const u32x4 &xb, floatx4 acc) {
-    if (KIND == kE4M3) {
+    if (KIND == kE4M3 || KIND == kE4M3Quant) {
         intx8 a, b;
         a[0] = w_lo.x; a[1] = w_lo.y; a[2] = w_lo.z; a[3] = w_lo.w;
         a[4] = w_hi.x; a[5] = w_hi.y; a[6] = w_hi.z; a[7] = w_hi.w;
@@ -211,16 +213,77 @@ small_gemm_kernel(SmallParams p) {
     uint64_t tr1 = 0, tr2 = 0;
 #endif
     WItem buf0[SPW], buf1[SPW];
+    __shared__ uint32_t row_max[16 * 16];             // kE4M3Quant: per wave and token row
+    float row_scale = 1.0f;
     const int passes = MULTIPASS ? p.k_passes : 1;
     for (int pass = 0; pass < passes; ++pass) {
         const int k_wave = ((slice * passes + pass) * waves + wave) * (SPW * KSTEP) + KLANE * g;
-#pragma unroll
-        for (int s = 0; s < SPW; ++s)
-#pragma unroll
-            for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
         if (KIND == kPlainF16) voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * 2u;
         else voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * 1024u;   // block column of the slice
-        fetch(buf0, 0);
+        if (KIND == kE4M3Quant) {
+            // Fused activation quantisation (Sec. 2.2 per-token scaling; one token tile, the
+            // workgroup covers all of K): every wave loads the FP16 activations of its own slice,
+            // the row maxima are combined through LDS, and each lane converts what it holds --
+            // the same divisions and conversions as the stand-alone kernel, no Xq round trip.
+            u32x4 xr[SPW][4];
+            const bool row_ok = r16 < p.M;
+#pragma unroll
+            for (int s = 0; s < SPW; ++s) {
+                const int k = k_wave + s * KSTEP;
+                const uint8_t *src = p.X + (int64_t)r16 * p.x_row_bytes + 2 * (int64_t)k;
+                const bool ok0 = row_ok && k < p.K, ok1 = row_ok && (k + 64) < p.K;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                xr[s][0] = ok0 ? *reinterpret_cast<const u32x4 *>(src) : zero;
+                xr[s][1] = ok0 ? *reinterpret_cast<const u32x4 *>(src + 16) : zero;
+                xr[s][2] = ok1 ? *reinterpret_cast<const u32x4 *>(src + 128) : zero;
+                xr[s][3] = ok1 ? *reinterpret_cast<const u32x4 *>(src + 144) : zero;
+            }
+            fetch(buf0, 0);                            // the weights travel during the reduction
+            float sc;
+            if (p.static_scale) {
+                sc = *p.static_scale;
+            } else {
+                uint32_t amax_bits = 0;                // |x| as an integer compare on the magnitude bits
+#pragma unroll
+                for (int s = 0; s < SPW; ++s)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t w[4] = {xr[s][q].x, xr[s][q].y, xr[s][q].z, xr[s][q].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            amax_bits = max(amax_bits, max(w[e] & 0x7fffu, (w[e] >> 16) & 0x7fffu));
+                    }
+                amax_bits = max(amax_bits, (uint32_t)__shfl_xor((int)amax_bits, 16, 64));
+                amax_bits = max(amax_bits, (uint32_t)__shfl_xor((int)amax_bits, 32, 64));
+                if (g == 0) row_max[wave * 16 + r16] = amax_bits;
+                __syncthreads();
+                uint32_t all = 0;
+                for (int w2 = 0; w2 < waves; ++w2) all = max(all, row_max[w2 * 16 + r16]);
+                const float amax = half_bits_to_float(all);
+                sc = (amax == 0.0f) ? 1.0f : amax / 448.0f;
+            }
+            row_scale = sc;
+#pragma unroll
+            for (int s = 0; s < SPW; ++s) {
+                if (p.quant_hw) {
+                    xa[s][0] = u32x4{quant4<true>(xr[s][0].x, xr[s][0].y, sc), quant4<true>(xr[s][0].z, xr[s][0].w, sc),
+                                     quant4<true>(xr[s][1].x, xr[s][1].y, sc), quant4<true>(xr[s][1].z, xr[s][1].w, sc)};
+                    xb[s][0] = u32x4{quant4<true>(xr[s][2].x, xr[s][2].y, sc), quant4<true>(xr[s][2].z, xr[s][2].w, sc),
+                                     quant4<true>(xr[s][3].x, xr[s][3].y, sc), quant4<true>(xr[s][3].z, xr[s][3].w, sc)};
+                } else {
+                    xa[s][0] = u32x4{quant4<false>(xr[s][0].x, xr[s][0].y, sc), quant4<false>(xr[s][0].z, xr[s][0].w, sc),
+                                     quant4<false>(xr[s][1].x, xr[s][1].y, sc), quant4<false>(xr[s][1].z, xr[s][1].w, sc)};
+                    xb[s][0] = u32x4{quant4<false>(xr[s][2].x, xr[s][2].y, sc), quant4<false>(xr[s][2].z, xr[s][2].w, sc),
+                                     quant4<false>(xr[s][3].x, xr[s][3].y, sc), quant4<false>(xr[s][3].z, xr[s][3].w, sc)};
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SPW; ++s)
+#pragma unroll
+                for (int i = 0; i < MT; ++i) load_x<KIND>(xa[s][i], xb[s][i], p, 16 * i + r16, k_wave + s * KSTEP);
+            fetch(buf0, 0);
+        }
         // The scheduling barriers keep the compiler from sinking the look-ahead loads below the
         // multiplies (which would turn every wait into a full drain).  For odd T the last
         // half-trip multiplies zeros into a spare slot.
@@ -266,8 +329,8 @@ small_gemm_kernel(SmallParams p) {
                 for (int q = 0; q < 4 && n + q < p.N; ++q) dst[q] = v[q];
             }
         } else {
-            if (KIND == kE4M3) {
-                float sc = p.scales[m] * p.w_scale;
+            if (KIND == kE4M3 || KIND == kE4M3Quant) {
+                float sc = (KIND == kE4M3Quant ? row_scale : p.scales[m]) * p.w_scale;
                 sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
             }
             uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
@@ -357,6 +420,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const Tuning &t = tuning();
     SmallConfig c;
     c.mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    if (kind == kE4M3Quant) kind = kE4M3;             // same launch shapes
     const int kstep = (kind == kE4M3) ? 128 : 64;
     const int steps = (int)((K + kstep - 1) / kstep);
     const int max_waves = c.mt == 4 ? 8 : 16;     // four token tiles need 256 VGPRs per wave
@@ -431,6 +495,27 @@ static void launch_small_t(const SmallParams &p, const SmallConfig &c, dim3 grid
     else kern1<<<grid, c.waves * 64, lds, stream>>>(p);
 }
 
+// The fused-quantisation kind exists for one token tile, one K pass and no grid split only.
+static void launch_small_quant(const SmallParams &p, const SmallConfig &c, dim3 grid, hipStream_t stream) {
+    size_t lds = (size_t)((c.tiles_per_wg + 1) & ~1) * c.waves * 64 * sizeof(floatx4);
+    auto k2 = small_gemm_kernel<kE4M3Quant, 1, 2, false>;
+    auto k4 = small_gemm_kernel<kE4M3Quant, 1, 4, false>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        attr_set = true;
+    }
+    if (c.spw == 2) k2<<<grid, c.waves * 64, lds, stream>>>(p);
+    else k4<<<grid, c.waves * 64, lds, stream>>>(p);
+}
+
+bool small_gemm_fuses_quant(int64_t M, int64_t N, int64_t K) {
+    if (tuning().small_fuse_quant == 0) return false;
+    SmallConfig c = choose_small(kE4M3, M, N, K);
+    return c.mt == 1 && c.split == 1 && c.passes == 1;
+}
+
 template <int KIND>
 static void launch_small_k(const SmallParams &p, const SmallConfig &c, dim3 grid, hipStream_t stream) {
     switch (c.mt * 10 + c.spw) {
@@ -447,6 +532,8 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.X = static_cast<const uint8_t *>(a.X);
     p.x_row_bytes = (kind == kE4M3) ? a.ldx : 2 * a.ldx;
     p.scales = a.scales;
+    p.static_scale = a.static_scale;
+    p.quant_hw = tuning().quant_hw != 0 ? 1 : 0;
     p.w_scale = a.w_scale;
     p.W0 = static_cast<const uint8_t *>(a.W0);
     p.W1 = static_cast<const uint8_t *>(a.W1);
@@ -471,9 +558,11 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
                         a.partial_bytes < (size_t)c.split * a.M * a.N * sizeof(float)))
         return kErrWorkspace;
     dim3 grid(grid_x, (unsigned)c.split);
+    if (kind == kE4M3Quant && !(c.mt == 1 && c.split == 1 && c.passes == 1)) return kErrArg;   // caller checks first
     switch (kind) {
         case kPlainF16: launch_small_k<kPlainF16>(p, c, grid, stream); break;
         case kNestedF16: launch_small_k<kNestedF16>(p, c, grid, stream); break;
+        case kE4M3Quant: launch_small_quant(p, c, grid, stream); break;
         default: launch_small_k<kE4M3>(p, c, grid, stream); break;
     }
     if (hipGetLastError() != hipSuccess) return kErrHip;

@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
     return t;
 }
 
@@ -83,6 +83,20 @@ static int check_out(const uint16_t *Y, int64_t N, int64_t ldy) {
     if (Y == nullptr) return kErrArg;
     if (ldy < N || !aligned(Y, 2)) return kErrShape;
     return kOk;
+}
+
+// FP8-mode GEMM straight from FP16 activations where the streaming kernel can quantise them
+// itself (decode batches whose K fits one workgroup pass); returns -1 if it cannot.
+static int fp8_gemm_fused(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const float *act_scale,
+                          const uint8_t *Wq, int64_t N, float w_scale, uint16_t *Y, int64_t ldy,
+                          hipStream_t stream) {
+    if (!route_small(kE4M3, M, N, K, K) || !small_gemm_fuses_quant(M, N, K)) return -1;
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.X = X;  a.ldx = ldx;  a.static_scale = act_scale;  a.w_scale = w_scale;
+    a.W0 = Wq;  a.W1 = nullptr;  a.ldw = K;
+    a.M = M;  a.N = N;  a.K = K;  a.Y = Y;  a.ldy = ldy;
+    return launch_small_gemm(kE4M3Quant, a, stream);
 }
 
 static int fp8_gemm(const uint8_t *Xq, const float *scales, int64_t M, int64_t K, const uint8_t *Wq,
@@ -245,9 +259,11 @@ int nestedfp_gemm(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const ui
         return run_gemm(kNestedF16, a, s);
     }
     if (!carve(workspace, workspace_bytes, kE4M3, M, N, K, true, ws)) return NESTEDFP_ERR_WORKSPACE;
+    // Sec. 4.1: the upper plane read as E4M3 is the weight times 2^8
+    st = fp8_gemm_fused(X, M, K, ldx, act_scale, upper, N, 0.00390625f, Y, ldy, s);
+    if (st >= 0) return st;
     st = launch_quantize_act(X, M, K, ldx, act_scale, ws.xq, ws.scales, s);
     if (st != kOk) return st;
-    // Sec. 4.1: the upper plane read as E4M3 is the weight times 2^8
     return fp8_gemm(ws.xq, ws.scales, M, K, upper, N, 0.00390625f, Y, ldy, ws.partials, ws.partial_bytes, s);
 }
 
@@ -288,6 +304,8 @@ int nestedfp_plain_gemm_fp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx
     hipStream_t s = static_cast<hipStream_t>(stream);
     Workspace ws;
     if (!carve(workspace, workspace_bytes, kE4M3, M, N, K, true, ws)) return NESTEDFP_ERR_WORKSPACE;
+    st = fp8_gemm_fused(X, M, K, ldx, act_scale, Wq, N, w_scale, Y, ldy, s);
+    if (st >= 0) return st;
     st = launch_quantize_act(X, M, K, ldx, act_scale, ws.xq, ws.scales, s);
     if (st != kOk) return st;
     return fp8_gemm(ws.xq, ws.scales, M, K, Wq, N, w_scale, Y, ldy, ws.partials, ws.partial_bytes, s);
@@ -349,7 +367,7 @@ int nestedfp_linear(const uint16_t *X, int64_t M, int64_t ldx, const nestedfp_la
 }
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
-                                     "large_split", "large_bm", "large_waves", "large_epilogue", "quant_hw",
+                                     "large_split", "large_bm", "large_waves", "large_epilogue", "small_fuse_quant", "quant_hw",
                                      nullptr};
 
 const char *nestedfp_tune_name(int index) {
@@ -370,6 +388,7 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "large_bm")) t.large_bm = value;
     else if (!strcmp(knob, "large_waves")) t.large_waves = value;
     else if (!strcmp(knob, "large_epilogue")) t.large_epilogue = value;
+    else if (!strcmp(knob, "small_fuse_quant")) t.small_fuse_quant = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;
     else return NESTEDFP_ERR_ARG;
     return NESTEDFP_OK;

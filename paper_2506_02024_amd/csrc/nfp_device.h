@@ -104,6 +104,19 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
     return (float)cvt.f;
 }
 
+// Four FP16 activations (two packed dwords) -> four E4M3 bytes at scale s (Sec. 2.2, per-token
+// scaling): binary32 division, correctly rounded (no fast-math), clamp to +-448, RNE.
+template <bool HW>
+__device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s) {
+    float a = clamp448(half_bits_to_float(w01 & 0xffffu) / s);
+    float b = clamp448(half_bits_to_float(w01 >> 16) / s);
+    float c = clamp448(half_bits_to_float(w23 & 0xffffu) / s);
+    float d = clamp448(half_bits_to_float(w23 >> 16) / s);
+    if (HW) return e4m3x4_from_float_hw(a, b, c, d);
+    return e4m3_from_float_sw(a) | (e4m3_from_float_sw(b) << 8) | (e4m3_from_float_sw(c) << 16) |
+           (e4m3_from_float_sw(d) << 24);
+}
+
 __device__ __forceinline__ uint32_t float2_to_half2_bits(float a, float b) {
     union { _Float16 f[2]; uint32_t u; } cvt;
     cvt.f[0] = (_Float16)a;

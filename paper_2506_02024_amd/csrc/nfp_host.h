@@ -12,13 +12,15 @@ enum { kOk = 0, kErrArg = 1, kErrShape = 2, kErrRange = 3, kErrWorkspace = 4, kE
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? kOk : kErrHip; }
 
 // weight operand kinds of the GEMM kernels
-enum WeightKind { kPlainF16 = 0, kNestedF16 = 1, kE4M3 = 2 };
+// kE4M3Quant: packed E4M3 weights, FP16 activations quantised per token inside the kernel
+enum WeightKind { kPlainF16 = 0, kNestedF16 = 1, kE4M3 = 2, kE4M3Quant = 3 };
 
 struct GemmArgs {
     // activations: fp16 X (kPlainF16 / kNestedF16) or E4M3 Xq with per-row scales (kE4M3)
     const void *X;        // uint16_t* or uint8_t*
     int64_t ldx;          // elements
     const float *scales;  // [M], kE4M3 only
+    const float *static_scale;  // kE4M3Quant: optional per-tensor activation scale (device float)
     float w_scale;        // kE4M3 only
     // weights
     const void *W0;       // fp16 W, or upper plane, or E4M3 weights
@@ -42,6 +44,7 @@ struct Tuning {
     int64_t large_bm;        // tile height of the tiled kernel
     int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
+    int64_t small_fuse_quant;  // 0: never quantise activations inside the streaming kernel
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
 };
 Tuning &tuning();
@@ -61,6 +64,7 @@ int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
 
 // streaming (small-M) and tiled (large-M) GEMM families
 bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw);
+bool small_gemm_fuses_quant(int64_t M, int64_t N, int64_t K);
 size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K);
 int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream);
 size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K);

@@ -10,18 +10,6 @@ namespace nfp {
 constexpr int kQuantThreads = 256;
 
 template <bool HW>
-__device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s) {
-    // binary32 division, correctly rounded (no fast-math): the quotient is what gets rounded
-    float a = clamp448(half_bits_to_float(w01 & 0xffffu) / s);
-    float b = clamp448(half_bits_to_float(w01 >> 16) / s);
-    float c = clamp448(half_bits_to_float(w23 & 0xffffu) / s);
-    float d = clamp448(half_bits_to_float(w23 >> 16) / s);
-    if (HW) return e4m3x4_from_float_hw(a, b, c, d);
-    return e4m3_from_float_sw(a) | (e4m3_from_float_sw(b) << 8) | (e4m3_from_float_sw(c) << 16) |
-           (e4m3_from_float_sw(d) << 24);
-}
-
-template <bool HW>
 __global__ void __launch_bounds__(kQuantThreads)
 quantize_act_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
                     const float *__restrict__ static_scale, uint8_t *__restrict__ Xq,

@@ -292,3 +292,34 @@ def test_llama70b_shapes_sampled(nfp, name, M):
 def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, M):
     # the (N, K) shapes of Sec. 5.2 / Fig. 6, M inside its 32..2048 sweep
     _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_8B, "N=%d K=%d M=%d" % (N, K, M), seed=N % 89)
+
+
+@pytest.mark.parametrize("M,N,K,split", [(16, 4096, 4096, -1), (1, 6144, 4096, -1), (5, 304, 2048 + 64, 1),
+                                         (16, 520, 528, 1), (13, 272, 4096 + 16, 1)])
+def test_fused_activation_quantisation_equals_the_two_kernel_path(nfp, M, N, K, split):
+    # decode batches whose K fits one workgroup pass quantise the activations inside the GEMM
+    # kernel; the result must be bit-identical to quantise-then-multiply and match the oracle
+    W = workloads.weight_host(N, K, seed=N + K)
+    X = workloads.act_host(M, K, seed=M + K)
+    X[0, :] = 0                                        # an all-zero token: scale 1
+    Xd = to_dev(X)
+    up, _ = nfp.decompose(to_dev(W))
+    sc = torch.tensor([0.0123], dtype=torch.float32, device="cuda:0")
+    nfp.tune("small_split", split)
+    try:
+        fused = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8))
+        fused_static = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8, act_scale=sc))
+        nfp.tune("small_fuse_quant", 0)
+        plain = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8))
+        plain_static = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8, act_scale=sc))
+        Xq_d, s_d = nfp.quantize_act(Xd)
+        pre = bits(nfp.gemm_fp8_prequantized(Xq_d, s_d, up))
+    finally:
+        nfp.tune("small_fuse_quant", -1)
+        nfp.tune("small_split", -1)
+    assert np.array_equal(fused, plain) and np.array_equal(fused, pre)
+    assert np.array_equal(fused_static, plain_static)
+    Xq, s = oracle.quantize_act(X)
+    up_ref, _, _ = oracle.decompose(W)
+    assert_gemm_close(fused.view(np.float16), oracle.gemm_fp8(Xq, s, up_ref), "fused FP8 mode")
+
