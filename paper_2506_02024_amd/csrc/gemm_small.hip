@@ -263,18 +263,19 @@ small_gemm_kernel(SmallParams p) {
                 sc = (amax == 0.0f) ? 1.0f : amax / 448.0f;
             }
             row_scale = sc;
+            const float rc = 1.0f / sc;                // correctly rounded; see div_by_scale
 #pragma unroll
             for (int s = 0; s < SPW; ++s) {
                 if (p.quant_hw) {
-                    xa[s][0] = u32x4{quant4<true>(xr[s][0].x, xr[s][0].y, sc), quant4<true>(xr[s][0].z, xr[s][0].w, sc),
-                                     quant4<true>(xr[s][1].x, xr[s][1].y, sc), quant4<true>(xr[s][1].z, xr[s][1].w, sc)};
-                    xb[s][0] = u32x4{quant4<true>(xr[s][2].x, xr[s][2].y, sc), quant4<true>(xr[s][2].z, xr[s][2].w, sc),
-                                     quant4<true>(xr[s][3].x, xr[s][3].y, sc), quant4<true>(xr[s][3].z, xr[s][3].w, sc)};
+                    xa[s][0] = u32x4{quant4<true>(xr[s][0].x, xr[s][0].y, sc, rc), quant4<true>(xr[s][0].z, xr[s][0].w, sc, rc),
+                                     quant4<true>(xr[s][1].x, xr[s][1].y, sc, rc), quant4<true>(xr[s][1].z, xr[s][1].w, sc, rc)};
+                    xb[s][0] = u32x4{quant4<true>(xr[s][2].x, xr[s][2].y, sc, rc), quant4<true>(xr[s][2].z, xr[s][2].w, sc, rc),
+                                     quant4<true>(xr[s][3].x, xr[s][3].y, sc, rc), quant4<true>(xr[s][3].z, xr[s][3].w, sc, rc)};
                 } else {
-                    xa[s][0] = u32x4{quant4<false>(xr[s][0].x, xr[s][0].y, sc), quant4<false>(xr[s][0].z, xr[s][0].w, sc),
-                                     quant4<false>(xr[s][1].x, xr[s][1].y, sc), quant4<false>(xr[s][1].z, xr[s][1].w, sc)};
-                    xb[s][0] = u32x4{quant4<false>(xr[s][2].x, xr[s][2].y, sc), quant4<false>(xr[s][2].z, xr[s][2].w, sc),
-                                     quant4<false>(xr[s][3].x, xr[s][3].y, sc), quant4<false>(xr[s][3].z, xr[s][3].w, sc)};
+                    xa[s][0] = u32x4{quant4<false>(xr[s][0].x, xr[s][0].y, sc, rc), quant4<false>(xr[s][0].z, xr[s][0].w, sc, rc),
+                                     quant4<false>(xr[s][1].x, xr[s][1].y, sc, rc), quant4<false>(xr[s][1].z, xr[s][1].w, sc, rc)};
+                    xb[s][0] = u32x4{quant4<false>(xr[s][2].x, xr[s][2].y, sc, rc), quant4<false>(xr[s][2].z, xr[s][2].w, sc, rc),
+                                     quant4<false>(xr[s][3].x, xr[s][3].y, sc, rc), quant4<false>(xr[s][3].z, xr[s][3].w, sc, rc)};
                 }
             }
         } else {
@@ -511,7 +512,10 @@ static void launch_small_quant(const SmallParams &p, const SmallConfig &c, dim3 
 }
 
 bool small_gemm_fuses_quant(int64_t M, int64_t N, int64_t K) {
-    if (tuning().small_fuse_quant == 0) return false;
+    // Off unless asked for: every workgroup has to convert all of its 16 x K activations
+    // itself, which costs more VALU time per CU (measured 3-6 us per call at K = 4096) than
+    // the separate quantisation launch it saves.
+    if (tuning().small_fuse_quant <= 0) return false;
     SmallConfig c = choose_small(kE4M3, M, N, K);
     return c.mt == 1 && c.split == 1 && c.passes == 1;
 }

@@ -104,14 +104,25 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
     return (float)cvt.f;
 }
 
+// Correctly rounded binary32 quotient a / s from y = RN(1 / s) (itself one IEEE division per
+// token row): q0 = RN(a*y), r = a - q0*s exactly (FMA), q = RN(q0 + r*y).  With a correctly
+// rounded reciprocal this is the correctly rounded quotient whenever nothing over- or
+// underflows (Markstein's theorem); here |a| is a finite FP16 value and s lies far inside the
+// binary32 range, and the identity is also checked exhaustively against the oracle's division.
+__device__ __forceinline__ float div_by_scale(float a, float s, float y) {
+    float q0 = a * y;
+    float r = __builtin_fmaf(-q0, s, a);
+    return __builtin_copysignf(__builtin_fmaf(r, y, q0), a);       // s > 0; keeps -0 / s = -0
+}
+
 // Four FP16 activations (two packed dwords) -> four E4M3 bytes at scale s (Sec. 2.2, per-token
-// scaling): binary32 division, correctly rounded (no fast-math), clamp to +-448, RNE.
+// scaling): quotient correctly rounded in binary32, clamp to +-448, RNE.  y = 1.0f / s.
 template <bool HW>
-__device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s) {
-    float a = clamp448(half_bits_to_float(w01 & 0xffffu) / s);
-    float b = clamp448(half_bits_to_float(w01 >> 16) / s);
-    float c = clamp448(half_bits_to_float(w23 & 0xffffu) / s);
-    float d = clamp448(half_bits_to_float(w23 >> 16) / s);
+__device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s, float y) {
+    float a = clamp448(div_by_scale(half_bits_to_float(w01 & 0xffffu), s, y));
+    float b = clamp448(div_by_scale(half_bits_to_float(w01 >> 16), s, y));
+    float c = clamp448(div_by_scale(half_bits_to_float(w23 & 0xffffu), s, y));
+    float d = clamp448(div_by_scale(half_bits_to_float(w23 >> 16), s, y));
     if (HW) return e4m3x4_from_float_hw(a, b, c, d);
     return e4m3_from_float_sw(a) | (e4m3_from_float_sw(b) << 8) | (e4m3_from_float_sw(c) << 16) |
            (e4m3_from_float_sw(d) << 24);

@@ -44,7 +44,7 @@ struct Tuning {
     int64_t large_bm;        // tile height of the tiled kernel
     int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
-    int64_t small_fuse_quant;  // 0: never quantise activations inside the streaming kernel
+    int64_t small_fuse_quant;  // 1: quantise activations inside the streaming kernel where it can
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
 };
 Tuning &tuning();

@@ -44,12 +44,13 @@ quantize_act_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
         s = (amax == 0.0f) ? 1.0f : amax / 448.0f;
     }
     if (threadIdx.x == 0) scales[m] = s;
+    const float y = 1.0f / s;                        // correctly rounded; see div_by_scale
     u32x2 *out = reinterpret_cast<u32x2 *>(Xq + m * K);
     for (int c = threadIdx.x; c < chunks; c += kQuantThreads) {
         u32x4 v = row[c];
         u32x2 q;
-        q.x = quant4<HW>(v.x, v.y, s);
-        q.y = quant4<HW>(v.z, v.w, s);
+        q.x = quant4<HW>(v.x, v.y, s, y);
+        q.y = quant4<HW>(v.z, v.w, s, y);
         out[c] = q;
     }
 }
@@ -92,14 +93,15 @@ quantize_act_onepass_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t l
         s = (amax == 0.0f) ? 1.0f : amax / 448.0f;
     }
     if (threadIdx.x == 0) scales[m] = s;
+    const float y = 1.0f / s;                        // correctly rounded; see div_by_scale
     u32x2 *out = reinterpret_cast<u32x2 *>(Xq + m * K);
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         int c = threadIdx.x + i * blockDim.x;
         if (c < chunks) {
             u32x2 q;
-            q.x = quant4<HW>(v[i].x, v[i].y, s);
-            q.y = quant4<HW>(v[i].z, v[i].w, s);
+            q.x = quant4<HW>(v[i].x, v[i].y, s, y);
+            q.y = quant4<HW>(v[i].z, v[i].w, s, y);
             out[c] = q;
         }
     }

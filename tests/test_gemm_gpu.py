@@ -297,8 +297,8 @@ def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, M):
 @pytest.mark.parametrize("M,N,K,split", [(16, 4096, 4096, -1), (1, 6144, 4096, -1), (5, 304, 2048 + 64, 1),
                                          (16, 520, 528, 1), (13, 272, 4096 + 16, 1)])
 def test_fused_activation_quantisation_equals_the_two_kernel_path(nfp, M, N, K, split):
-    # decode batches whose K fits one workgroup pass quantise the activations inside the GEMM
-    # kernel; the result must be bit-identical to quantise-then-multiply and match the oracle
+    # decode batches whose K fits one workgroup pass can quantise the activations inside the GEMM
+    # kernel (knob small_fuse_quant); the result must be bit-identical to quantise-then-multiply and match the oracle
     W = workloads.weight_host(N, K, seed=N + K)
     X = workloads.act_host(M, K, seed=M + K)
     X[0, :] = 0                                        # an all-zero token: scale 1
@@ -306,6 +306,7 @@ def test_fused_activation_quantisation_equals_the_two_kernel_path(nfp, M, N, K, 
     up, _ = nfp.decompose(to_dev(W))
     sc = torch.tensor([0.0123], dtype=torch.float32, device="cuda:0")
     nfp.tune("small_split", split)
+    nfp.tune("small_fuse_quant", 1)
     try:
         fused = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8))
         fused_static = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8, act_scale=sc))

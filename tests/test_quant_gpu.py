@@ -72,3 +72,32 @@ def test_static_per_tensor_scale(nfp):
     Xq_ref, s_ref = oracle.quantize_act(X, static_scale=0.0625)
     assert np.array_equal(s.cpu().numpy(), s_ref)
     assert np.array_equal(Xq.cpu().numpy(), Xq_ref)
+
+
+def test_quotient_is_the_correctly_rounded_division_for_every_half_and_many_scales(nfp):
+    # The kernels divide by multiplying with the row's reciprocal and one FMA correction.
+    # Every finite FP16 word against a few hundred scales (random over the binary32 range the
+    # method can produce, all-ones and power-of-two significands, amax/448 of odd maxima):
+    # the codes must equal the oracle's, which performs the binary32 division itself.
+    words = workloads.all_fp16_words()
+    vals = words.view(np.float16)
+    finite = vals[np.isfinite(vals.astype(np.float32))]
+    X = np.zeros((32, 2048), dtype=np.float16)
+    X.reshape(-1)[: finite.size] = finite
+    rng = np.random.default_rng(11)
+    scales = list(np.exp(rng.uniform(np.log(1e-7), np.log(300.0), 160)).astype(np.float32))
+    scales += [np.float32(1.0), np.float32(2.0 ** -20), np.float32(146.2143), np.float32(0.99999994),
+               np.float32(1.9999999), np.float32(3.0), np.float32(1.0 / 3.0), np.float32(65504.0 / 448.0)]
+    scales += [np.float32(np.float16(a)) / np.float32(448.0) for a in (0.3337, 7.0, 1.0, 33.0, 6.1e-5, 5.96e-8)]
+    scales += [np.frombuffer(np.uint32(b).tobytes(), dtype=np.float32)[0]
+               for b in (0x3f7fffff, 0x3fffffff, 0x3effffff, 0x40ffffff, 0x3c7fffff, 0x3f800001, 0x3fc00001)]
+    Xd = to_dev(X)
+    for sc in scales:
+        sd = torch.tensor([float(sc)], dtype=torch.float32, device="cuda:0")
+        Xq, _ = nfp.quantize_act(Xd, static_scale=sd)
+        Xq_ref, _ = oracle.quantize_act(X, static_scale=float(sc))
+        got = Xq.cpu().numpy()
+        mism = np.nonzero(got != Xq_ref)
+        assert mism[0].size == 0, "scale %r: x=%r got %#x want %#x" % (
+            sc, X[mism[0][0], mism[1][0]], got[mism[0][0], mism[1][0]], Xq_ref[mism[0][0], mism[1][0]])
+
