@@ -606,23 +606,38 @@ large_gemm_kernel(LargeParams p) {
 
 struct LargeConfig { int tm, tn, split, waves; };
 
+// Tile size and K split from a small cost model: the workgroups are dealt round-robin to the
+// 256 CUs, a CU works through its share at the measured rate of the tile size (the 128x128
+// tile reads twice the LDS bytes per flop and runs at ~0.72 of the 256x256 one), and a split
+// adds a reduction launch plus the traffic of the fp32 partials.  Constants fitted to sweeps
+// of M = 128 ... 2048 on the Llama-3-8B shapes.
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
-    int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    c.tm = c.tn = (tiles256 >= 256) ? 256 : 128;
-    if (t.large_bm == 128 || t.large_bm == 256) c.tm = c.tn = (int)t.large_bm;
-    int64_t tiles = ((M + c.tm - 1) / c.tm) * ((N + c.tn - 1) / c.tn);
-    int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
-    c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
+    const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
+    const double rate_cu = (kind == kE4M3 ? 2.3e15 : 1.15e15) / 256.0;     // flop/s of one CU, 256x256 tile
+    double best = 1e30;
+    c.tm = c.tn = 256;
     c.split = 1;
-    if (tiles < 256) {                                  // fewer tiles than CUs: split K
-        int64_t s = (512 + tiles - 1) / tiles;
-        if (s > 8) s = 8;
-        if (s > kt / 4) s = kt / 4 > 0 ? kt / 4 : 1;
-        c.split = (int)s;
+    for (int bm = 256; bm >= 128; bm -= 128) {
+        if ((t.large_bm == 128 || t.large_bm == 256) && bm != t.large_bm) continue;
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bm - 1) / bm);
+        for (int split = 1; split <= 8; split *= 2) {
+            if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
+            else if (split > 1 && split > kt / 4) break;
+            const int per = (kt + split - 1) / split;                     // K-tiles per workgroup
+            const int64_t rounds = (tiles * split + 255) / 256;
+            // a lone 128x128 workgroup on a CU hides fewer of its stalls than two of them
+            const double eff = bm == 256 ? 1.0 : (tiles * split >= 384 ? 0.72 : 0.6);
+            double time = (double)rounds * (2.0 * bm * bm * 64.0 * (kind == kE4M3 ? 2 : 1) * per + 6.0e6) /
+                          (rate_cu * eff);                                // + prologue/epilogue per tile
+            // reduction launch + partials written and read back; a small bias keeps near-ties unsplit
+            if (split > 1) time = time * 1.04 + 5e-6 + 8.0 * (double)M * (double)N * split / 3e12;
+            if (time < best) { best = time;  c.tm = c.tn = bm;  c.split = split; }
+            if (t.large_split > 0) break;
+        }
     }
-    if (t.large_split > 0) c.split = (int)(t.large_split < kt ? t.large_split : kt);
+    c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
     return c;
 }
 
