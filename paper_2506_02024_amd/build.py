@@ -13,7 +13,6 @@ HIPCC_FLAGS = [
     # keep the compiler from emitting packed-FP32 VALU forms
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
-] + (["-DNFP_TRACE"] if os.environ.get("NFP_TRACE") else []) + os.environ.get("NFP_DEFS", "").split() + [
 ]
 
 

@@ -227,9 +227,6 @@ struct LargeKernel {
         uint32_t x_lim, w_lim;
         int wave, lane, wm, wn;
         int kt, cur;
-#ifdef NFP_TRACE
-        uint64_t tr_vm = 0, tr_bar = 0;
-#endif
     };
 
     // The merge of a thread's PWP pieces (16 weights each) is cut into quarters of 4 weights
@@ -356,19 +353,9 @@ struct LargeKernel {
             // Everything this wave still needs from the current stage is in registers.  Once all
             // waves are here and their loads of the next K-tile have landed, the current stage
             // is free and the next one complete.
-#ifdef NFP_TRACE
-            uint64_t ta = __builtin_readcyclecounter();
-            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            uint64_t tb = __builtin_readcyclecounter();
-            __syncthreads();
-            uint64_t tc = __builtin_readcyclecounter();
-            c.tr_vm += tb - ta;  c.tr_bar += tc - tb;
-#else
             if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __syncthreads();
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
         slot<OLDER, S, 0>(c);
@@ -451,9 +438,6 @@ struct LargeKernel {
         // The one barrier per K-tile sits in front of the LAST substep: by then every wave holds
         // that substep's fragments in registers, so the current stage is free for K-tile kt+2,
         // and the first fragments of K-tile kt+1 are fetched underneath the last MFMAs.
-#ifdef NFP_TRACE
-        uint64_t tr_start = __builtin_readcyclecounter();
-#endif
         if (wave < DW) {
             dma_range<0, DMAS>(c, 0, kt_begin);
             dma_range<0, DMAS>(c, 1, kt_begin + 1);
@@ -481,15 +465,9 @@ struct LargeKernel {
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
         }
         __syncthreads();
-#ifdef NFP_TRACE
-        const uint64_t tr_loop = __builtin_readcyclecounter();
-#endif
         read_all<0>(fr[0], lds, wm, wn, lane);
         if (!kTwoRoles || wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
-#ifdef NFP_TRACE
-        const uint64_t tr_end_loop = __builtin_readcyclecounter();
-#endif
         if (p.row_store && gridDim.y == 1) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
             __syncthreads();
@@ -497,15 +475,6 @@ struct LargeKernel {
         } else {
             epilogue(p, acc, m0, n0, wm, wn, lane, split);
         }
-#ifdef NFP_TRACE
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        const uint64_t tr_end = __builtin_readcyclecounter();
-        if (lane == 0 && p.partials != nullptr) {
-            uint64_t *o = reinterpret_cast<uint64_t *>(p.partials) + 8 * ((uint64_t)blockIdx.x * WAVES + wave);
-            o[0] = tr_loop - tr_start;  o[1] = tr_end_loop - tr_loop;  o[2] = c.tr_vm;  o[3] = c.tr_bar;
-            o[4] = tr_end - tr_end_loop;  o[5] = tr_end - tr_start;  o[6] = tr_start;  o[7] = tr_end;
-        }
-#endif
     }
 
     // Result tile through LDS: the MFMA layout leaves a lane with 4 consecutive outputs of one

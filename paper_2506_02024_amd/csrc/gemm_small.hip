@@ -207,11 +207,6 @@ small_gemm_kernel(SmallParams p) {
         for (int i = 0; i < MT; ++i) slots[((tile * waves + wave) * MT + i) * 64 + lane] = acc[i];
     };
 
-#ifdef NFP_TRACE
-    const uint64_t tr0 = __builtin_readcyclecounter();
-    const uint64_t rt0 = __builtin_amdgcn_s_memrealtime();
-    uint64_t tr1 = 0, tr2 = 0;
-#endif
     WItem buf0[SPW], buf1[SPW];
     __shared__ uint32_t row_max[16 * 16];             // kE4M3Quant: per wave and token row
     float row_scale = 1.0f;
@@ -293,22 +288,13 @@ small_gemm_kernel(SmallParams p) {
             __builtin_amdgcn_sched_barrier(0);
             consume(buf0, tile);
             __builtin_amdgcn_sched_barrier(0);
-#ifdef NFP_TRACE
-            if (tile == 0 && pass == 0) tr1 = __builtin_readcyclecounter();
-#endif
             fetch(buf0, tile + 2);
             __builtin_amdgcn_sched_barrier(0);
             consume(buf1, tile + 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-#ifdef NFP_TRACE
-    tr2 = __builtin_readcyclecounter();
-#endif
     __syncthreads();
-#ifdef NFP_TRACE
-    const uint64_t tr3 = __builtin_readcyclecounter();
-#endif
 
     // ---- fixed-order reduction over the waves of the workgroup -----------------------------
     for (int item = wave; item < T * MT; item += waves) {
@@ -350,16 +336,6 @@ small_gemm_kernel(SmallParams p) {
             }
         }
     }
-#ifdef NFP_TRACE
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    const uint64_t tr4 = __builtin_readcyclecounter();
-    if (lane == 0 && gridDim.y == 1 && p.partials != nullptr) {
-        uint64_t *o = reinterpret_cast<uint64_t *>(p.partials) + 8 * ((uint64_t)blockIdx.x * waves + wave);
-        o[0] = tr0;  o[1] = tr1 - tr0;  o[2] = tr2 - tr0;  o[3] = tr3 - tr0;  o[4] = tr4 - tr0;
-        o[5] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11));   // XCC_ID
-        o[6] = rt0;  o[7] = __builtin_amdgcn_s_memrealtime();
-    }
-#endif
 }
 
 // Sums the S split-K partials in slice order, applies the FP8-mode scale, writes fp16.
