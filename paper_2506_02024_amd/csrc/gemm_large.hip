@@ -575,38 +575,53 @@ large_gemm_kernel(LargeParams p) {
 
 struct LargeConfig { int tm, tn, split, waves; };
 
-// Tile size and K split from a small cost model: the workgroups are dealt round-robin to the
-// 256 CUs, a CU works through its share at the measured rate of the tile size (the 128x128
-// tile reads twice the LDS bytes per flop and runs at ~0.72 of the 256x256 one), and a split
-// adds a reduction launch plus the traffic of the fp32 partials.  Constants fitted to sweeps
-// of M = 128 ... 2048 on the Llama-3-8B shapes.
+// Tile shape and K split from a small cost model.  The workgroups are dealt round-robin to the
+// 256 CUs; a workgroup costs a fixed part plus a time per K-tile that depends on the tile shape
+// and the weight kind; two 128x128 workgroups share a CU and together run s2 times faster than
+// one after the other; a layer cannot finish before its weights have crossed the memory bus
+// once; a split adds a reduction launch plus the traffic of the fp32 partials.  The constants
+// are a least-squares fit (microseconds) to sweeps of every shape and split over M = 128 ...
+// 4096 on the four Llama-3-8B layer shapes and a square 8192 layer.
+struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
+static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};    // tokens x weight rows
+static const TileCost kTileCost[3][4] = {
+    {{1.331, 0.57}, {1.036, 0.0}, {1.113, 0.57}, {0.818, 0.0}},     // plain FP16
+    {{1.441, 1.59}, {1.106, 0.0}, {1.149, 1.30}, {0.913, 0.0}},     // NestedFP16
+    {{1.345, 6.36}, {1.091, 0.54}, {1.113, 2.10}, {0.882, 0.18}},   // E4M3
+};
+static const double kPairSpeedup[3] = {1.42, 1.38, 1.41};
+
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
     const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
-    const double rate_cu = (kind == kE4M3 ? 2.3e15 : 1.15e15) / 256.0;     // flop/s of one CU, 256x256 tile
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
-    for (int bm = 256; bm >= 128; bm -= 128) {
-        if ((t.large_bm == 128 || t.large_bm == 256) && bm != t.large_bm) continue;
-        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bm - 1) / bm);
+    const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
+    const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.43e6;
+    for (int sh = 0; sh < 4; ++sh) {
+        const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
+        if (want_m && bm != want_m) continue;
+        if (want_n && bn != want_n) continue;
+        const TileCost &tc = kTileCost[kind > 2 ? 2 : kind][sh];
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 8; split *= 2) {
             if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
             else if (split > 1 && split > kt / 4) break;
             const int per = (kt + split - 1) / split;                     // K-tiles per workgroup
-            const int64_t rounds = (tiles * split + 255) / 256;
-            // a lone 128x128 workgroup on a CU hides fewer of its stalls than two of them
-            const double eff = bm == 256 ? 1.0 : (tiles * split >= 384 ? 0.72 : 0.6);
-            double time = (double)rounds * (2.0 * bm * bm * 64.0 * (kind == kE4M3 ? 2 : 1) * per + 6.0e6) /
-                          (rate_cu * eff);                                // + prologue/epilogue per tile
-            // reduction launch + partials written and read back; a small bias keeps near-ties unsplit
-            if (split > 1) time = time * 1.04 + 5e-6 + 8.0 * (double)M * (double)N * split / 3e12;
-            if (time < best) { best = time;  c.tm = c.tn = bm;  c.split = split; }
+            const int slices = (kt + per - 1) / per;
+            const int64_t rounds = (tiles * slices + 255) / 256;
+            double time = (double)rounds * (tc.tfix + per * tc.tk);
+            if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
+            if (time < mem_floor) time = mem_floor;
+            if (slices > 1) time += 3.77 + 8.0 * (double)M * (double)N * slices / 4.13e6;
+            if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
     }
-    c.waves = (t.large_waves == 4 && c.tm == 256) ? 4 : 8;
+    c.waves = (t.large_waves == 4 && c.tm == 256 && c.tn == 256) ? 4 : 8;
     return c;
 }
 
@@ -630,8 +645,10 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
-    else if (c.tm == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    if (c.tm == 256 && c.tn == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
+    else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
+    else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
     else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
 }
 

@@ -106,6 +106,10 @@ def test_prefill_sized_batches(nfp, M, N, K):
     {"large_bm": 128, "large_split": 1},
     {"large_bm": 256, "large_split": 3},
     {"large_bm": 128, "large_split": 5},
+    {"large_bm": 256, "large_bn": 128, "large_split": 1},
+    {"large_bm": 128, "large_bn": 256, "large_split": 1},
+    {"large_bm": 256, "large_bn": 128, "large_split": 2},
+    {"large_bm": 128, "large_bn": 256, "large_split": 3},
     {"small_max_m": 0},                       # route a decode-sized batch through the tiled kernel
 ])
 def test_prefill_launch_shapes(nfp, knobs):
