@@ -68,7 +68,16 @@ struct LargeKernel {
     static constexpr int FM = WTM / 32, FN = WTN / 32;
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
     static constexpr int LDS_BYTES = 2 * STAGE;
-    static constexpr int SUBSTEPS = (KIND == kE4M3) ? 2 : 4;
+    static constexpr int SUBSTEPS = 2;                 // E4M3 loop: two substeps of 64 bytes
+    // slot plan of the FP16 loop (see there)
+    static constexpr int FM16 = WTM / 16, FN16 = WTN / 16;
+    static constexpr int MF = FM16 * FN16;                           // MFMAs per substep
+    static constexpr int NPRE = FN16 + 2;
+    static constexpr int NREST = FM16 - 2;
+    static constexpr int RSTR = (3 * FN16) / 4 > 0 ? (3 * FN16) / 4 : 1;      // slots between the early token reads
+    static constexpr int QB = (NREST - 1) * RSTR + 3;                // slot that starts with the barrier
+    static constexpr int TSTR = (MF - QB) / NPRE > 0 ? (MF - QB) / NPRE : 1;  // slots between the look-ahead reads
+    static constexpr int TAIL0 = MF - NPRE * TSTR;
 
     // MFMA operand fragments of one K substep (16 halves / 64 E4M3 bytes per row)
     struct Frags {
@@ -127,22 +136,19 @@ struct LargeKernel {
     // a load instruction blocks the issue of whatever is behind it while the address queue is
     // full, and those waves have the time to spare.
     static constexpr int DW = WAVES == 8 ? 4 : WAVES;  // waves that issue direct-to-LDS loads
-    // The younger waves of a workgroup with two waves per SIMD do their share of the plane merge
-    // half a K-tile after the older ones, so that a SIMD never has both of its waves in the
-    // merge (and none in the matrix pipe) at the same time.
     static constexpr bool kTwoRoles = WAVES != DW;
-    // The planes are loaded, merged and written to LDS 16 weights (16 bytes of each plane, two
-    // FP16 chunks) at a time; a weight row is four such pieces.  A group of 256 threads takes
-    // 64 rows per pass; within a wave lane l takes row l % 16, column group l / 16 of a 16-row
-    // tile: the chunk order of the packed blocks, and 16 consecutive lanes then write one
-    // chunk column of 16 consecutive rows, the bank pattern of the fragment reads.  With two waves per SIMD the older waves have time to spare (see DW)
-    // and take three passes out of four.
-    static constexpr int PASSES = TN / 64;             // 64-row passes over the weight tile
-    static constexpr int NP_OLD = kTwoRoles ? (3 * PASSES + 3) / 4 : PASSES;
-    static constexpr int NP_YNG = kTwoRoles ? PASSES - NP_OLD : 0;
-    static constexpr int PWP = NP_OLD;                 // register pieces per thread (the larger share)
-    struct PlaneRegs { u32x4 w[2 * PWP]; };
-    struct PlaneOffsets { uint32_t w[PWP]; uint32_t kpos, lim; };
+    // The planes are loaded, merged and written to LDS one packed 1 KB block of each plane at a
+    // time (a "piece": 16 rows x 64 columns; lane l holds chunk l, i.e. row l % 16, columns
+    // 16 * (l / 16) .. +15).  16 consecutive lanes then write one chunk column of 16 consecutive
+    // rows, the bank pattern of the fragment reads.  The older wave of a SIMD wins every
+    // arbitration and has time to spare, so the loading waves take three of every four pieces
+    // (measured: 3:1 beats 2:2 and 4:0); a weight tile of 128 rows is merged by them alone.
+    static constexpr int NPO = TN == 256 ? 3 : 2;         // pieces of an older (loading) wave
+    static constexpr int NPY = TN / 64 - NPO;             // pieces of a younger wave
+    static constexpr int NPW = NPO > NPY ? NPO : NPY;
+    template <bool OLDER> static constexpr int pieces() { return OLDER ? NPO : NPY; }
+    struct PlaneRegs { u32x4 u[NPW], l[NPW]; };
+    struct PlaneOffsets { uint32_t lane_off; uint32_t lds_off; uint32_t lim; };
     static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
     static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
 
@@ -217,11 +223,8 @@ struct LargeKernel {
     struct Ctx {
         floatx16 (&acc)[FN][FM];
         Frags (&fr)[2];
-        PlaneRegs &pf;
-        u32x4 merged;                                   // FP16 chunk being assembled by the plane merge
-        const PlaneOffsets &off;
         const DmaOffsets &dof;
-        __amdgpu_buffer_rsrc_t rx, rw0, rw1;
+        __amdgpu_buffer_rsrc_t rx, rw0;
         uint8_t *lds;
         lds_byte *lds3;
         uint32_t x_lim, w_lim;
@@ -229,94 +232,74 @@ struct LargeKernel {
         int kt, cur;
     };
 
-    // The merge of a thread's PWP pieces (16 weights each) is cut into quarters of 4 weights
-    // (8 VALU instructions, Sec. 4.2 / Alg. 1) and spread over the MFMA slots of one substep:
-    // a SIMD hides about four plain VALU instructions behind each MFMA and no more.
-    // EARLY: older waves, right after the barrier of K-tile kt (registers hold K-tile kt+2, it
-    // goes into the stage just freed, the registers are refilled with kt+3).  Otherwise: younger
-    // waves, in substep 1 of K-tile kt (registers hold kt+1, which goes into the other stage,
-    // free since the barrier of kt-1; refill with kt+2).
-    template <bool EARLY> static constexpr int quarters() { return 4 * (EARLY ? NP_OLD : NP_YNG); }
-    template <bool EARLY> static constexpr int qps() { return (quarters<EARLY>() + MFMAS - 1) / MFMAS; }
-    // first quarter of slot q: spread evenly when there are fewer quarters than slots
-    template <bool EARLY> static constexpr int quarter_begin(int q) {
-        return quarters<EARLY>() >= MFMAS ? (q * qps<EARLY>() < quarters<EARLY>() ? q * qps<EARLY>() : quarters<EARLY>())
-                                         : (q * quarters<EARLY>() + MFMAS - 1) / MFMAS;
-    }
-
-    template <bool EARLY, int G>
-    static __device__ __forceinline__ void plane_quarter(Ctx &c) {
-        constexpr int I = G / 4, J = G % 4;             // piece, quarter within it
-        const uint32_t u = c.pf.w[2 * I][J], l = c.pf.w[2 * I + 1][J];
-        uint32_t a, b;
-        merge4(u, l, a, b);
-        c.merged[2 * (J & 1)] = a;
-        c.merged[2 * (J & 1) + 1] = b;
-        if constexpr ((J & 1) == 1) {
-            // two quarters = one 16-byte FP16 chunk of the row
-            const int t = threadIdx.x;
-            const int c4 = (t >> 4) & 3, row = (EARLY ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15) + 64 * I;
-            uint8_t *stage = c.lds + (EARLY ? c.cur : c.cur ^ 1) * STAGE;
-            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + (J >> 1))) = c.merged;
-        }
-        if constexpr (J == 3) {
-            const uint32_t ktn = (uint32_t)(c.kt + (EARLY ? 3 : 2));
-            const uint32_t kb = ktn * 1024u;
-            const uint32_t kill = (ktn < c.off.lim) ? 0u : 0x80000000u;
-            c.pf.w[2 * I] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, (c.off.w[I] + kb) | kill, 0, 0);
-            c.pf.w[2 * I + 1] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, (c.off.w[I] + kb) | kill, 0, 0);
-        }
-    }
-
-    template <bool EARLY, int G, int END>
-    static __device__ __forceinline__ void plane_quarters(Ctx &c) {
-        if constexpr (G < END) {
-            plane_quarter<EARLY, G>(c);
-            plane_quarters<EARLY, G + 1, END>(c);
-        }
-    }
-
-    template <bool OLDER>
-    static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p) {
-        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
-        const int t = threadIdx.x;
-        const int c4 = (t >> 4) & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15);
-        // packed planes: the 16 weights of row r, column group c4 of K-tile kt are chunk
-        // (r % 16) + 16 * c4 of block (r / 16, kt); a wave reads whole 1 KB blocks
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int row = r0 + 64 * i;
-            o.w[i] = (uint32_t)((row >> 4) * p.kblocks) * 1024u + (uint32_t)(((row & 15) + 16 * c4) << 4);
-        }
-        o.kpos = 0;
+    static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p, int wave, int lane) {
+        const int r = lane & 15, c4 = lane >> 4;
+        const int tile0 = wave < DW ? wave * NPO : DW * NPO + (wave - DW) * NPY;      // first row tile of the wave
+        o.lane_off = (uint32_t)(tile0 * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+        // FP16 stage: row 16 * row tile + r, 16-byte chunks 2 * c4 and 2 * c4 + 1 (XOR-swizzled)
+        o.lds_off = (uint32_t)(tile0 * 16 + r) * 128u + (uint32_t)(((2 * c4) ^ ((r >> 1) & 7)) << 4);
         o.lim = (uint32_t)p.kblocks;                    // block columns of the plane
     }
 
-    template <bool OLDER>
-    static __device__ __forceinline__ void load_planes(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
-                                                       __amdgpu_buffer_rsrc_t rw1, int kt) {
-        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
-        const uint32_t kb = (uint32_t)kt * 1024u;
+    template <int P>
+    static __device__ __forceinline__ void load_piece(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
+                                                      __amdgpu_buffer_rsrc_t rw1, int kblocks, int kt) {
         const uint32_t kill = ((uint32_t)kt < o.lim) ? 0u : 0x80000000u;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            pf.w[2 * i] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.w[i] + kb) | kill, 0, 0);
-            pf.w[2 * i + 1] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.w[i] + kb) | kill, 0, 0);
-        }
+        const uint32_t soff = (uint32_t)(P * kblocks + kt) * 1024u;
+        pf.u[P] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.lane_off + soff) | kill, 0, 0);
+        pf.l[P] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.lane_off + soff) | kill, 0, 0);
     }
 
-    template <bool OLDER>
-    static __device__ __forceinline__ void store_planes(const PlaneRegs &pf, uint8_t *stage) {
-        constexpr int NP = OLDER ? NP_OLD : NP_YNG;
-        const int t = threadIdx.x;
-        const int c4 = (t >> 4) & 3, r0 = (OLDER ? 0 : 64 * NP_OLD) + 16 * ((t & 255) >> 6) + (t & 15);
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int row = r0 + 64 * i;
-            u32x4 w_lo, w_hi;
-            merge16(pf.w[2 * i], pf.w[2 * i + 1], w_lo, w_hi);       // Sec. 4.2, Alg. 1
-            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4)) = w_lo;
-            *reinterpret_cast<u32x4 *>(stage + swz(row, 2 * c4 + 1)) = w_hi;
+    // Sec. 4.2, Alg. 1 on the J-th four weights of piece P (8 VALU instructions); every second
+    // quarter completes a 16-byte chunk of the FP16 row, which goes into the tile of `stage`
+    template <int P, int J>
+    static __device__ __forceinline__ void merge_quarter(const PlaneRegs &pf, const PlaneOffsets &o, u32x4 &merged, uint8_t *stage) {
+        uint32_t w01, w23;
+        merge4(pf.u[P][J], pf.l[P][J], w01, w23);
+        merged[2 * (J & 1)] = w01;
+        merged[2 * (J & 1) + 1] = w23;
+        if constexpr ((J & 1) == 1)
+            *reinterpret_cast<u32x4 *>(stage + ((o.lds_off ^ (uint32_t)((J >> 1) << 4)) + P * 2048)) = merged;
+    }
+
+    // When the quarters of a wave's pieces run.  The registers of a piece hold K-tile kt+1 while
+    // K-tile kt is multiplied; it goes into the other stage (free since the barrier of kt-1) and
+    // the registers are reloaded with kt+2 right behind the piece's last quarter, most of a
+    // K-tile before they are needed again.  Older waves: pieces 0 and 1 in the first substep, 2
+    // in the head of the second (before the barrier), one quarter every few slots; younger
+    // waves: their piece spread over the first substep.
+    template <bool OLDER> static constexpr int piece_sub(int p) { return OLDER && p >= 2 ? 1 : 0; }
+    template <bool OLDER> static constexpr int piece_stride(int p) { return OLDER ? (MF >= 32 ? 4 : 1) : MF / 4; }
+    template <bool OLDER> static constexpr int piece_slot(int p) { return OLDER ? ((p & 1) ? MF / 2 : 0) : MF / 8; }
+    static_assert(NPO <= 3 && NPY <= 1 && NPY >= 0, "merge slots");
+    static_assert(KIND != kNestedF16 || NPO < 3 || 3 * piece_stride<true>(2) < QB, "merge slots");
+    // (piece * 4 + quarter) that runs at slot q of substep s, or -1
+    template <bool OLDER> static constexpr int quarter_at(int s, int q) {
+        for (int p = 0; p < pieces<OLDER>(); ++p)
+            if (piece_sub<OLDER>(p) == s && q >= piece_slot<OLDER>(p) && (q - piece_slot<OLDER>(p)) % piece_stride<OLDER>(p) == 0 &&
+                (q - piece_slot<OLDER>(p)) / piece_stride<OLDER>(p) < 4)
+                return 4 * p + (q - piece_slot<OLDER>(p)) / piece_stride<OLDER>(p);
+        return -1;
+    }
+
+    template <bool OLDER, int G, class C>
+    static __device__ __forceinline__ void plane_quarter(C &c) {
+        constexpr int P = G / 4, J = G % 4;
+        merge_quarter<P, J>(c.pf, c.off, c.merged, c.lds + (c.cur ^ 1) * STAGE);
+        if constexpr (J == 3) load_piece<P>(c.pf, c.off, c.rw0, c.rw1, c.kblocks, c.kt + 2);
+    }
+
+    // stage 0 is merged here; stage 1 is written in the first K-tile of the loop, as in every later one
+    template <bool OLDER, int P>
+    static __device__ __forceinline__ void plane_prologue(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
+                                                          __amdgpu_buffer_rsrc_t rw1, int kblocks, int kt_begin, uint8_t *lds) {
+        if constexpr (P < pieces<OLDER>()) {
+            u32x4 merged;
+            load_piece<P>(pf, o, rw0, rw1, kblocks, kt_begin);
+            merge_quarter<P, 0>(pf, o, merged, lds);  merge_quarter<P, 1>(pf, o, merged, lds);
+            merge_quarter<P, 2>(pf, o, merged, lds);  merge_quarter<P, 3>(pf, o, merged, lds);
+            load_piece<P>(pf, o, rw0, rw1, kblocks, kt_begin + 1);
+            plane_prologue<OLDER, P + 1>(pf, o, rw0, rw1, kblocks, kt_begin, lds);
         }
     }
 
@@ -337,11 +320,7 @@ struct LargeKernel {
 #pragma unroll
                 for (int d = Q * DPS; d < (Q + 1) * DPS && d < DMAS; ++d)
                     dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
-                if constexpr (KIND == kNestedF16)
-                    plane_quarters<true, quarter_begin<true>(Q), quarter_begin<true>(Q + 1)>(c);
             }
-        } else if constexpr (S == 1 && !OLDER && KIND == kNestedF16 && NP_YNG > 0) {
-            plane_quarters<false, quarter_begin<false>(Q), quarter_begin<false>(Q + 1)>(c);
         }
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (Q + 1 < MFMAS) slot<OLDER, S, Q + 1>(c);
@@ -372,11 +351,97 @@ struct LargeKernel {
         }
     }
 
-    template <int I, int END>
-    static __device__ __forceinline__ void dma_range(Ctx &c, int stage_idx, int kt) {
-        if constexpr (I < END) {
-            dma_one(I, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + stage_idx * STAGE, c.wave, kt);
-            dma_range<I + 1, END>(c, stage_idx, kt);
+    // ---- FP16 kinds: the same loop on v_mfma_f32_16x16x32_f16 --------------------------------
+    // Under the chip's power limit (which, not the issue rate, bounds a full-chip FP16 GEMM on
+    // random operands) the 16x16x32 instruction sustains about 15 % more flops than 32x32x16: it
+    // moves half as many accumulator registers per flop.  A K-tile is two substeps of 32 halves;
+    // a wave's tile is FN16 x FM16 blocks of 16 weight rows x 16 tokens, the MFMAs of a substep
+    // run token block by token block (the FN16 weight fragments stay, the token fragments
+    // stream).  LDS reads: the first NPRE fragments of a substep (all weight fragments, two token
+    // fragments) are fetched in the tail of the substep before it, the other token fragments
+    // early in the substep itself, about two token blocks ahead of their use.  The barrier of
+    // the K-tile sits in the second substep behind the last read of the current stage (slot QB);
+    // loads of K-tile kt+2, the older waves' plane merge and the reads of K-tile kt+1 follow it.
+    static constexpr int DPS16 = (DMAS + (MF - QB) - 1) / (MF - QB);
+    static_assert(KIND == kE4M3 || (FM16 >= 3 && TAIL0 >= QB && QB < MF), "slot plan of the 16x16x32 loop");
+    struct Frags16 { intx4 a[FN16]; intx4 b[FM16]; };
+
+    struct Ctx16 {
+        floatx4 (&acc)[FN16][FM16];
+        Frags16 (&fr)[2];
+        PlaneRegs &pf;
+        u32x4 merged;                                   // FP16 chunk being assembled by the plane merge
+        const PlaneOffsets &off;
+        const DmaOffsets &dof;
+        __amdgpu_buffer_rsrc_t rx, rw0, rw1;
+        uint8_t *lds;
+        lds_byte *lds3;
+        uint32_t x_lim, w_lim;
+        int wave, lane, wm, wn;
+        int kblocks;
+        int kt, cur;
+    };
+
+    // fragment R of substep s in the order of first use: weight blocks 0..FN16-1, token blocks 0..FM16-1;
+    // lane l takes row l % 16, halves 32*s + 8*(l/16) .. +7 (16x16x32 operand layout)
+    template <int R>
+    static __device__ __forceinline__ void read16(Frags16 &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        const int r16 = lane & 15, c = 4 * s + (lane >> 4);
+        if constexpr (R < FN16) f.a[R] = *reinterpret_cast<const intx4 *>(stage + swz(wn * WTN + 16 * R + r16, c));
+        else f.b[R - FN16] = *reinterpret_cast<const intx4 *>(stage + TN * 128 + swz(wm * WTM + 16 * (R - FN16) + r16, c));
+    }
+
+    template <int R, int END>
+    static __device__ __forceinline__ void read16_range(Frags16 &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        if constexpr (R < END) {
+            read16<R>(f, stage, wm, wn, lane, s);
+            read16_range<R + 1, END>(f, stage, wm, wn, lane, s);
+        }
+    }
+
+    template <bool OLDER, int S, int Q>
+    static __device__ __forceinline__ void slot16(Ctx16 &c) {
+        constexpr bool last = (S == 1);
+        if constexpr (last && Q == QB) {
+            // every read of the current stage has been issued; once all waves are here and their
+            // loads of the next K-tile have landed, the stage is free and the next one complete
+            // (the loading waves' plane loads of this K-tile are younger than those and may still fly)
+            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(KIND == kNestedF16 ? 2 * NPO : 0) : "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        {
+            constexpr int j = Q / FN16, i = Q % FN16;
+            union { intx4 v; half8 h; } a, b;
+            a.v = c.fr[S].a[i];
+            b.v = c.fr[S].b[j];
+            c.acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c.acc[i][j], 0, 0, 0);
+        }
+        if constexpr (Q % RSTR == 0 && Q / RSTR < NREST)
+            read16<FN16 + 2 + Q / RSTR>(c.fr[S], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
+        if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < NPRE)
+            read16<(Q - TAIL0) / TSTR>(c.fr[S ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn, c.lane, last ? 0 : 1);
+        if constexpr (last && Q >= QB) {
+            if constexpr (OLDER) {
+#pragma unroll
+                for (int d = (Q - QB) * DPS16; d < (Q - QB + 1) * DPS16 && d < DMAS; ++d)
+                    dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+            }
+        }
+        if constexpr (KIND == kNestedF16 && quarter_at<OLDER>(S, Q) >= 0) plane_quarter<OLDER, quarter_at<OLDER>(S, Q)>(c);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (Q + 1 < MF) slot16<OLDER, S, Q + 1>(c);
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void k_loop16(Ctx16 &c, int kt_begin, int kt_end) {
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            c.kt = kt;
+            c.cur = (kt - kt_begin) & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            slot16<OLDER, 0, 0>(c);
+            slot16<OLDER, 1, 0>(c);
         }
     }
 
@@ -407,14 +472,6 @@ struct LargeKernel {
         const int kt_begin = split * p.ktiles_per_split;
         const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
 
-        floatx16 acc[FN][FM];
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-            for (int j = 0; j < FM; ++j)
-#pragma unroll
-                for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-
         const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
         const __amdgpu_buffer_rsrc_t rw0 = KIND == kPlainF16
             ? tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes)
@@ -423,57 +480,74 @@ struct LargeKernel {
         DmaOffsets dof;
         make_dma_offsets(dof, p, wave, lane);
         PlaneOffsets off;
-        if (KIND == kNestedF16) {
-            if (!kTwoRoles || wave < DW) make_plane_offsets<true>(off, p);
-            else make_plane_offsets<false>(off, p);
-        }
+        if (KIND == kNestedF16) make_plane_offsets(off, p, wave, lane);
         PlaneRegs pf;
-        Frags fr[2];
-        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, (uint32_t)p.k_bytes,
-              KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes,
-              wave, lane, wm, wn, kt_begin, 0};
+        const uint32_t x_lim = (uint32_t)p.k_bytes;
+        const uint32_t w_lim = KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
 
         // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
         // into LDS; the planes take the register path (they have to pass through the merge).
-        // The one barrier per K-tile sits in front of the LAST substep: by then every wave holds
-        // that substep's fragments in registers, so the current stage is free for K-tile kt+2,
+        // There is one barrier per K-tile, placed where every wave has fetched the last
+        // fragments of the current stage: from there on the stage is free for K-tile kt+2,
         // and the first fragments of K-tile kt+1 are fetched underneath the last MFMAs.
         if (wave < DW) {
-            dma_range<0, DMAS>(c, 0, kt_begin);
-            dma_range<0, DMAS>(c, 1, kt_begin + 1);
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int i = 0; i < DMAS; ++i)
+                    dma_one(i, dof, x_lim, w_lim, rx, rw0, lds3 + st * STAGE, wave, kt_begin + st);
         }
         if (KIND == kNestedF16) {
-            if (!kTwoRoles || wave < DW) {
-                PlaneRegs pf1;
-                load_planes<true>(pf, off, rw0, rw1, kt_begin);
-                load_planes<true>(pf1, off, rw0, rw1, kt_begin + 1);
-                store_planes<true>(pf, lds);
-                store_planes<true>(pf1, lds + STAGE);
-                load_planes<true>(pf, off, rw0, rw1, kt_begin + 2);
-                // everything but the last plane loads (the token loads were issued before them)
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NP_OLD) : "memory");
-            } else {
-                // younger waves keep K-tile kt_begin+1 in registers: their share of it is
-                // written in substep 1 of the first K-tile, as in every later one
-                load_planes<false>(pf, off, rw0, rw1, kt_begin);
-                store_planes<false>(pf, lds);
-                load_planes<false>(pf, off, rw0, rw1, kt_begin + 1);
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NP_YNG) : "memory");
-            }
+            if (wave < DW) plane_prologue<true, 0>(pf, off, rw0, rw1, p.kblocks, kt_begin, lds);
+            else plane_prologue<false, 0>(pf, off, rw0, rw1, p.kblocks, kt_begin, lds);
+            // everything but the plane loads issued last (the token loads came before them all)
+            if (wave < DW) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NPO) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NPY) : "memory");
         } else {
             // the loads of K-tile kt_begin (a wave that issued none passes straight through)
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
         }
         __syncthreads();
-        read_all<0>(fr[0], lds, wm, wn, lane);
-        if (!kTwoRoles || wave < DW) k_loop<true>(c, kt_begin, kt_end);
-        else k_loop<false>(c, kt_begin, kt_end);
-        if (p.row_store && gridDim.y == 1) {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
-            __syncthreads();
-            epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
+
+        if constexpr (KIND == kE4M3) {
+            floatx16 acc[FN][FM];
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+            Frags fr[2];
+            Ctx c{acc, fr, dof, rx, rw0, lds, lds3, x_lim, w_lim, wave, lane, wm, wn, kt_begin, 0};
+            read_all<0>(fr[0], lds, wm, wn, lane);
+            if (!kTwoRoles || wave < DW) k_loop<true>(c, kt_begin, kt_end);
+            else k_loop<false>(c, kt_begin, kt_end);
+            if (p.row_store && gridDim.y == 1) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+                __syncthreads();
+                epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
+            } else {
+                epilogue(p, acc, m0, n0, wm, wn, lane, split);
+            }
         } else {
-            epilogue(p, acc, m0, n0, wm, wn, lane, split);
+            floatx4 acc[FN16][FM16];
+#pragma unroll
+            for (int i = 0; i < FN16; ++i)
+#pragma unroll
+                for (int j = 0; j < FM16; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+            Frags16 fr[2];
+            Ctx16 c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, x_lim, w_lim,
+                    wave, lane, wm, wn, p.kblocks, kt_begin, 0};
+            read16_range<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
+            if (!kTwoRoles || wave < DW) k_loop16<true>(c, kt_begin, kt_end);
+            else k_loop16<false>(c, kt_begin, kt_end);
+            if (p.row_store && gridDim.y == 1) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __syncthreads();
+                epilogue_lds16(p, acc, m0, n0, wm, wn, lane, wave, lds);
+            } else {
+                epilogue16(p, acc, m0, n0, wm, wn, lane, split);
+            }
         }
     }
 
@@ -506,6 +580,12 @@ struct LargeKernel {
                     *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * h) = o;
                 }
         }
+        store_tile_rows(p, m0, n0, lane, wave, lds);
+    }
+
+    // the FP16 tile in LDS goes out as whole rows, 16 bytes per lane
+    static __device__ __forceinline__ void store_tile_rows(const LargeParams &p, int m0, int n0, int lane, int wave,
+                                                           const uint8_t *lds) {
         __syncthreads();
         constexpr int RPI = 64 / OCH;                  // rows per store instruction
         constexpr int ROWS = TM / WAVES;               // rows per wave
@@ -517,6 +597,65 @@ struct LargeKernel {
             const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4));
             const int m = m0 + row;
             if (m < p.M && n < p.N) *reinterpret_cast<u32x4 *>(p.Y + (int64_t)m * p.ldy + n) = v;
+        }
+    }
+
+    // 16x16x32 accumulators: lane l holds token l % 16 and the four consecutive weight rows
+    // 4 * (l / 16) .. +3 of every 16x16 block
+    static __device__ __forceinline__ void epilogue_lds16(const LargeParams &p, floatx4 (&acc)[FN16][FM16], int m0, int n0,
+                                                          int wm, int wn, int lane, int wave, uint8_t *lds) {
+        const int r16 = lane & 15, q4 = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < FM16; ++j) {
+            const int row = wm * WTM + 16 * j + r16;
+#pragma unroll
+            for (int i = 0; i < FN16; ++i) {
+                const int col = wn * WTN + 16 * i + 4 * q4;
+                const int chunk = col >> 3;
+                u32x2 o;
+                o.x = float2_to_half2_bits(acc[i][j][0], acc[i][j][1]);
+                o.y = float2_to_half2_bits(acc[i][j][2], acc[i][j][3]);
+                *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * (q4 & 1)) = o;
+            }
+        }
+        store_tile_rows(p, m0, n0, lane, wave, lds);
+    }
+
+    static __device__ __forceinline__ void epilogue16(const LargeParams &p, floatx4 (&acc)[FN16][FM16], int m0, int n0,
+                                                      int wm, int wn, int lane, int split) {
+        const int r16 = lane & 15, q4 = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < FM16; ++j) {
+            const int m = m0 + wm * WTM + 16 * j + r16;
+            if (m >= p.M) continue;
+#pragma unroll
+            for (int i = 0; i < FN16; ++i) {
+                const int n = n0 + wn * WTN + 16 * i + 4 * q4;
+                if (n >= p.N) continue;
+                const floatx4 v = acc[i][j];
+                if (gridDim.y > 1) {
+                    float *dst = p.partials + ((int64_t)split * p.M + m) * p.N + n;
+                    if ((p.N & 3) == 0) {
+                        *reinterpret_cast<floatx4 *>(dst) = v;
+                    } else {
+                        for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
+                    }
+                } else {
+                    uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
+                    if (p.vec_store) {
+                        u32x2 o;
+                        o.x = float2_to_half2_bits(v[0], v[1]);
+                        o.y = float2_to_half2_bits(v[2], v[3]);
+                        *reinterpret_cast<u32x2 *>(dst) = o;
+                    } else {
+                        for (int e = 0; e < 4 && n + e < p.N; ++e) {
+                            union { _Float16 f; uint16_t u; } cv;
+                            cv.f = (_Float16)v[e];
+                            dst[e] = cv.u;
+                        }
+                    }
+                }
+            }
         }
     }
 
@@ -573,7 +712,7 @@ large_gemm_kernel(LargeParams p) {
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
-struct LargeConfig { int tm, tn, split, waves; };
+struct LargeConfig { int tm, tn, split; };
 
 // Tile shape and K split from a small cost model.  The workgroups are dealt round-robin to the
 // 256 CUs; a workgroup costs a fixed part plus a time per K-tile that depends on the tile shape
@@ -585,11 +724,11 @@ struct LargeConfig { int tm, tn, split, waves; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};    // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.331, 0.57}, {1.036, 0.0}, {1.113, 0.57}, {0.818, 0.0}},     // plain FP16
-    {{1.441, 1.59}, {1.106, 0.0}, {1.149, 1.30}, {0.913, 0.0}},     // NestedFP16
-    {{1.345, 6.36}, {1.091, 0.54}, {1.113, 2.10}, {0.882, 0.18}},   // E4M3
+    {{1.321, 0.69}, {1.019, 0.0}, {1.096, 0.50}, {0.811, 0.0}},     // plain FP16
+    {{1.408, 0.95}, {1.080, 0.0}, {1.013, 1.74}, {0.866, 0.0}},     // NestedFP16
+    {{1.337, 7.28}, {1.085, 1.12}, {1.110, 2.62}, {0.864, 0.85}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.42, 1.38, 1.41};
+static const double kPairSpeedup[3] = {1.46, 1.37, 1.41};
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -600,7 +739,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.43e6;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.47e6;
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
@@ -616,12 +755,11 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += 3.77 + 8.0 * (double)M * (double)N * slices / 4.13e6;
+            if (slices > 1) time += 4.32 + 8.0 * (double)M * (double)N * slices / 4.32e6;
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
     }
-    c.waves = (t.large_waves == 4 && c.tm == 256 && c.tn == 256) ? 4 : 8;
     return c;
 }
 
@@ -645,8 +783,7 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.tn == 256 && c.waves == 4) launch_large_t<KIND, 256, 256, 2, 2>(p, grid, stream);
-    else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
     else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
     else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
     else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);

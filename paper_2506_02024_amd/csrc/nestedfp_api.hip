@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
     return t;
 }
 
@@ -367,7 +367,7 @@ int nestedfp_linear(const uint16_t *X, int64_t M, int64_t ldx, const nestedfp_la
 }
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
-                                     "large_split", "large_bm", "large_bn", "large_waves", "large_epilogue", "small_fuse_quant", "quant_hw",
+                                     "large_split", "large_bm", "large_bn", "large_epilogue", "small_fuse_quant", "quant_hw",
                                      nullptr};
 
 const char *nestedfp_tune_name(int index) {
@@ -387,7 +387,6 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "large_split")) t.large_split = value;
     else if (!strcmp(knob, "large_bm")) t.large_bm = value;
     else if (!strcmp(knob, "large_bn")) t.large_bn = value;
-    else if (!strcmp(knob, "large_waves")) t.large_waves = value;
     else if (!strcmp(knob, "large_epilogue")) t.large_epilogue = value;
     else if (!strcmp(knob, "small_fuse_quant")) t.small_fuse_quant = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;

@@ -43,7 +43,6 @@ struct Tuning {
     int64_t large_split;     // grid-level split-K of the tiled kernel
     int64_t large_bm;        // tokens per tile of the tiled kernel (128 or 256)
     int64_t large_bn;        // weight rows per tile (128 or 256; unset: same as large_bm)
-    int64_t large_waves;     // waves per workgroup of the 256x256 tile (4 or 8)
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
     int64_t small_fuse_quant;  // 1: quantise activations inside the streaming kernel where it can
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
