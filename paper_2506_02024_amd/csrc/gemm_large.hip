@@ -8,11 +8,13 @@
 // of per wave.
 //
 // Tile: TM tokens x TN weight rows x 128 bytes of K per row (64 halves or 128 E4M3 bytes),
-// two LDS stages, 8 waves as 2 (tokens) x 4 (weight rows).  Weight rows are the MFMA "A"
-// operand and tokens the "B" operand, so a lane holds 4 consecutive output columns of one
-// token.  Tokens and plain / E4M3 weights reach LDS by direct-to-LDS buffer loads; FP16 rows
-// are 128 bytes with the 16-byte chunk index XOR-swizzled with the row so that the MFMA
-// fragment reads are free of bank conflicts, packed E4M3 blocks are copied as they are.
+// two LDS stages, 8 waves.  Weight rows are the MFMA "A" operand and tokens the "B" operand,
+// so a lane holds 4 consecutive output columns of one token.  Tokens and plain / E4M3 weights
+// reach LDS by direct-to-LDS buffer loads; FP16 rows are 128 bytes with the 16-byte chunk
+// index XOR-swizzled with the row so that the MFMA fragment reads are free of bank conflicts,
+// packed E4M3 blocks are copied as they are.
+#include <type_traits>
+
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -63,94 +65,109 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base
 
 template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 struct LargeKernel {
-    static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static_assert(WAVES == 8, "two waves per SIMD: one loading (older), one not");
+    static constexpr int THREADS = 64 * WAVES;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
-    static constexpr int FM = WTM / 32, FN = WTN / 32;
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
     static constexpr int LDS_BYTES = 2 * STAGE;
-    static constexpr int SUBSTEPS = 2;                 // E4M3 loop: two substeps of 64 bytes
-    // slot plan of the FP16 loop (see there)
-    static constexpr int FM16 = WTM / 16, FN16 = WTN / 16;
-    static constexpr int MF = FM16 * FN16;                           // MFMAs per substep
-    static constexpr int NPRE = FN16 + 2;
-    static constexpr int NREST = FM16 - 2;
-    static constexpr int RSTR = (3 * FN16) / 4 > 0 ? (3 * FN16) / 4 : 1;      // slots between the early token reads
-    static constexpr int QB = (NREST - 1) * RSTR + 3;                // slot that starts with the barrier
-    static constexpr int TSTR = (MF - QB) / NPRE > 0 ? (MF - QB) / NPRE : 1;  // slots between the look-ahead reads
-    static constexpr int TAIL0 = MF - NPRE * TSTR;
 
-    // MFMA operand fragments of one K substep (16 halves / 64 E4M3 bytes per row)
-    struct Frags {
-        intx4 a[FN][KIND == kE4M3 ? 2 : 1];
-        intx4 b[FM][KIND == kE4M3 ? 2 : 1];
-    };
+    // ---- MFMA tiling ------------------------------------------------------------------------
+    // FP16 kinds: v_mfma_f32_16x16x32_f16.  Under the chip's power limit (which, not the issue
+    // rate, bounds a full-chip FP16 GEMM on random operands) it sustains about 15 % more flops
+    // than 32x32x16: it moves half as many accumulator registers per flop.  E4M3:
+    // v_mfma_scale_f32_32x32x64_f8f6f4 (the 16x16x128 shape would need more fragment registers
+    // than a wave with a 128x64 tile has).  A wave's tile is FNB x FMB blocks of MB weight rows x
+    // MB tokens; a K-tile (128 bytes per row) is two substeps of 64 bytes per row; a fragment is
+    // NCH 16-byte chunks per lane: lane l supplies row l % MB and bytes 16 * NCH * (l / MB) .. of
+    // the substep's 64.
+    static constexpr int MB = KIND == kE4M3 ? 32 : 16;
+    static constexpr int SUBS = 2;
+    static constexpr int NCH = KIND == kE4M3 ? 2 : 1;
+    static constexpr int FMB = WTM / MB, FNB = WTN / MB;
+    static constexpr int MF = FMB * FNB;                             // MFMAs per substep
+    typedef typename std::conditional<MB == 32, floatx16, floatx4>::type AccT;
+    // Slot plan of a substep.  The MFMAs run token block by token block (the FNB weight
+    // fragments stay, the token fragments stream).  The first NPRE fragments of a substep (all
+    // weight fragments, up to two token fragments) are fetched in the tail of the substep before
+    // it, the other token fragments early in the substep itself, about two token blocks ahead of
+    // their use.  The one barrier of a K-tile sits in its second substep behind the last read of
+    // the current stage (slot QB): from there on the stage is free for K-tile kt+2; the loads of
+    // kt+2 and the first reads of kt+1 follow it.
+    static constexpr int NB0 = FMB < 2 ? FMB : 2;
+    static constexpr int NPRE = FNB + NB0;
+    static constexpr int NREST = FMB - NB0;
+    static constexpr int RSTR = (3 * FNB) / 4 > 0 ? (3 * FNB) / 4 : 1;        // slots between the early token reads
+    static constexpr int QB = NREST > 0 ? (NREST - 1) * RSTR + (MB == 32 ? 2 : 3) : 0;   // slot that starts with the barrier
+    static constexpr int RPT = (NPRE + (MF - QB) - 1) / (MF - QB);            // look-ahead reads per tail slot
+    static constexpr int TSLOTS = (NPRE + RPT - 1) / RPT;                     // tail slots that read
+    static constexpr int TSTR = (MF - QB) / TSLOTS;                           // slots between them
+    static constexpr int TAIL0 = MF - TSLOTS * TSTR;
+    static_assert(QB < MF && TAIL0 >= QB && TSTR >= 1, "slot plan");
 
-    // The r-th LDS read of a substep's fragments, in the order the MFMAs need them:
-    // a[0], b[0..FM-1], a[1..FN-1] (NC reads each).
+    struct Frags { intx4 a[FNB][NCH]; intx4 b[FMB][NCH]; };
+
+    // LDS address of chunk q of a weight fragment: row, substep s, lane group g = l / MB.
+    // FP16 kinds: rows of 128 bytes, XOR-swizzled.  E4M3: the stage holds the packed 1 KB blocks
+    // as they are in memory, [row tile][2 blocks]; a substep is one block, and 16 lanes with
+    // consecutive rows read 256 consecutive bytes.
+    static __device__ __forceinline__ int w_addr(int row, int s, int g, int q) {
+        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (NCH * g + q)) << 4);
+        return swz(row, 4 * s + NCH * g + q);
+    }
+
+    // fragment R of substep s in the order of first use: weight blocks 0..FNB-1, token blocks 0..FMB-1
     template <int R>
-    static __device__ __forceinline__ void read_one(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        constexpr int NC = KIND == kE4M3 ? 2 : 1;
-        constexpr int F = R / NC, Q = R % NC;              // fragment index in issue order, chunk within it
-        const uint8_t *sW = stage, *sX = stage + TN * 128;
-        const int r32 = lane & 31, h = lane >> 5;
-        const int c = NC * (2 * s + h) + Q;
-        if (F == 0) f.a[0][Q] = *reinterpret_cast<const intx4 *>(sW + w_addr(wn * WTN + r32, s, h, Q));
-        else if (F <= FM) f.b[F - 1][Q] = *reinterpret_cast<const intx4 *>(sX + swz(wm * WTM + 32 * (F - 1) + r32, c));
-        else f.a[F - FM][Q] = *reinterpret_cast<const intx4 *>(sW + w_addr(wn * WTN + 32 * (F - FM) + r32, s, h, Q));
+    static __device__ __forceinline__ void read_frag(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        const int r = lane % MB, g = lane / MB;
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            if constexpr (R < FNB)
+                f.a[R][q] = *reinterpret_cast<const intx4 *>(stage + w_addr(wn * WTN + MB * R + r, s, g, q));
+            else
+                f.b[R - FNB][q] = *reinterpret_cast<const intx4 *>(
+                    stage + TN * 128 + swz(wm * WTM + MB * (R - FNB) + r, 4 * s + NCH * g + q));
+        }
     }
 
-    // LDS address of a weight fragment chunk.  FP16 kinds: rows of 128 bytes, XOR-swizzled.
-    // E4M3: the stage holds the packed 1 KB blocks as they are in memory, [row tile][2 blocks];
-    // a substep is one block, and 16 lanes with consecutive rows read 256 consecutive bytes.
-    static __device__ __forceinline__ int w_addr(int row, int s, int h, int q) {
-        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (2 * h + q)) << 4);
-        return swz(row, 2 * s + h);
+    template <int R, int END>
+    static __device__ __forceinline__ void read_frags(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        if constexpr (R < END) {
+            read_frag<R>(f, stage, wm, wn, lane, s);
+            read_frags<R + 1, END>(f, stage, wm, wn, lane, s);
+        }
     }
 
+    // weight rows are the "A" operand, tokens the "B" operand: a lane gets one token of the block
+    // and groups of four consecutive weight rows
     template <int Q>
-    static __device__ __forceinline__ void mfma_one(const Frags &f, floatx16 (&acc)[FN][FM]) {
-        constexpr int i = Q / FM, j = Q % FM;
-        if (KIND == kE4M3) {
-            intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w,
-                       f.a[i][NC1].x, f.a[i][NC1].y, f.a[i][NC1].z, f.a[i][NC1].w};
-            intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w,
-                       f.b[j][NC1].x, f.b[j][NC1].y, f.b[j][NC1].z, f.b[j][NC1].w};
+    static __device__ __forceinline__ void mfma_one(const Frags &f, AccT (&acc)[FNB][FMB]) {
+        constexpr int j = Q / FNB, i = Q % FNB;
+        if constexpr (KIND == kE4M3) {
+            intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w, f.a[i][NCH - 1].x, f.a[i][NCH - 1].y, f.a[i][NCH - 1].z, f.a[i][NCH - 1].w};
+            intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w, f.b[j][NCH - 1].x, f.b[j][NCH - 1].y, f.b[j][NCH - 1].z, f.b[j][NCH - 1].w};
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
         } else {
             union { intx4 v; half8 h; } a, b;
             a.v = f.a[i][0];
             b.v = f.b[j][0];
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc[i][j], 0, 0, 0);
         }
     }
-
-    static constexpr int NC1 = KIND == kE4M3 ? 1 : 0;
 
     // ---- direct-to-LDS loads (buffer_load ... lds) -------------------------------------------
     // One wave instruction fills 1 KB of LDS = 8 tile rows in lane order (lane l -> row l/8,
     // physical chunk l%8), so the XOR swizzle is applied on the global side: lane l fetches
     // the logical chunk (l%8) ^ ((row>>1)&7) of its row.  No VGPR staging, no ds_write.
-    static constexpr int WAVES = WAVES_M * WAVES_N;
     // With two waves per SIMD the older one wins every arbitration and reaches the barrier long
     // before the younger one.  The loads are therefore issued by the older four waves only:
     // a load instruction blocks the issue of whatever is behind it while the address queue is
     // full, and those waves have the time to spare.
-    static constexpr int DW = WAVES == 8 ? 4 : WAVES;  // waves that issue direct-to-LDS loads
-    static constexpr bool kTwoRoles = WAVES != DW;
-    // The planes are loaded, merged and written to LDS one packed 1 KB block of each plane at a
-    // time (a "piece": 16 rows x 64 columns; lane l holds chunk l, i.e. row l % 16, columns
-    // 16 * (l / 16) .. +15).  16 consecutive lanes then write one chunk column of 16 consecutive
-    // rows, the bank pattern of the fragment reads.  The older wave of a SIMD wins every
-    // arbitration and has time to spare, so the loading waves take three of every four pieces
-    // (measured: 3:1 beats 2:2 and 4:0); a weight tile of 128 rows is merged by them alone.
-    static constexpr int NPO = TN == 256 ? 3 : 2;         // pieces of an older (loading) wave
-    static constexpr int NPY = TN / 64 - NPO;             // pieces of a younger wave
-    static constexpr int NPW = NPO > NPY ? NPO : NPY;
-    template <bool OLDER> static constexpr int pieces() { return OLDER ? NPO : NPY; }
-    struct PlaneRegs { u32x4 u[NPW], l[NPW]; };
-    struct PlaneOffsets { uint32_t lane_off; uint32_t lds_off; uint32_t lim; };
+    static constexpr int DW = 4;                       // waves that issue direct-to-LDS loads
     static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
     static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
+    static constexpr int DMAS = XG + (KIND == kNestedF16 ? 0 : WG8);   // loads per loading wave per K-tile
+    static constexpr int DPS = (DMAS + (MF - QB) - 1) / (MF - QB);     // loads per slot behind the barrier
 
     struct DmaOffsets {
         uint32_t x[XG], w[WG8];
@@ -205,32 +222,19 @@ struct LargeKernel {
         }
     }
 
-    // ---- the K loop as an explicit instruction schedule ---------------------------------------
-    // Every MFMA of a substep is followed by the few other instructions assigned to its slot
-    // and a scheduling fence, so the order below is the order in the binary:
-    //   * LDS reads of the next substep's fragments, one (FP16) or two (E4M3) per MFMA, in the
-    //     order the MFMAs will need them;
-    //   * the direct-to-LDS loads, spread over three substeps so that the eight waves never
-    //     fill the texture-address queue (a wave that cannot issue its load cannot issue the
-    //     MFMA behind it either);
-    //   * for the planes: merge + LDS write + reload, one 16-weight piece at a time.
-    static constexpr int READS = (FN + FM) * (KIND == kE4M3 ? 2 : 1);
-    static constexpr int MFMAS = FN * FM;
-    static constexpr int RPS = (READS + MFMAS - 1) / MFMAS;            // reads per slot
-    static constexpr int DMAS = XG + (KIND == kNestedF16 ? 0 : WG8);   // loads per wave per K-tile
-    static constexpr int DPS = (DMAS + MFMAS - 1) / MFMAS;             // loads per slot of the last substep
-
-    struct Ctx {
-        floatx16 (&acc)[FN][FM];
-        Frags (&fr)[2];
-        const DmaOffsets &dof;
-        __amdgpu_buffer_rsrc_t rx, rw0;
-        uint8_t *lds;
-        lds_byte *lds3;
-        uint32_t x_lim, w_lim;
-        int wave, lane, wm, wn;
-        int kt, cur;
-    };
+    // ---- plane merge (NestedFP16) -------------------------------------------------------------
+    // The planes are loaded, merged and written to LDS one packed 1 KB block of each plane at a
+    // time (a "piece": 16 rows x 64 columns; lane l holds chunk l, i.e. row l % 16, columns
+    // 16 * (l / 16) .. +15).  16 consecutive lanes then write one chunk column of 16 consecutive
+    // rows, the bank pattern of the fragment reads.  The older wave of a SIMD has time to spare,
+    // so the loading waves take three of every four pieces (measured: 3:1 beats 2:2 and 4:0); a
+    // weight tile of 128 rows is merged by them alone.
+    static constexpr int NPO = TN == 256 ? 3 : 2;         // pieces of an older (loading) wave
+    static constexpr int NPY = TN / 64 - NPO;             // pieces of a younger wave
+    static constexpr int NPW = NPO > NPY ? NPO : NPY;
+    template <bool OLDER> static constexpr int pieces() { return OLDER ? NPO : NPY; }
+    struct PlaneRegs { u32x4 u[NPW], l[NPW]; };
+    struct PlaneOffsets { uint32_t lane_off; uint32_t lds_off; uint32_t lim; };
 
     static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p, int wave, int lane) {
         const int r = lane & 15, c4 = lane >> 4;
@@ -282,13 +286,6 @@ struct LargeKernel {
         return -1;
     }
 
-    template <bool OLDER, int G, class C>
-    static __device__ __forceinline__ void plane_quarter(C &c) {
-        constexpr int P = G / 4, J = G % 4;
-        merge_quarter<P, J>(c.pf, c.off, c.merged, c.lds + (c.cur ^ 1) * STAGE);
-        if constexpr (J == 3) load_piece<P>(c.pf, c.off, c.rw0, c.rw1, c.kblocks, c.kt + 2);
-    }
-
     // stage 0 is merged here; stage 1 is written in the first K-tile of the loop, as in every later one
     template <bool OLDER, int P>
     static __device__ __forceinline__ void plane_prologue(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
@@ -303,72 +300,14 @@ struct LargeKernel {
         }
     }
 
-    // OLDER: one of the DW waves that issue the direct-to-LDS loads.  The K loop exists once per
-    // role so that it has no branches inside.
-    template <bool OLDER, int S, int Q>
-    static __device__ __forceinline__ void slot(Ctx &c) {
-        constexpr bool last = (S == SUBSTEPS - 1);
-        mfma_one<Q>(c.fr[S & 1], c.acc);
-        {   // fragments of the following substep (of the next K-tile after the barrier)
-            const uint8_t *src = c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE;
-            constexpr int s_next = last ? 0 : S + 1;
-            Frags &dst = c.fr[(S + 1) & 1];
-            read_range<Q * RPS, (Q + 1) * RPS < READS ? (Q + 1) * RPS : READS>(dst, src, c.wm, c.wn, c.lane, s_next);
-        }
-        if constexpr (last) {
-            if constexpr (OLDER) {
-#pragma unroll
-                for (int d = Q * DPS; d < (Q + 1) * DPS && d < DMAS; ++d)
-                    dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (Q + 1 < MFMAS) slot<OLDER, S, Q + 1>(c);
-    }
-
-    template <bool OLDER, int S>
-    static __device__ __forceinline__ void substeps(Ctx &c) {
-        if constexpr (S == SUBSTEPS - 1) {
-            // Everything this wave still needs from the current stage is in registers.  Once all
-            // waves are here and their loads of the next K-tile have landed, the current stage
-            // is free and the next one complete.
-            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        slot<OLDER, S, 0>(c);
-        if constexpr (S + 1 < SUBSTEPS) substeps<OLDER, S + 1>(c);
-    }
-
-    template <bool OLDER>
-    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            c.kt = kt;
-            c.cur = (kt - kt_begin) & 1;
-            __builtin_amdgcn_sched_barrier(0);
-            substeps<OLDER, 0>(c);
-        }
-    }
-
-    // ---- FP16 kinds: the same loop on v_mfma_f32_16x16x32_f16 --------------------------------
-    // Under the chip's power limit (which, not the issue rate, bounds a full-chip FP16 GEMM on
-    // random operands) the 16x16x32 instruction sustains about 15 % more flops than 32x32x16: it
-    // moves half as many accumulator registers per flop.  A K-tile is two substeps of 32 halves;
-    // a wave's tile is FN16 x FM16 blocks of 16 weight rows x 16 tokens, the MFMAs of a substep
-    // run token block by token block (the FN16 weight fragments stay, the token fragments
-    // stream).  LDS reads: the first NPRE fragments of a substep (all weight fragments, two token
-    // fragments) are fetched in the tail of the substep before it, the other token fragments
-    // early in the substep itself, about two token blocks ahead of their use.  The barrier of
-    // the K-tile sits in the second substep behind the last read of the current stage (slot QB);
-    // loads of K-tile kt+2, the older waves' plane merge and the reads of K-tile kt+1 follow it.
-    static constexpr int DPS16 = (DMAS + (MF - QB) - 1) / (MF - QB);
-    static_assert(KIND == kE4M3 || (FM16 >= 3 && TAIL0 >= QB && QB < MF), "slot plan of the 16x16x32 loop");
-    struct Frags16 { intx4 a[FN16]; intx4 b[FM16]; };
-
-    struct Ctx16 {
-        floatx4 (&acc)[FN16][FM16];
-        Frags16 (&fr)[2];
+    // ---- the K loop as an explicit instruction schedule ---------------------------------------
+    // Every MFMA is followed by the few other instructions assigned to its slot and a scheduling
+    // fence, so the order below is the order in the binary.  OLDER: one of the DW waves that
+    // issue the direct-to-LDS loads; the loop exists once per role so that it has no branches
+    // inside.  PAR: which of the two fragment sets the substep multiplies.
+    struct Ctx {
+        AccT (&acc)[FNB][FMB];
+        Frags (&fr)[2];
         PlaneRegs &pf;
         u32x4 merged;                                   // FP16 chunk being assembled by the plane merge
         const PlaneOffsets &off;
@@ -382,26 +321,9 @@ struct LargeKernel {
         int kt, cur;
     };
 
-    // fragment R of substep s in the order of first use: weight blocks 0..FN16-1, token blocks 0..FM16-1;
-    // lane l takes row l % 16, halves 32*s + 8*(l/16) .. +7 (16x16x32 operand layout)
-    template <int R>
-    static __device__ __forceinline__ void read16(Frags16 &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        const int r16 = lane & 15, c = 4 * s + (lane >> 4);
-        if constexpr (R < FN16) f.a[R] = *reinterpret_cast<const intx4 *>(stage + swz(wn * WTN + 16 * R + r16, c));
-        else f.b[R - FN16] = *reinterpret_cast<const intx4 *>(stage + TN * 128 + swz(wm * WTM + 16 * (R - FN16) + r16, c));
-    }
-
-    template <int R, int END>
-    static __device__ __forceinline__ void read16_range(Frags16 &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        if constexpr (R < END) {
-            read16<R>(f, stage, wm, wn, lane, s);
-            read16_range<R + 1, END>(f, stage, wm, wn, lane, s);
-        }
-    }
-
-    template <bool OLDER, int S, int Q>
-    static __device__ __forceinline__ void slot16(Ctx16 &c) {
-        constexpr bool last = (S == 1);
+    template <bool OLDER, int S, int PAR, int Q>
+    static __device__ __forceinline__ void slot(Ctx &c) {
+        constexpr bool last = (S == SUBS - 1);
         if constexpr (last && Q == QB) {
             // every read of the current stage has been issued; once all waves are here and their
             // loads of the next K-tile have landed, the stage is free and the next one complete
@@ -411,53 +333,36 @@ struct LargeKernel {
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
         }
-        {
-            constexpr int j = Q / FN16, i = Q % FN16;
-            union { intx4 v; half8 h; } a, b;
-            a.v = c.fr[S].a[i];
-            b.v = c.fr[S].b[j];
-            c.acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c.acc[i][j], 0, 0, 0);
-        }
+        mfma_one<Q>(c.fr[PAR], c.acc);
         if constexpr (Q % RSTR == 0 && Q / RSTR < NREST)
-            read16<FN16 + 2 + Q / RSTR>(c.fr[S], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
-        if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < NPRE)
-            read16<(Q - TAIL0) / TSTR>(c.fr[S ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn, c.lane, last ? 0 : 1);
-        if constexpr (last && Q >= QB) {
-            if constexpr (OLDER) {
-#pragma unroll
-                for (int d = (Q - QB) * DPS16; d < (Q - QB + 1) * DPS16 && d < DMAS; ++d)
-                    dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
-            }
+            read_frag<FNB + NB0 + Q / RSTR>(c.fr[PAR], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
+        if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < TSLOTS) {
+            constexpr int r0 = (Q - TAIL0) / TSTR * RPT;
+            read_frags<r0, (r0 + RPT < NPRE ? r0 + RPT : NPRE)>(c.fr[PAR ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn,
+                                                                c.lane, last ? 0 : S + 1);
         }
-        if constexpr (KIND == kNestedF16 && quarter_at<OLDER>(S, Q) >= 0) plane_quarter<OLDER, quarter_at<OLDER>(S, Q)>(c);
+        if constexpr (last && OLDER && Q >= QB) {
+#pragma unroll
+            for (int d = (Q - QB) * DPS; d < (Q - QB + 1) * DPS && d < DMAS; ++d)
+                dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+        }
+        if constexpr (KIND == kNestedF16 && quarter_at<OLDER>(S, Q) >= 0) {
+            constexpr int G = quarter_at<OLDER>(S, Q);
+            merge_quarter<G / 4, G % 4>(c.pf, c.off, c.merged, c.lds + (c.cur ^ 1) * STAGE);
+            if constexpr (G % 4 == 3) load_piece<G / 4>(c.pf, c.off, c.rw0, c.rw1, c.kblocks, c.kt + 2);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (Q + 1 < MF) slot16<OLDER, S, Q + 1>(c);
+        if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
     }
 
     template <bool OLDER>
-    static __device__ __forceinline__ void k_loop16(Ctx16 &c, int kt_begin, int kt_end) {
+    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             c.kt = kt;
             c.cur = (kt - kt_begin) & 1;
             __builtin_amdgcn_sched_barrier(0);
-            slot16<OLDER, 0, 0>(c);
-            slot16<OLDER, 1, 0>(c);
-        }
-    }
-
-    template <int R, int END>
-    static __device__ __forceinline__ void read_range(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        if constexpr (R < END) {
-            read_one<R>(f, stage, wm, wn, lane, s);
-            read_range<R + 1, END>(f, stage, wm, wn, lane, s);
-        }
-    }
-
-    template <int R>
-    static __device__ __forceinline__ void read_all(Frags &f, const uint8_t *stage, int wm, int wn, int lane) {
-        if constexpr (R < READS) {
-            read_one<R>(f, stage, wm, wn, lane, 0);
-            read_all<R + 1>(f, stage, wm, wn, lane);
+            slot<OLDER, 0, 0, 0>(c);
+            slot<OLDER, 1, 1, 0>(c);
         }
     }
 
@@ -487,9 +392,6 @@ struct LargeKernel {
 
         // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
         // into LDS; the planes take the register path (they have to pass through the merge).
-        // There is one barrier per K-tile, placed where every wave has fetched the last
-        // fragments of the current stage: from there on the stage is free for K-tile kt+2,
-        // and the first fragments of K-tile kt+1 are fetched underneath the last MFMAs.
         if (wave < DW) {
 #pragma unroll
             for (int st = 0; st < 2; ++st)
@@ -509,83 +411,63 @@ struct LargeKernel {
         }
         __syncthreads();
 
-        if constexpr (KIND == kE4M3) {
-            floatx16 acc[FN][FM];
+        AccT acc[FNB][FMB];
 #pragma unroll
-            for (int i = 0; i < FN; ++i)
+        for (int i = 0; i < FNB; ++i)
 #pragma unroll
-                for (int j = 0; j < FM; ++j)
+            for (int j = 0; j < FMB; ++j)
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-            Frags fr[2];
-            Ctx c{acc, fr, dof, rx, rw0, lds, lds3, x_lim, w_lim, wave, lane, wm, wn, kt_begin, 0};
-            read_all<0>(fr[0], lds, wm, wn, lane);
-            if (!kTwoRoles || wave < DW) k_loop<true>(c, kt_begin, kt_end);
-            else k_loop<false>(c, kt_begin, kt_end);
-            if (p.row_store && gridDim.y == 1) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
-                __syncthreads();
-                epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
-            } else {
-                epilogue(p, acc, m0, n0, wm, wn, lane, split);
-            }
+                for (int q = 0; q < (MB == 32 ? 16 : 4); ++q) acc[i][j][q] = 0.f;
+        Frags fr[2];
+        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, x_lim, w_lim,
+              wave, lane, wm, wn, p.kblocks, kt_begin, 0};
+        read_frags<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
+        if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
+        else k_loop<false>(c, kt_begin, kt_end);
+        if (p.row_store && gridDim.y == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+            __syncthreads();
+            epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
         } else {
-            floatx4 acc[FN16][FM16];
-#pragma unroll
-            for (int i = 0; i < FN16; ++i)
-#pragma unroll
-                for (int j = 0; j < FM16; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-            Frags16 fr[2];
-            Ctx16 c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, x_lim, w_lim,
-                    wave, lane, wm, wn, p.kblocks, kt_begin, 0};
-            read16_range<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
-            if (!kTwoRoles || wave < DW) k_loop16<true>(c, kt_begin, kt_end);
-            else k_loop16<false>(c, kt_begin, kt_end);
-            if (p.row_store && gridDim.y == 1) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __syncthreads();
-                epilogue_lds16(p, acc, m0, n0, wm, wn, lane, wave, lds);
-            } else {
-                epilogue16(p, acc, m0, n0, wm, wn, lane, split);
-            }
+            epilogue(p, acc, m0, n0, wm, wn, lane, split);
         }
     }
 
     // Result tile through LDS: the MFMA layout leaves a lane with 4 consecutive outputs of one
-    // token, so direct stores are 8-byte pieces scattered over 32 rows per instruction.  Written
+    // token, so direct stores are 8-byte pieces scattered over 16 or 32 rows per instruction.  Written
     // to LDS as FP16 first (16-byte chunks XOR-swizzled with the row), the tile goes out as
     // whole rows, 16 bytes per lane, every store instruction covering complete 128-byte lines.
     // The caller guarantees that no wave still reads the operand stages.
     static constexpr int OCH = TN * 2 / 16;            // 16-byte chunks per output row
     static_assert(TM * TN * 2 <= LDS_BYTES, "output tile must fit into the operand stages");
-    static __device__ __forceinline__ void epilogue_lds(const LargeParams &p, floatx16 (&acc)[FN][FM], int m0, int n0,
+    // Accumulator layout: lane l holds token l % MB of a block and, for v = 0 .. MB*MB/256 - 1,
+    // the four consecutive weight rows (MB == 32 ? 8 v + 4 (l / 32) : 4 (l / 16)) .. +3.
+    static constexpr int NV = MB == 32 ? 4 : 1;
+    static __device__ __forceinline__ int acc_col(int lane, int v) { return MB == 32 ? 8 * v + 4 * (lane >> 5) : 4 * (lane >> 4); }
+
+    static __device__ __forceinline__ void epilogue_lds(const LargeParams &p, AccT (&acc)[FNB][FMB], int m0, int n0,
                                                         int wm, int wn, int lane, int wave, uint8_t *lds) {
-        const int r32 = lane & 31, h = lane >> 5;
+        const int r = lane % MB;
 #pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const int row = wm * WTM + 32 * j + r32;
+        for (int j = 0; j < FMB; ++j) {
+            const int row = wm * WTM + MB * j + r;
             float s = 1.0f;
             if (KIND == kE4M3) {
                 const int m = m0 + row;
                 s = (m < p.M ? p.scales[m] : 0.f) * p.w_scale;
             }
 #pragma unroll
-            for (int i = 0; i < FN; ++i)
+            for (int i = 0; i < FNB; ++i)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int chunk = wn * (WTN / 8) + 4 * i + q;
+                for (int v = 0; v < NV; ++v) {
+                    const int col = wn * WTN + MB * i + acc_col(lane, v);
+                    const int chunk = col >> 3;
                     u32x2 o;
-                    o.x = float2_to_half2_bits(acc[i][j][4 * q] * s, acc[i][j][4 * q + 1] * s);
-                    o.y = float2_to_half2_bits(acc[i][j][4 * q + 2] * s, acc[i][j][4 * q + 3] * s);
-                    *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * h) = o;
+                    o.x = float2_to_half2_bits(acc[i][j][4 * v] * s, acc[i][j][4 * v + 1] * s);
+                    o.y = float2_to_half2_bits(acc[i][j][4 * v + 2] * s, acc[i][j][4 * v + 3] * s);
+                    *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * ((col >> 2) & 1)) = o;
                 }
         }
-        store_tile_rows(p, m0, n0, lane, wave, lds);
-    }
-
-    // the FP16 tile in LDS goes out as whole rows, 16 bytes per lane
-    static __device__ __forceinline__ void store_tile_rows(const LargeParams &p, int m0, int n0, int lane, int wave,
-                                                           const uint8_t *lds) {
         __syncthreads();
         constexpr int RPI = 64 / OCH;                  // rows per store instruction
         constexpr int ROWS = TM / WAVES;               // rows per wave
@@ -600,106 +482,45 @@ struct LargeKernel {
         }
     }
 
-    // 16x16x32 accumulators: lane l holds token l % 16 and the four consecutive weight rows
-    // 4 * (l / 16) .. +3 of every 16x16 block
-    static __device__ __forceinline__ void epilogue_lds16(const LargeParams &p, floatx4 (&acc)[FN16][FM16], int m0, int n0,
-                                                          int wm, int wn, int lane, int wave, uint8_t *lds) {
-        const int r16 = lane & 15, q4 = lane >> 4;
-#pragma unroll
-        for (int j = 0; j < FM16; ++j) {
-            const int row = wm * WTM + 16 * j + r16;
-#pragma unroll
-            for (int i = 0; i < FN16; ++i) {
-                const int col = wn * WTN + 16 * i + 4 * q4;
-                const int chunk = col >> 3;
-                u32x2 o;
-                o.x = float2_to_half2_bits(acc[i][j][0], acc[i][j][1]);
-                o.y = float2_to_half2_bits(acc[i][j][2], acc[i][j][3]);
-                *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * (q4 & 1)) = o;
-            }
-        }
-        store_tile_rows(p, m0, n0, lane, wave, lds);
-    }
-
-    static __device__ __forceinline__ void epilogue16(const LargeParams &p, floatx4 (&acc)[FN16][FM16], int m0, int n0,
-                                                      int wm, int wn, int lane, int split) {
-        const int r16 = lane & 15, q4 = lane >> 4;
-#pragma unroll
-        for (int j = 0; j < FM16; ++j) {
-            const int m = m0 + wm * WTM + 16 * j + r16;
-            if (m >= p.M) continue;
-#pragma unroll
-            for (int i = 0; i < FN16; ++i) {
-                const int n = n0 + wn * WTN + 16 * i + 4 * q4;
-                if (n >= p.N) continue;
-                const floatx4 v = acc[i][j];
-                if (gridDim.y > 1) {
-                    float *dst = p.partials + ((int64_t)split * p.M + m) * p.N + n;
-                    if ((p.N & 3) == 0) {
-                        *reinterpret_cast<floatx4 *>(dst) = v;
-                    } else {
-                        for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
-                    }
-                } else {
-                    uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
-                    if (p.vec_store) {
-                        u32x2 o;
-                        o.x = float2_to_half2_bits(v[0], v[1]);
-                        o.y = float2_to_half2_bits(v[2], v[3]);
-                        *reinterpret_cast<u32x2 *>(dst) = o;
-                    } else {
-                        for (int e = 0; e < 4 && n + e < p.N; ++e) {
-                            union { _Float16 f; uint16_t u; } cv;
-                            cv.f = (_Float16)v[e];
-                            dst[e] = cv.u;
-                        }
-                    }
-                }
-            }
-        }
-    }
-
-    static __device__ __forceinline__ void epilogue(const LargeParams &p, floatx16 (&acc)[FN][FM], int m0, int n0,
+    static __device__ __forceinline__ void epilogue(const LargeParams &p, AccT (&acc)[FNB][FMB], int m0, int n0,
                                                     int wm, int wn, int lane, int split) {
-        const int r32 = lane & 31, h = lane >> 5;
+        const int r = lane % MB;
 #pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const int m = m0 + wm * WTM + 32 * j + r32;
+        for (int j = 0; j < FMB; ++j) {
+            const int m = m0 + wm * WTM + MB * j + r;
             if (m >= p.M) continue;
             float s = 1.0f;
             if (KIND == kE4M3 && gridDim.y == 1) s = p.scales[m] * p.w_scale;
 #pragma unroll
-            for (int i = 0; i < FN; ++i) {
+            for (int i = 0; i < FNB; ++i)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + wn * WTN + 32 * i + 8 * q + 4 * h;
+                for (int v = 0; v < NV; ++v) {
+                    const int n = n0 + wn * WTN + MB * i + acc_col(lane, v);
                     if (n >= p.N) continue;
-                    float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                                  acc[i][j][4 * q + 3]};
+                    const float x[4] = {acc[i][j][4 * v], acc[i][j][4 * v + 1], acc[i][j][4 * v + 2], acc[i][j][4 * v + 3]};
                     if (gridDim.y > 1) {
                         float *dst = p.partials + ((int64_t)split * p.M + m) * p.N + n;
                         if ((p.N & 3) == 0) {
-                            *reinterpret_cast<floatx4 *>(dst) = floatx4{v[0], v[1], v[2], v[3]};
+                            *reinterpret_cast<floatx4 *>(dst) = floatx4{x[0], x[1], x[2], x[3]};
                         } else {
-                            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e];
+                            for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = x[e];
                         }
                     } else {
                         uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
                         if (p.vec_store) {
                             u32x2 o;
-                            o.x = float2_to_half2_bits(v[0] * s, v[1] * s);
-                            o.y = float2_to_half2_bits(v[2] * s, v[3] * s);
+                            o.x = float2_to_half2_bits(x[0] * s, x[1] * s);
+                            o.y = float2_to_half2_bits(x[2] * s, x[3] * s);
                             *reinterpret_cast<u32x2 *>(dst) = o;
                         } else {
                             for (int e = 0; e < 4 && n + e < p.N; ++e) {
-                                union { _Float16 f; uint16_t u; } c;
-                                c.f = (_Float16)(v[e] * s);
-                                dst[e] = c.u;
+                                union { _Float16 f; uint16_t u; } cv;
+                                cv.f = (_Float16)(x[e] * s);
+                                dst[e] = cv.u;
                             }
                         }
                     }
                 }
-            }
         }
     }
 };
@@ -724,11 +545,11 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};    // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.321, 0.69}, {1.019, 0.0}, {1.096, 0.50}, {0.811, 0.0}},     // plain FP16
-    {{1.408, 0.95}, {1.080, 0.0}, {1.013, 1.74}, {0.866, 0.0}},     // NestedFP16
-    {{1.337, 7.28}, {1.085, 1.12}, {1.110, 2.62}, {0.864, 0.85}},   // E4M3
+    {{1.316, 0.58}, {1.018, 0.0}, {1.089, 0.78}, {0.809, 0.0}},     // plain FP16
+    {{1.396, 1.24}, {1.069, 0.21}, {1.014, 1.63}, {0.871, 0.0}},    // NestedFP16
+    {{1.319, 3.94}, {1.069, 1.44}, {1.090, 2.98}, {0.859, 0.95}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.46, 1.37, 1.41};
+static const double kPairSpeedup[3] = {1.45, 1.38, 1.41};
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -739,7 +560,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.47e6;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.46e6;
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
@@ -755,7 +576,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += 4.32 + 8.0 * (double)M * (double)N * slices / 4.32e6;
+            if (slices > 1) time += 4.28 + 8.0 * (double)M * (double)N * slices / 4.42e6;
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
