@@ -49,6 +49,16 @@ struct LargeParams {
 // global->LDS copy (8 lanes per row) are conflict-free under the same map.
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
+// FP16 tiles: which 16-byte chunk of a 128-byte global row the physical chunk slot p of an LDS row
+// holds (before the XOR swizzle).  The sum over k does not care about the order of k as long as
+// both operands agree.  The register-path NestedFP kernel gets its weights 16 consecutive columns
+// per lane (lane group g = l / 16 holds columns 16 g .. 16 g + 15 of a packed block), so substep
+// s of a K-tile multiplies halves 16 g + 8 s .. + 7, i.e. chunk 2 g + s of the row; all FP16 kernels
+// use that order, so that they add up alike and FP16 mode equals the plain FP16 GEMM bit for bit.
+// In LDS the four lane groups must read ADJACENT chunks (a stride of two chunks between the
+// groups halves the LDS read rate: bank conflicts), so chunk 2 g + s is stored in slot 4 s + g.
+__device__ __forceinline__ int fp16_chunk_of_slot(int p) { return ((p & 3) << 1) | (p >> 2); }
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint8_t *base, int64_t row0, int rows,
                                                             int64_t row_bytes, int k_bytes) {
     // raw buffer over the rows of one tile; anything past the last valid byte reads as zero
@@ -63,375 +73,17 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + (row0 >> 4) * tile_bytes), 0, bytes, 0x00020000);
 }
 
+// ---- writing a workgroup's result tile ------------------------------------------------------------
+// MB: rows of an MFMA block (16 or 32).  Accumulator layout: lane l holds token l % MB of a block
+// and, for v = 0 .. MB*MB/256 - 1, the four consecutive weight rows
+// (MB == 32 ? 8 v + 4 (l / 32) : 4 (l / 16)) .. +3.
 template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
-struct LargeKernel {
+struct TileStore {
     static constexpr int WAVES = WAVES_M * WAVES_N;
-    static_assert(WAVES == 8, "two waves per SIMD: one loading (older), one not");
-    static constexpr int THREADS = 64 * WAVES;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
-    static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
-    static constexpr int LDS_BYTES = 2 * STAGE;
-
-    // ---- MFMA tiling ------------------------------------------------------------------------
-    // FP16 kinds: v_mfma_f32_16x16x32_f16.  Under the chip's power limit (which, not the issue
-    // rate, bounds a full-chip FP16 GEMM on random operands) it sustains about 15 % more flops
-    // than 32x32x16: it moves half as many accumulator registers per flop.  E4M3:
-    // v_mfma_scale_f32_32x32x64_f8f6f4 (the 16x16x128 shape would need more fragment registers
-    // than a wave with a 128x64 tile has).  A wave's tile is FNB x FMB blocks of MB weight rows x
-    // MB tokens; a K-tile (128 bytes per row) is two substeps of 64 bytes per row; a fragment is
-    // NCH 16-byte chunks per lane: lane l supplies row l % MB and bytes 16 * NCH * (l / MB) .. of
-    // the substep's 64.
     static constexpr int MB = KIND == kE4M3 ? 32 : 16;
-    static constexpr int SUBS = 2;
-    static constexpr int NCH = KIND == kE4M3 ? 2 : 1;
     static constexpr int FMB = WTM / MB, FNB = WTN / MB;
-    static constexpr int MF = FMB * FNB;                             // MFMAs per substep
     typedef typename std::conditional<MB == 32, floatx16, floatx4>::type AccT;
-    // Slot plan of a substep.  The MFMAs run token block by token block (the FNB weight
-    // fragments stay, the token fragments stream).  The first NPRE fragments of a substep (all
-    // weight fragments, up to two token fragments) are fetched in the tail of the substep before
-    // it, the other token fragments early in the substep itself, about two token blocks ahead of
-    // their use.  The one barrier of a K-tile sits in its second substep behind the last read of
-    // the current stage (slot QB): from there on the stage is free for K-tile kt+2; the loads of
-    // kt+2 and the first reads of kt+1 follow it.
-    static constexpr int NB0 = FMB < 2 ? FMB : 2;
-    static constexpr int NPRE = FNB + NB0;
-    static constexpr int NREST = FMB - NB0;
-    static constexpr int RSTR = (3 * FNB) / 4 > 0 ? (3 * FNB) / 4 : 1;        // slots between the early token reads
-    static constexpr int QB = NREST > 0 ? (NREST - 1) * RSTR + (MB == 32 ? 2 : 3) : 0;   // slot that starts with the barrier
-    static constexpr int RPT = (NPRE + (MF - QB) - 1) / (MF - QB);            // look-ahead reads per tail slot
-    static constexpr int TSLOTS = (NPRE + RPT - 1) / RPT;                     // tail slots that read
-    static constexpr int TSTR = (MF - QB) / TSLOTS;                           // slots between them
-    static constexpr int TAIL0 = MF - TSLOTS * TSTR;
-    static_assert(QB < MF && TAIL0 >= QB && TSTR >= 1, "slot plan");
-
-    struct Frags { intx4 a[FNB][NCH]; intx4 b[FMB][NCH]; };
-
-    // LDS address of chunk q of a weight fragment: row, substep s, lane group g = l / MB.
-    // FP16 kinds: rows of 128 bytes, XOR-swizzled.  E4M3: the stage holds the packed 1 KB blocks
-    // as they are in memory, [row tile][2 blocks]; a substep is one block, and 16 lanes with
-    // consecutive rows read 256 consecutive bytes.
-    static __device__ __forceinline__ int w_addr(int row, int s, int g, int q) {
-        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (NCH * g + q)) << 4);
-        return swz(row, 4 * s + NCH * g + q);
-    }
-
-    // fragment R of substep s in the order of first use: weight blocks 0..FNB-1, token blocks 0..FMB-1
-    template <int R>
-    static __device__ __forceinline__ void read_frag(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        const int r = lane % MB, g = lane / MB;
-#pragma unroll
-        for (int q = 0; q < NCH; ++q) {
-            if constexpr (R < FNB)
-                f.a[R][q] = *reinterpret_cast<const intx4 *>(stage + w_addr(wn * WTN + MB * R + r, s, g, q));
-            else
-                f.b[R - FNB][q] = *reinterpret_cast<const intx4 *>(
-                    stage + TN * 128 + swz(wm * WTM + MB * (R - FNB) + r, 4 * s + NCH * g + q));
-        }
-    }
-
-    template <int R, int END>
-    static __device__ __forceinline__ void read_frags(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
-        if constexpr (R < END) {
-            read_frag<R>(f, stage, wm, wn, lane, s);
-            read_frags<R + 1, END>(f, stage, wm, wn, lane, s);
-        }
-    }
-
-    // weight rows are the "A" operand, tokens the "B" operand: a lane gets one token of the block
-    // and groups of four consecutive weight rows
-    template <int Q>
-    static __device__ __forceinline__ void mfma_one(const Frags &f, AccT (&acc)[FNB][FMB]) {
-        constexpr int j = Q / FNB, i = Q % FNB;
-        if constexpr (KIND == kE4M3) {
-            intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w, f.a[i][NCH - 1].x, f.a[i][NCH - 1].y, f.a[i][NCH - 1].z, f.a[i][NCH - 1].w};
-            intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w, f.b[j][NCH - 1].x, f.b[j][NCH - 1].y, f.b[j][NCH - 1].z, f.b[j][NCH - 1].w};
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
-        } else {
-            union { intx4 v; half8 h; } a, b;
-            a.v = f.a[i][0];
-            b.v = f.b[j][0];
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc[i][j], 0, 0, 0);
-        }
-    }
-
-    // ---- direct-to-LDS loads (buffer_load ... lds) -------------------------------------------
-    // One wave instruction fills 1 KB of LDS = 8 tile rows in lane order (lane l -> row l/8,
-    // physical chunk l%8), so the XOR swizzle is applied on the global side: lane l fetches
-    // the logical chunk (l%8) ^ ((row>>1)&7) of its row.  No VGPR staging, no ds_write.
-    // With two waves per SIMD the older one wins every arbitration and reaches the barrier long
-    // before the younger one.  The loads are therefore issued by the older four waves only:
-    // a load instruction blocks the issue of whatever is behind it while the address queue is
-    // full, and those waves have the time to spare.
-    static constexpr int DW = 4;                       // waves that issue direct-to-LDS loads
-    static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
-    static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
-    static constexpr int DMAS = XG + (KIND == kNestedF16 ? 0 : WG8);   // loads per loading wave per K-tile
-    static constexpr int DPS = (DMAS + (MF - QB) - 1) / (MF - QB);     // loads per slot behind the barrier
-
-    struct DmaOffsets {
-        uint32_t x[XG], w[WG8];
-        uint32_t kpos;                                 // this lane's K byte position in a K-tile
-        int wbit;                                      // E4M3: which of a K-tile's two block columns this wave loads
-    };
-
-    static __device__ __forceinline__ void make_dma_offsets(DmaOffsets &o, const LargeParams &p, int wave, int lane) {
-        const int pc = lane & 7;
-        const int c = pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);     // (row >> 1) & 7 for row = gid*8 + lane/8
-        o.kpos = 16u * c;
-#pragma unroll
-        for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
-#pragma unroll
-        for (int i = 0; i < WG8; ++i) {
-            if (KIND == kE4M3) {
-                // packed upper plane: load i of wave w is block b = i*DW + w of the stage, i.e. block
-                // column (2*kt + b%2) of row tile b/2; lane l fetches chunk l
-                const int b = i * DW + wave;
-                o.w[i] = (uint32_t)((b >> 1) * p.kblocks + (b & 1)) * 1024u + 16u * lane;
-            } else {
-                o.w[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
-            }
-        }
-        o.wbit = wave & 1;
-    }
-
-    typedef __attribute__((address_space(3))) uint8_t lds_byte;
-
-    // the i-th of a wave's XG + WG8 direct-to-LDS loads of one K-tile (token rows first);
-    // i is a constant at every call site
-    static __device__ __forceinline__ void dma_one(int i, const DmaOffsets &o, uint32_t x_lim, uint32_t w_lim,
-                                                   __amdgpu_buffer_rsrc_t rx, __amdgpu_buffer_rsrc_t rw,
-                                                   lds_byte *stage, int wave, int kt) {
-        const uint32_t kb = (uint32_t)kt * 128u;
-        if (i < XG) {
-            const uint32_t kill = (kb + o.kpos < x_lim) ? 0u : 0x80000000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(stage + TN * 128 + (i * DW + wave) * 1024),
-                                                     16, (o.x[i] + kb) | kill, 0, 0, 0);
-        } else {
-            const int j = i - XG;
-            if (KIND == kE4M3) {
-                // w_lim = block columns of the plane; past them the load is sent out of range
-                const uint32_t kill = ((uint32_t)(2 * kt + o.wbit) < w_lim) ? 0u : 0x80000000u;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
-                                                         16, (o.w[j] + (uint32_t)kt * 2048u) | kill, 0, 0, 0);
-            } else {
-                const uint32_t kill = (kb + o.kpos < w_lim) ? 0u : 0x80000000u;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
-                                                         16, (o.w[j] + kb) | kill, 0, 0, 0);
-            }
-        }
-    }
-
-    // ---- plane merge (NestedFP16) -------------------------------------------------------------
-    // The planes are loaded, merged and written to LDS one packed 1 KB block of each plane at a
-    // time (a "piece": 16 rows x 64 columns; lane l holds chunk l, i.e. row l % 16, columns
-    // 16 * (l / 16) .. +15).  16 consecutive lanes then write one chunk column of 16 consecutive
-    // rows, the bank pattern of the fragment reads.  The older wave of a SIMD has time to spare,
-    // so the loading waves take three of every four pieces (measured: 3:1 beats 2:2 and 4:0); a
-    // weight tile of 128 rows is merged by them alone.
-    static constexpr int NPO = TN == 256 ? 3 : 2;         // pieces of an older (loading) wave
-    static constexpr int NPY = TN / 64 - NPO;             // pieces of a younger wave
-    static constexpr int NPW = NPO > NPY ? NPO : NPY;
-    template <bool OLDER> static constexpr int pieces() { return OLDER ? NPO : NPY; }
-    struct PlaneRegs { u32x4 u[NPW], l[NPW]; };
-    struct PlaneOffsets { uint32_t lane_off; uint32_t lds_off; uint32_t lim; };
-
-    static __device__ __forceinline__ void make_plane_offsets(PlaneOffsets &o, const LargeParams &p, int wave, int lane) {
-        const int r = lane & 15, c4 = lane >> 4;
-        const int tile0 = wave < DW ? wave * NPO : DW * NPO + (wave - DW) * NPY;      // first row tile of the wave
-        o.lane_off = (uint32_t)(tile0 * p.kblocks) * 1024u + (uint32_t)lane * 16u;
-        // FP16 stage: row 16 * row tile + r, 16-byte chunks 2 * c4 and 2 * c4 + 1 (XOR-swizzled)
-        o.lds_off = (uint32_t)(tile0 * 16 + r) * 128u + (uint32_t)(((2 * c4) ^ ((r >> 1) & 7)) << 4);
-        o.lim = (uint32_t)p.kblocks;                    // block columns of the plane
-    }
-
-    template <int P>
-    static __device__ __forceinline__ void load_piece(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
-                                                      __amdgpu_buffer_rsrc_t rw1, int kblocks, int kt) {
-        const uint32_t kill = ((uint32_t)kt < o.lim) ? 0u : 0x80000000u;
-        const uint32_t soff = (uint32_t)(P * kblocks + kt) * 1024u;
-        pf.u[P] = __builtin_amdgcn_raw_buffer_load_b128(rw0, (o.lane_off + soff) | kill, 0, 0);
-        pf.l[P] = __builtin_amdgcn_raw_buffer_load_b128(rw1, (o.lane_off + soff) | kill, 0, 0);
-    }
-
-    // Sec. 4.2, Alg. 1 on the J-th four weights of piece P (8 VALU instructions); every second
-    // quarter completes a 16-byte chunk of the FP16 row, which goes into the tile of `stage`
-    template <int P, int J>
-    static __device__ __forceinline__ void merge_quarter(const PlaneRegs &pf, const PlaneOffsets &o, u32x4 &merged, uint8_t *stage) {
-        uint32_t w01, w23;
-        merge4(pf.u[P][J], pf.l[P][J], w01, w23);
-        merged[2 * (J & 1)] = w01;
-        merged[2 * (J & 1) + 1] = w23;
-        if constexpr ((J & 1) == 1)
-            *reinterpret_cast<u32x4 *>(stage + ((o.lds_off ^ (uint32_t)((J >> 1) << 4)) + P * 2048)) = merged;
-    }
-
-    // When the quarters of a wave's pieces run.  The registers of a piece hold K-tile kt+1 while
-    // K-tile kt is multiplied; it goes into the other stage (free since the barrier of kt-1) and
-    // the registers are reloaded with kt+2 right behind the piece's last quarter, most of a
-    // K-tile before they are needed again.  Older waves: pieces 0 and 1 in the first substep, 2
-    // in the head of the second (before the barrier), one quarter every few slots; younger
-    // waves: their piece spread over the first substep.
-    template <bool OLDER> static constexpr int piece_sub(int p) { return OLDER && p >= 2 ? 1 : 0; }
-    template <bool OLDER> static constexpr int piece_stride(int p) { return OLDER ? (MF >= 32 ? 4 : 1) : MF / 4; }
-    template <bool OLDER> static constexpr int piece_slot(int p) { return OLDER ? ((p & 1) ? MF / 2 : 0) : MF / 8; }
-    static_assert(NPO <= 3 && NPY <= 1 && NPY >= 0, "merge slots");
-    static_assert(KIND != kNestedF16 || NPO < 3 || 3 * piece_stride<true>(2) < QB, "merge slots");
-    // (piece * 4 + quarter) that runs at slot q of substep s, or -1
-    template <bool OLDER> static constexpr int quarter_at(int s, int q) {
-        for (int p = 0; p < pieces<OLDER>(); ++p)
-            if (piece_sub<OLDER>(p) == s && q >= piece_slot<OLDER>(p) && (q - piece_slot<OLDER>(p)) % piece_stride<OLDER>(p) == 0 &&
-                (q - piece_slot<OLDER>(p)) / piece_stride<OLDER>(p) < 4)
-                return 4 * p + (q - piece_slot<OLDER>(p)) / piece_stride<OLDER>(p);
-        return -1;
-    }
-
-    // stage 0 is merged here; stage 1 is written in the first K-tile of the loop, as in every later one
-    template <bool OLDER, int P>
-    static __device__ __forceinline__ void plane_prologue(PlaneRegs &pf, const PlaneOffsets &o, __amdgpu_buffer_rsrc_t rw0,
-                                                          __amdgpu_buffer_rsrc_t rw1, int kblocks, int kt_begin, uint8_t *lds) {
-        if constexpr (P < pieces<OLDER>()) {
-            u32x4 merged;
-            load_piece<P>(pf, o, rw0, rw1, kblocks, kt_begin);
-            merge_quarter<P, 0>(pf, o, merged, lds);  merge_quarter<P, 1>(pf, o, merged, lds);
-            merge_quarter<P, 2>(pf, o, merged, lds);  merge_quarter<P, 3>(pf, o, merged, lds);
-            load_piece<P>(pf, o, rw0, rw1, kblocks, kt_begin + 1);
-            plane_prologue<OLDER, P + 1>(pf, o, rw0, rw1, kblocks, kt_begin, lds);
-        }
-    }
-
-    // ---- the K loop as an explicit instruction schedule ---------------------------------------
-    // Every MFMA is followed by the few other instructions assigned to its slot and a scheduling
-    // fence, so the order below is the order in the binary.  OLDER: one of the DW waves that
-    // issue the direct-to-LDS loads; the loop exists once per role so that it has no branches
-    // inside.  PAR: which of the two fragment sets the substep multiplies.
-    struct Ctx {
-        AccT (&acc)[FNB][FMB];
-        Frags (&fr)[2];
-        PlaneRegs &pf;
-        u32x4 merged;                                   // FP16 chunk being assembled by the plane merge
-        const PlaneOffsets &off;
-        const DmaOffsets &dof;
-        __amdgpu_buffer_rsrc_t rx, rw0, rw1;
-        uint8_t *lds;
-        lds_byte *lds3;
-        uint32_t x_lim, w_lim;
-        int wave, lane, wm, wn;
-        int kblocks;
-        int kt, cur;
-    };
-
-    template <bool OLDER, int S, int PAR, int Q>
-    static __device__ __forceinline__ void slot(Ctx &c) {
-        constexpr bool last = (S == SUBS - 1);
-        if constexpr (last && Q == QB) {
-            // every read of the current stage has been issued; once all waves are here and their
-            // loads of the next K-tile have landed, the stage is free and the next one complete
-            // (the loading waves' plane loads of this K-tile are younger than those and may still fly)
-            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(KIND == kNestedF16 ? 2 * NPO : 0) : "memory");
-            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        mfma_one<Q>(c.fr[PAR], c.acc);
-        if constexpr (Q % RSTR == 0 && Q / RSTR < NREST)
-            read_frag<FNB + NB0 + Q / RSTR>(c.fr[PAR], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
-        if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < TSLOTS) {
-            constexpr int r0 = (Q - TAIL0) / TSTR * RPT;
-            read_frags<r0, (r0 + RPT < NPRE ? r0 + RPT : NPRE)>(c.fr[PAR ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn,
-                                                                c.lane, last ? 0 : S + 1);
-        }
-        if constexpr (last && OLDER && Q >= QB) {
-#pragma unroll
-            for (int d = (Q - QB) * DPS; d < (Q - QB + 1) * DPS && d < DMAS; ++d)
-                dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw0, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
-        }
-        if constexpr (KIND == kNestedF16 && quarter_at<OLDER>(S, Q) >= 0) {
-            constexpr int G = quarter_at<OLDER>(S, Q);
-            merge_quarter<G / 4, G % 4>(c.pf, c.off, c.merged, c.lds + (c.cur ^ 1) * STAGE);
-            if constexpr (G % 4 == 3) load_piece<G / 4>(c.pf, c.off, c.rw0, c.rw1, c.kblocks, c.kt + 2);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
-    }
-
-    template <bool OLDER>
-    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            c.kt = kt;
-            c.cur = (kt - kt_begin) & 1;
-            __builtin_amdgcn_sched_barrier(0);
-            slot<OLDER, 0, 0, 0>(c);
-            slot<OLDER, 1, 1, 0>(c);
-        }
-    }
-
-    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
-        const int lane = threadIdx.x & 63;
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-        const int tile = blockIdx.x;
-        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
-        const int m0 = tm * TM, n0 = tn * TN;
-        const int split = blockIdx.y;
-        const int kt_begin = split * p.ktiles_per_split;
-        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
-
-        const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
-        const __amdgpu_buffer_rsrc_t rw0 = KIND == kPlainF16
-            ? tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes)
-            : plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks);
-        const __amdgpu_buffer_rsrc_t rw1 = KIND == kNestedF16 ? plane_rsrc(p.W1, n0, min(TN, p.N - n0), p.kblocks) : rw0;
-        DmaOffsets dof;
-        make_dma_offsets(dof, p, wave, lane);
-        PlaneOffsets off;
-        if (KIND == kNestedF16) make_plane_offsets(off, p, wave, lane);
-        PlaneRegs pf;
-        const uint32_t x_lim = (uint32_t)p.k_bytes;
-        const uint32_t w_lim = KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
-
-        // Two LDS stages.  Tokens (and plain / E4M3 weights) go straight from global memory
-        // into LDS; the planes take the register path (they have to pass through the merge).
-        if (wave < DW) {
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-#pragma unroll
-                for (int i = 0; i < DMAS; ++i)
-                    dma_one(i, dof, x_lim, w_lim, rx, rw0, lds3 + st * STAGE, wave, kt_begin + st);
-        }
-        if (KIND == kNestedF16) {
-            if (wave < DW) plane_prologue<true, 0>(pf, off, rw0, rw1, p.kblocks, kt_begin, lds);
-            else plane_prologue<false, 0>(pf, off, rw0, rw1, p.kblocks, kt_begin, lds);
-            // everything but the plane loads issued last (the token loads came before them all)
-            if (wave < DW) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NPO) : "memory");
-            else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * NPY) : "memory");
-        } else {
-            // the loads of K-tile kt_begin (a wave that issued none passes straight through)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
-        }
-        __syncthreads();
-
-        AccT acc[FNB][FMB];
-#pragma unroll
-        for (int i = 0; i < FNB; ++i)
-#pragma unroll
-            for (int j = 0; j < FMB; ++j)
-#pragma unroll
-                for (int q = 0; q < (MB == 32 ? 16 : 4); ++q) acc[i][j][q] = 0.f;
-        Frags fr[2];
-        Ctx c{acc, fr, pf, u32x4{0, 0, 0, 0}, off, dof, rx, rw0, rw1, lds, lds3, x_lim, w_lim,
-              wave, lane, wm, wn, p.kblocks, kt_begin, 0};
-        read_frags<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
-        if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
-        else k_loop<false>(c, kt_begin, kt_end);
-        if (p.row_store && gridDim.y == 1) {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
-            __syncthreads();
-            epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
-        } else {
-            epilogue(p, acc, m0, n0, wm, wn, lane, split);
-        }
-    }
 
     // Result tile through LDS: the MFMA layout leaves a lane with 4 consecutive outputs of one
     // token, so direct stores are 8-byte pieces scattered over 16 or 32 rows per instruction.  Written
@@ -439,10 +91,7 @@ struct LargeKernel {
     // whole rows, 16 bytes per lane, every store instruction covering complete 128-byte lines.
     // The caller guarantees that no wave still reads the operand stages.
     static constexpr int OCH = TN * 2 / 16;            // 16-byte chunks per output row
-    static_assert(TM * TN * 2 <= LDS_BYTES, "output tile must fit into the operand stages");
-    // Accumulator layout: lane l holds token l % MB of a block and, for v = 0 .. MB*MB/256 - 1,
-    // the four consecutive weight rows (MB == 32 ? 8 v + 4 (l / 32) : 4 (l / 16)) .. +3.
-    static constexpr int NV = MB == 32 ? 4 : 1;
+        static constexpr int NV = MB == 32 ? 4 : 1;
     static __device__ __forceinline__ int acc_col(int lane, int v) { return MB == 32 ? 8 * v + 4 * (lane >> 5) : 4 * (lane >> 4); }
 
     static __device__ __forceinline__ void epilogue_lds(const LargeParams &p, AccT (&acc)[FNB][FMB], int m0, int n0,
@@ -526,10 +175,492 @@ struct LargeKernel {
 };
 
 template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+struct LargeKernel {
+    static_assert(KIND == kPlainF16 || KIND == kE4M3, "NestedFP16 has a kernel of its own");
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static_assert(WAVES == 8, "two waves per SIMD: one loading (older), one not");
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
+    static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
+    static constexpr int LDS_BYTES = 2 * STAGE;
+    typedef TileStore<KIND, TM, TN, WAVES_M, WAVES_N> Store;
+    static_assert(TM * TN * 2 <= LDS_BYTES, "output tile must fit into the operand stages");
+
+    // ---- MFMA tiling ------------------------------------------------------------------------
+    // FP16 kinds: v_mfma_f32_16x16x32_f16.  Under the chip's power limit (which, not the issue
+    // rate, bounds a full-chip FP16 GEMM on random operands) it sustains about 15 % more flops
+    // than 32x32x16: it moves half as many accumulator registers per flop.  E4M3:
+    // v_mfma_scale_f32_32x32x64_f8f6f4 (the 16x16x128 shape would need more fragment registers
+    // than a wave with a 128x64 tile has).  A wave's tile is FNB x FMB blocks of MB weight rows x
+    // MB tokens; a K-tile (128 bytes per row) is two substeps of 64 bytes per row; a fragment is
+    // NCH 16-byte chunks per lane: lane l supplies row l % MB and bytes 16 * NCH * (l / MB) .. of
+    // the substep's 64.
+    static constexpr int MB = KIND == kE4M3 ? 32 : 16;
+    static constexpr int SUBS = 2;
+    static constexpr int NCH = KIND == kE4M3 ? 2 : 1;
+    static constexpr int FMB = WTM / MB, FNB = WTN / MB;
+    static constexpr int MF = FMB * FNB;                             // MFMAs per substep
+    typedef typename std::conditional<MB == 32, floatx16, floatx4>::type AccT;
+    // Slot plan of a substep.  The MFMAs run token block by token block (the FNB weight
+    // fragments stay, the token fragments stream).  The first NPRE fragments of a substep (all
+    // weight fragments, up to two token fragments) are fetched in the tail of the substep before
+    // it, the other token fragments early in the substep itself, about two token blocks ahead of
+    // their use.  The one barrier of a K-tile sits in its second substep behind the last read of
+    // the current stage (slot QB): from there on the stage is free for K-tile kt+2; the loads of
+    // kt+2 and the first reads of kt+1 follow it.
+    static constexpr int NB0 = FMB < 2 ? FMB : 2;
+    static constexpr int NPRE = FNB + NB0;
+    static constexpr int NREST = FMB - NB0;
+    static constexpr int RSTR = (3 * FNB) / 4 > 0 ? (3 * FNB) / 4 : 1;        // slots between the early token reads
+    static constexpr int QB = NREST > 0 ? (NREST - 1) * RSTR + (MB == 32 ? 2 : 3) : 0;   // slot that starts with the barrier
+    static constexpr int RPT = (NPRE + (MF - QB) - 1) / (MF - QB);            // look-ahead reads per tail slot
+    static constexpr int TSLOTS = (NPRE + RPT - 1) / RPT;                     // tail slots that read
+    static constexpr int TSTR = (MF - QB) / TSLOTS;                           // slots between them
+    static constexpr int TAIL0 = MF - TSLOTS * TSTR;
+    static_assert(QB < MF && TAIL0 >= QB && TSTR >= 1, "slot plan");
+
+    struct Frags { intx4 a[FNB][NCH]; intx4 b[FMB][NCH]; };
+
+    // the chunk slot of an LDS row that lane group g reads in substep s (see fp16_chunk_of_slot)
+    static __device__ __forceinline__ int k_chunk(int s, int g, int q) { return 4 * s + NCH * g + q; }
+
+    // LDS address of chunk q of a weight fragment: row, substep s, lane group g = l / MB.
+    // FP16 kinds: rows of 128 bytes, XOR-swizzled.  E4M3: the stage holds the packed 1 KB blocks
+    // as they are in memory, [row tile][2 blocks]; a substep is one block, and 16 lanes with
+    // consecutive rows read 256 consecutive bytes.
+    static __device__ __forceinline__ int w_addr(int row, int s, int g, int q) {
+        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (NCH * g + q)) << 4);
+        return swz(row, k_chunk(s, g, q));
+    }
+
+    // fragment R of substep s in the order of first use: weight blocks 0..FNB-1, token blocks 0..FMB-1
+    template <int R>
+    static __device__ __forceinline__ void read_frag(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        const int r = lane % MB, g = lane / MB;
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            if constexpr (R < FNB)
+                f.a[R][q] = *reinterpret_cast<const intx4 *>(stage + w_addr(wn * WTN + MB * R + r, s, g, q));
+            else
+                f.b[R - FNB][q] = *reinterpret_cast<const intx4 *>(
+                    stage + TN * 128 + swz(wm * WTM + MB * (R - FNB) + r, k_chunk(s, g, q)));
+        }
+    }
+
+    template <int R, int END>
+    static __device__ __forceinline__ void read_frags(Frags &f, const uint8_t *stage, int wm, int wn, int lane, int s) {
+        if constexpr (R < END) {
+            read_frag<R>(f, stage, wm, wn, lane, s);
+            read_frags<R + 1, END>(f, stage, wm, wn, lane, s);
+        }
+    }
+
+    // weight rows are the "A" operand, tokens the "B" operand: a lane gets one token of the block
+    // and groups of four consecutive weight rows
+    template <int Q>
+    static __device__ __forceinline__ void mfma_one(const Frags &f, AccT (&acc)[FNB][FMB]) {
+        constexpr int j = Q / FNB, i = Q % FNB;
+        if constexpr (KIND == kE4M3) {
+            intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w, f.a[i][NCH - 1].x, f.a[i][NCH - 1].y, f.a[i][NCH - 1].z, f.a[i][NCH - 1].w};
+            intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w, f.b[j][NCH - 1].x, f.b[j][NCH - 1].y, f.b[j][NCH - 1].z, f.b[j][NCH - 1].w};
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
+        } else {
+            union { intx4 v; half8 h; } a, b;
+            a.v = f.a[i][0];
+            b.v = f.b[j][0];
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // ---- direct-to-LDS loads (buffer_load ... lds) -------------------------------------------
+    // One wave instruction fills 1 KB of LDS = 8 tile rows in lane order (lane l -> row l/8,
+    // physical chunk l%8), so the XOR swizzle is applied on the global side: lane l fetches
+    // the logical chunk (l%8) ^ ((row>>1)&7) of its row.  No VGPR staging, no ds_write.
+    // With two waves per SIMD the older one wins every arbitration and reaches the barrier long
+    // before the younger one.  The loads are therefore issued by the older four waves only:
+    // a load instruction blocks the issue of whatever is behind it while the address queue is
+    // full, and those waves have the time to spare.
+    static constexpr int DW = 4;                       // waves that issue direct-to-LDS loads
+    static constexpr int XG = TM / 8 / DW;             // 8-row groups per loading wave, token tile
+    static constexpr int WG8 = TN / 8 / DW;            // 8-row groups per loading wave, weight tile
+    static constexpr int DMAS = XG + WG8;              // loads per loading wave per K-tile
+    static constexpr int DPS = (DMAS + (MF - QB) - 1) / (MF - QB);     // loads per slot behind the barrier
+
+    struct DmaOffsets {
+        uint32_t x[XG], w[WG8];
+        uint32_t kpos;                                 // this lane's K byte position in a K-tile
+        int wbit;                                      // E4M3: which of a K-tile's two block columns this wave loads
+    };
+
+    static __device__ __forceinline__ void make_dma_offsets(DmaOffsets &o, const LargeParams &p, int wave, int lane) {
+        const int pc = lane & 7;
+        const int slot = pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);  // (row >> 1) & 7 for row = gid*8 + lane/8
+        const int c = KIND == kE4M3 ? slot : fp16_chunk_of_slot(slot);
+        o.kpos = 16u * c;
+#pragma unroll
+        for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
+#pragma unroll
+        for (int i = 0; i < WG8; ++i) {
+            if (KIND == kE4M3) {
+                // packed upper plane: load i of wave w is block b = i*DW + w of the stage, i.e. block
+                // column (2*kt + b%2) of row tile b/2; lane l fetches chunk l
+                const int b = i * DW + wave;
+                o.w[i] = (uint32_t)((b >> 1) * p.kblocks + (b & 1)) * 1024u + 16u * lane;
+            } else {
+                o.w[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.w_row_bytes + 16u * c;
+            }
+        }
+        o.wbit = wave & 1;
+    }
+
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    // the i-th of a wave's XG + WG8 direct-to-LDS loads of one K-tile (token rows first);
+    // i is a constant at every call site
+    static __device__ __forceinline__ void dma_one(int i, const DmaOffsets &o, uint32_t x_lim, uint32_t w_lim,
+                                                   __amdgpu_buffer_rsrc_t rx, __amdgpu_buffer_rsrc_t rw,
+                                                   lds_byte *stage, int wave, int kt) {
+        const uint32_t kb = (uint32_t)kt * 128u;
+        if (i < XG) {
+            const uint32_t kill = (kb + o.kpos < x_lim) ? 0u : 0x80000000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(stage + TN * 128 + (i * DW + wave) * 1024),
+                                                     16, (o.x[i] + kb) | kill, 0, 0, 0);
+        } else {
+            const int j = i - XG;
+            if (KIND == kE4M3) {
+                // w_lim = block columns of the plane; past them the load is sent out of range
+                const uint32_t kill = ((uint32_t)(2 * kt + o.wbit) < w_lim) ? 0u : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
+                                                         16, (o.w[j] + (uint32_t)kt * 2048u) | kill, 0, 0, 0);
+            } else {
+                const uint32_t kill = (kb + o.kpos < w_lim) ? 0u : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
+                                                         16, (o.w[j] + kb) | kill, 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- the K loop as an explicit instruction schedule ---------------------------------------
+    // Every MFMA is followed by the few other instructions assigned to its slot and a scheduling
+    // fence, so the order below is the order in the binary.  OLDER: one of the DW waves that
+    // issue the direct-to-LDS loads; the loop exists once per role so that it has no branches
+    // inside.  PAR: which of the two fragment sets the substep multiplies.
+    struct Ctx {
+        AccT (&acc)[FNB][FMB];
+        Frags (&fr)[2];
+        const DmaOffsets &dof;
+        __amdgpu_buffer_rsrc_t rx, rw;
+        uint8_t *lds;
+        lds_byte *lds3;
+        uint32_t x_lim, w_lim;
+        int wave, lane, wm, wn;
+        int kt, cur;
+    };
+
+    template <bool OLDER, int S, int PAR, int Q>
+    static __device__ __forceinline__ void slot(Ctx &c) {
+        constexpr bool last = (S == SUBS - 1);
+        if constexpr (last && Q == QB) {
+            // every read of the current stage has been issued; once all waves are here and their
+            // loads of the next K-tile have landed, the stage is free and the next one complete
+            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma_one<Q>(c.fr[PAR], c.acc);
+        if constexpr (Q % RSTR == 0 && Q / RSTR < NREST)
+            read_frag<FNB + NB0 + Q / RSTR>(c.fr[PAR], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
+        if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < TSLOTS) {
+            constexpr int r0 = (Q - TAIL0) / TSTR * RPT;
+            read_frags<r0, (r0 + RPT < NPRE ? r0 + RPT : NPRE)>(c.fr[PAR ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn,
+                                                                c.lane, last ? 0 : S + 1);
+        }
+        if constexpr (last && OLDER && Q >= QB) {
+#pragma unroll
+            for (int d = (Q - QB) * DPS; d < (Q - QB + 1) * DPS && d < DMAS; ++d)
+                dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            c.kt = kt;
+            c.cur = (kt - kt_begin) & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            slot<OLDER, 0, 0, 0>(c);
+            slot<OLDER, 1, 1, 0>(c);
+        }
+    }
+
+    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+        const int tile = blockIdx.x;
+        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        const int m0 = tm * TM, n0 = tn * TN;
+        const int split = blockIdx.y;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
+
+        const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
+        const __amdgpu_buffer_rsrc_t rw = KIND == kPlainF16
+            ? tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes)
+            : plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks);
+        DmaOffsets dof;
+        make_dma_offsets(dof, p, wave, lane);
+        const uint32_t x_lim = (uint32_t)p.k_bytes;
+        const uint32_t w_lim = KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
+
+        // Two LDS stages; tokens and weights go straight from global memory into LDS.
+        if (wave < DW) {
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int i = 0; i < DMAS; ++i)
+                    dma_one(i, dof, x_lim, w_lim, rx, rw, lds3 + st * STAGE, wave, kt_begin + st);
+        }
+        // the loads of K-tile kt_begin (a wave that issued none passes straight through)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
+        __syncthreads();
+
+        AccT acc[FNB][FMB];
+#pragma unroll
+        for (int i = 0; i < FNB; ++i)
+#pragma unroll
+            for (int j = 0; j < FMB; ++j)
+#pragma unroll
+                for (int q = 0; q < (MB == 32 ? 16 : 4); ++q) acc[i][j][q] = 0.f;
+        Frags fr[2];
+        Ctx c{acc, fr, dof, rx, rw, lds, lds3, x_lim, w_lim, wave, lane, wm, wn, kt_begin, 0};
+        read_frags<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
+        if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
+        else k_loop<false>(c, kt_begin, kt_end);
+        if (p.row_store && gridDim.y == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+            __syncthreads();
+            Store::epilogue_lds(p, acc, m0, n0, wm, wn, lane, wave, lds);
+        } else {
+            Store::epilogue(p, acc, m0, n0, wm, wn, lane, split);
+        }
+    }
+
+};
+
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 large_gemm_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     typedef LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N> Kern;
+    Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
+}
+
+// ---- NestedFP16 with the weights kept out of LDS ------------------------------------------------
+// Eight waves side by side along the weight rows: a wave owns TN/8 weight rows and all TM tokens
+// of the tile, so every weight is needed by exactly one wave.  The wave loads its packed plane
+// blocks straight into registers (lane l = chunk l: row l % 16, columns 16 * (l / 16) .. +15),
+// merges them there (Sec. 4.2, Alg. 1) and feeds the result to the MFMA as it is: the sum over k
+// does not care about the order of k, so substep s of a K-tile takes columns 16 g + 8 s .. + 7
+// from lane group g, and the token fragments are read from LDS in the same order (chunk
+// 2 g + s of the 128-byte row, see fp16_chunk_of_slot).  No ds_write, no weight tile in LDS; LDS holds four stages of
+// the token tile only (loads run three K-tiles ahead), and the one barrier per K-tile sits
+// at its end and waits for no LDS read.
+template <int TM, int TN>
+struct BypassKernel {
+    typedef TileStore<kNestedF16, TM, TN, 1, 8> Store;
+    static constexpr int DW = 4;                               // waves that issue the token loads
+    static constexpr int WTN = TN / 8;
+    static constexpr int FMB = TM / 16, FNB = WTN / 16;
+    static constexpr int MF = FMB * FNB;                       // MFMAs per substep
+    static constexpr int NST = 4;
+    static constexpr int STAGE = TM * 128;
+    static constexpr int LDS_BYTES = NST * STAGE > TM * TN * 2 ? NST * STAGE : TM * TN * 2;
+    static constexpr int XG = TM / 8 / DW;                     // loads per loading wave per K-tile
+    static constexpr int LEAD = 2;                             // token fragments are read this many blocks ahead
+    static constexpr int NMQ = 2 * FNB;                        // merges of four weights per substep
+    static constexpr int MQS = MF / NMQ;                       // slots between them
+    static constexpr int DQS = MF / XG;                        // slots between token loads
+    static_assert(FNB <= 2 && FMB > LEAD && MF % NMQ == 0 && MF % XG == 0 && MQS >= 2, "slot plan");
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    struct Raw { u32x4 u[FNB], l[FNB]; };                      // one K-tile of the wave's plane blocks
+
+    struct Ctx {
+        floatx4 (&acc)[FNB][FMB];
+        intx4 (&a)[2][FNB];                                    // merged weight fragments of substeps 0 / 1
+        intx4 (&b)[2][FMB];                                    // token fragments (a few are live at a time)
+        Raw (&raw)[2];
+        __amdgpu_buffer_rsrc_t rx, rw0, rw1;
+        uint32_t x_off, x_step, x_kpos, x_lim;               // offset of the wave's first load, step between its loads
+        uint32_t w_off, w_lim;
+        const uint8_t *lds;
+        lds_byte *lds3;
+        int wave, lane, kblocks;
+        int kt, st;                                            // K-tile, its LDS stage
+    };
+
+    template <int J>
+    static __device__ __forceinline__ void read_b(intx4 &dst, const uint8_t *stage, int lane, int s) {
+        dst = *reinterpret_cast<const intx4 *>(stage + swz(16 * J + (lane & 15), 4 * s + (lane >> 4)));
+    }
+
+    static __device__ __forceinline__ void load_raw(Raw &r, const Ctx &c, int kt) {
+        const uint32_t kill = ((uint32_t)kt < c.w_lim) ? 0u : 0x80000000u;
+#pragma unroll
+        for (int i = 0; i < FNB; ++i) {
+            const uint32_t off = (c.w_off + (uint32_t)(i * c.kblocks + kt) * 1024u) | kill;
+            r.u[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off, 0, 0);
+            r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, off, 0, 0);
+        }
+    }
+
+    // four weights of row tile I: dwords H (substep 0) or 2 + H (substep 1) of the lane's chunk
+    template <int S, int I, int H>
+    static __device__ __forceinline__ void merge_part(intx4 &dst, const Raw &r) {
+        uint32_t w01, w23;
+        merge4(r.u[I][2 * S + H], r.l[I][2 * S + H], w01, w23);
+        dst[2 * H] = (int)w01;
+        dst[2 * H + 1] = (int)w23;
+    }
+
+    static __device__ __forceinline__ void dma_x(const Ctx &c, int i, int kt) {
+        const uint32_t kb = (uint32_t)kt * 128u;
+        const uint32_t kill = (kb + c.x_kpos < c.x_lim) ? 0u : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rx, (__attribute__((address_space(3))) void *)(c.lds3 + (kt & (NST - 1)) * STAGE + (i * DW + c.wave) * 1024),
+                                                 16, (c.x_off + (uint32_t)i * c.x_step + kb) | kill, 0, 0, 0);
+    }
+
+    // PAR: which register set holds the plane blocks of this K-tile (the other one holds the next)
+    template <bool OLDER, int S, int PAR, int Q>
+    static __device__ __forceinline__ void slot(Ctx &c) {
+        constexpr int j = Q / FNB, i = Q % FNB;
+        {
+            union { intx4 v; half8 h; } a, b;
+            a.v = c.a[S][i];
+            b.v = c.b[S][j];
+            c.acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, c.acc[i][j], 0, 0, 0);
+        }
+        if constexpr (i == 0) {
+            // token fragment LEAD blocks ahead: this substep, the next one, or the next K-tile
+            if constexpr (j + LEAD < FMB) read_b<j + LEAD>(c.b[S][j + LEAD], c.lds + c.st * STAGE, c.lane, S);
+            else if constexpr (S == 0) read_b<j + LEAD - FMB>(c.b[1][j + LEAD - FMB], c.lds + c.st * STAGE, c.lane, 1);
+            else read_b<j + LEAD - FMB>(c.b[0][j + LEAD - FMB], c.lds + ((c.st + 1) & (NST - 1)) * STAGE, c.lane, 0);
+        }
+        if constexpr (Q % MQS == MQS - 1) {
+            // substep 0 merges this K-tile's second half, substep 1 the next K-tile's first half
+            constexpr int m = Q / MQS;
+            if constexpr (S == 0) merge_part<1, m / 2, m % 2>(c.a[1][m / 2], c.raw[PAR]);
+            else merge_part<0, m / 2, m % 2>(c.a[0][m / 2], c.raw[PAR ^ 1]);
+        }
+        if constexpr (OLDER && S == 0 && Q % DQS == 0) dma_x(c, Q / DQS, c.kt + 3);
+        if constexpr (S == 1 && Q == 0) load_raw(c.raw[PAR], c, c.kt + 2);     // its blocks are merged; two K-tiles ahead
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
+    }
+
+    template <bool OLDER, int PAR>
+    static __device__ __forceinline__ void k_tile(Ctx &c) {
+        __builtin_amdgcn_sched_barrier(0);
+        slot<OLDER, 0, PAR, 0>(c);
+        slot<OLDER, 1, PAR, 0>(c);
+        // The token loads of K-tile kt+2 (issued during kt-1) must have landed before anybody
+        // reads them (from the tail of kt+1 on).  Younger than them in this wave: the loads of
+        // this K-tile (XG token loads, 2 FNB plane loads).
+        if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(XG + 2 * FNB) : "memory");
+        __syncthreads();
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
+        for (int kt = kt_begin; kt < kt_end; kt += 2) {
+            c.kt = kt;
+            c.st = kt & (NST - 1);
+            k_tile<OLDER, 0>(c);
+            if (kt + 1 < kt_end) {
+                c.kt = kt + 1;
+                c.st = (kt + 1) & (NST - 1);
+                k_tile<OLDER, 1>(c);
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int tile = blockIdx.x;
+        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        const int m0 = tm * TM, n0 = tn * TN;
+        const int split = blockIdx.y;
+        // the LDS stage of a K-tile is kt % 4: start the slice on a multiple of 4 as far as the ring goes
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
+
+        floatx4 acc[FNB][FMB];
+#pragma unroll
+        for (int i = 0; i < FNB; ++i)
+#pragma unroll
+            for (int j = 0; j < FMB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        intx4 a[2][FNB], b[2][FMB];
+        Raw raw[2];
+        Ctx c{acc, a, b, raw,
+              tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes),
+              plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks), plane_rsrc(p.W1, n0, min(TN, p.N - n0), p.kblocks),
+              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, (uint32_t)p.kblocks, lds, lds3, wave, lane,
+              p.kblocks, kt_begin, 0};
+        {
+            const int pc = lane & 7;
+            const int ch = fp16_chunk_of_slot(pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7));   // (row >> 1) & 7 for row = gid*8 + lane/8
+            c.x_kpos = 16u * ch;
+            c.x_off = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * ch;
+            c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+        }
+        // token tiles of the first three K-tiles, plane blocks of the first two
+        if (wave < DW) {
+#pragma unroll
+            for (int d = 0; d < 3; ++d)
+#pragma unroll
+                for (int i = 0; i < XG; ++i) dma_x(c, i, kt_begin + d);
+        }
+        load_raw(raw[0], c, kt_begin);
+        load_raw(raw[1], c, kt_begin + 1);
+        // (in order: once the first plane blocks are here, the token loads issued before them are too)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * FNB) : "memory");
+        merge_part<0, 0, 0>(a[0][0], raw[0]);
+        merge_part<0, 0, 1>(a[0][0], raw[0]);
+        if constexpr (FNB > 1) {
+            merge_part<0, FNB - 1, 0>(a[0][FNB - 1], raw[0]);
+            merge_part<0, FNB - 1, 1>(a[0][FNB - 1], raw[0]);
+        }
+        __syncthreads();
+        c.st = kt_begin & (NST - 1);
+        {
+            const uint8_t *st0 = lds + c.st * STAGE;
+            read_b<0>(b[0][0], st0, lane, 0);
+            if (LEAD > 1) read_b<1>(b[0][1], st0, lane, 0);
+            if (LEAD > 2) read_b<2>(b[0][2], st0, lane, 0);
+            if (LEAD > 3) read_b<3>(b[0][3], st0, lane, 0);
+        }
+        if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
+        else k_loop<false>(c, kt_begin, kt_end);
+        if (p.row_store && gridDim.y == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+            __syncthreads();
+            Store::epilogue_lds(p, acc, m0, n0, 0, wave, lane, wave, lds);
+        } else {
+            Store::epilogue(p, acc, m0, n0, 0, wave, lane, split);
+        }
+    }
+};
+
+template <int TM, int TN>
+__global__ void __launch_bounds__(512)
+nested_bypass_kernel(LargeParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    typedef BypassKernel<TM, TN> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -545,11 +676,11 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};    // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.316, 0.58}, {1.018, 0.0}, {1.089, 0.78}, {0.809, 0.0}},     // plain FP16
-    {{1.396, 1.24}, {1.069, 0.21}, {1.014, 1.63}, {0.871, 0.0}},    // NestedFP16
-    {{1.319, 3.94}, {1.069, 1.44}, {1.090, 2.98}, {0.859, 0.95}},   // E4M3
+    {{1.320, 0.0}, {1.014, 0.0}, {1.094, 0.40}, {0.812, 0.0}},      // plain FP16
+    {{1.296, 1.01}, {0.942, 0.03}, {0.926, 1.56}, {0.673, 0.0}},    // NestedFP16
+    {{1.335, 3.30}, {1.085, 1.08}, {1.103, 2.54}, {0.875, 0.63}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.45, 1.38, 1.41};
+static const double kPairSpeedup[3] = {1.47, 1.18, 1.41};
 
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
@@ -560,7 +691,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.46e6;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.75e6;
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
@@ -576,7 +707,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += 4.28 + 8.0 * (double)M * (double)N * slices / 4.42e6;
+            if (slices > 1) time += 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
@@ -602,12 +733,31 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
     kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
 
+template <int TM, int TN>
+static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
+    auto kern = nested_bypass_kernel<TM, TN>;
+    constexpr int lds = BypassKernel<TM, TN>::LDS_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    kern<<<grid, 512, lds, stream>>>(p);
+}
+
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
     if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
     else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
     else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
     else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
+}
+
+static void launch_nested(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
+    if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256>(p, grid, stream);
+    else if (c.tm == 256) launch_bypass<256, 128>(p, grid, stream);
+    else if (c.tn == 256) launch_bypass<128, 256>(p, grid, stream);
+    else launch_bypass<128, 128>(p, grid, stream);
 }
 
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
@@ -639,7 +789,7 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)c.split);
     switch (kind) {
         case kPlainF16: launch_large_k<kPlainF16>(p, c, grid, stream); break;
-        case kNestedF16: launch_large_k<kNestedF16>(p, c, grid, stream); break;
+        case kNestedF16: launch_nested(p, c, grid, stream); break;
         default: launch_large_k<kE4M3>(p, c, grid, stream); break;
     }
     if (hipGetLastError() != hipSuccess) return kErrHip;

@@ -30,8 +30,18 @@ def run_both_modes(nfp, X, W, what, check_plain=True):
     ref16 = oracle.gemm_fp16(X, W)
     assert_gemm_close(y16.cpu().numpy(), ref16, what + " FP16 mode")
     if check_plain:
-        yp = nfp.plain_gemm_fp16(Xd, Wd)
-        assert np.array_equal(bits(yp), bits(y16)), what + ": FP16 mode differs from the plain fp16 GEMM"
+        # same tile shape and K split for both kernels: then the sums run in the same order
+        pins = {"large_bm": 128, "large_bn": 256, "large_split": 2}
+        for k, v in pins.items():
+            nfp.tune(k, v)
+        try:
+            yp = nfp.plain_gemm_fp16(Xd, Wd)
+            yn = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+        finally:
+            for k in pins:
+                nfp.tune(k, -1)
+        assert np.array_equal(bits(yp), bits(yn)), what + ": FP16 mode differs from the plain fp16 GEMM"
+        assert_gemm_close(yn.cpu().numpy(), ref16, what + " FP16 mode, pinned launch shape")
     # FP8 mode: lower plane is not passed at all
     y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
     Xq, s = oracle.quantize_act(X)
@@ -248,8 +258,15 @@ def test_llama8b_prefill_shapes_sampled(nfp, name, M):
     Xd = workloads.act_device(M, K, seed=12)
     up, lo = nfp.decompose(Wd)
     y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
-    yp = nfp.plain_gemm_fp16(Xd, Wd)
-    assert torch.equal(y16, yp)
+    # with the same tile shape and K split FP16 mode and the plain FP16 GEMM agree bit for bit
+    pins = {"large_bm": 256, "large_bn": 256, "large_split": 2 if name == "down" else 1}
+    for k, v in pins.items():
+        nfp.tune(k, v)
+    try:
+        assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd))
+    finally:
+        for k in pins:
+            nfp.tune(k, -1)
     y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
     rows, cols = workloads.sample_indices(M, N, 24, 96, seed=M)
     Xs = Xd[torch.from_numpy(rows).cuda()].cpu().numpy()
