@@ -31,7 +31,11 @@ struct Workspace {
 };
 
 static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
-    return use_small_gemm(M) && small_gemm_supports(kind, M, N, K, ldw);
+    if (!use_small_gemm(M) || !small_gemm_supports(kind, M, N, K, ldw)) return false;
+    // measured: with three or four token tiles per wave the streaming kernel falls behind the
+    // tiled NestedFP kernel (whose weights bypass LDS) on the widest layers (gate/up projections)
+    if (kind == kNestedF16 && M > 32 && N >= 16384 && tuning().small_max_m < 0) return false;
+    return true;
 }
 
 static size_t partial_bytes_for(int kind, int64_t M, int64_t N, int64_t K) {

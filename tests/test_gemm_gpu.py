@@ -289,7 +289,16 @@ def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
     Xd = workloads.act_device(M, K, seed=seed + 1)
     up, lo = nfp.decompose(Wd)
     y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
-    assert torch.equal(y16, nfp.plain_gemm_fp16(Xd, Wd)), tag + ": FP16 mode differs from plain fp16"
+    # same kernel family and launch shape for both: then FP16 mode and the plain FP16 GEMM agree bit for bit
+    pins = {"small_max_m": 64} if M <= 64 else {"large_bm": 256, "large_bn": 256, "large_split": 1}
+    for k, v in pins.items():
+        nfp.tune(k, v)
+    try:
+        assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd)), \
+            tag + ": FP16 mode differs from plain fp16"
+    finally:
+        for k in pins:
+            nfp.tune(k, -1)
     y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
     rows, cols = workloads.sample_indices(M, N, 16, 64, seed=seed)
     ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
