@@ -20,8 +20,6 @@
 
 namespace nfp {
 
-constexpr int kLargeThreads = 512;
-
 struct LargeParams {
     const uint8_t *X;       // fp16 X (bytes) or E4M3 Xq
     int64_t x_row_bytes;    // < 2^24 (checked on the host): tile-local offsets fit in 31 bits
