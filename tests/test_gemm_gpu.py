@@ -135,6 +135,31 @@ def test_prefill_launch_shapes(nfp, knobs):
             nfp.tune(k, -1)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes_and_launch_shapes(nfp, seed):
+    # seeded random problem sizes (ragged in every dimension) under random tile shapes and K
+    # splits, both modes against the oracle
+    rng = np.random.default_rng(seed)
+    for case in range(12):
+        M = int(rng.choice([rng.integers(1, 65), rng.integers(65, 300), rng.integers(300, 700)]))
+        N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 600), rng.integers(600, 1100)]))
+        K = 16 * int(rng.choice([rng.integers(1, 9), rng.integers(9, 70), rng.integers(70, 120)]))
+        knobs = {}
+        if rng.random() < 0.75:
+            knobs = {"large_bm": int(rng.choice([128, 256])), "large_bn": int(rng.choice([128, 256])),
+                     "large_split": int(rng.choice([1, 1, 2, 3, 5]))}
+        W = workloads.weight_host(N, K, seed=100 * seed + case)
+        X = workloads.act_host(M, K, seed=100 * seed + case + 50)
+        for k, v in knobs.items():
+            nfp.tune(k, v)
+        try:
+            run_both_modes(nfp, X, W, "seed %d case %d M=%d N=%d K=%d %s" % (seed, case, M, N, K, knobs),
+                           check_plain=False)
+        finally:
+            for k in knobs:
+                nfp.tune(k, -1)
+
+
 def test_one_hot_tokens_return_weights_exactly(nfp):
     # FP16 mode with one-hot rows returns the reconstructed weights themselves: checks the
     # operand layout, the transposition and Alg. 1 bit-exactly inside the GEMM kernels
