@@ -30,8 +30,9 @@ def run_both_modes(nfp, X, W, what, check_plain=True):
     ref16 = oracle.gemm_fp16(X, W)
     assert_gemm_close(y16.cpu().numpy(), ref16, what + " FP16 mode")
     if check_plain:
-        # same tile shape and K split for both kernels: then the sums run in the same order
-        pins = {"large_bm": 128, "large_bn": 256, "large_split": 2}
+        # same launch shape for both kernels (tile shape and K split of the tiled ones, K-steps per
+        # wave of the streaming ones): then the sums run in the same order
+        pins = {"large_bm": 128, "large_bn": 256, "large_split": 2, "small_spw": 4}
         for k, v in pins.items():
             nfp.tune(k, v)
         try:
@@ -315,7 +316,7 @@ def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
     up, lo = nfp.decompose(Wd)
     y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
     # same kernel family and launch shape for both: then FP16 mode and the plain FP16 GEMM agree bit for bit
-    pins = {"small_max_m": 64} if M <= 64 else {"large_bm": 256, "large_bn": 256, "large_split": 1}
+    pins = {"small_max_m": 64, "small_spw": 4} if M <= 64 else {"large_bm": 256, "large_bn": 256, "large_split": 1}
     for k, v in pins.items():
         nfp.tune(k, v)
     try:
