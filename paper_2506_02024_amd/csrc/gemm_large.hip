@@ -672,7 +672,7 @@ struct LargeConfig { int tm, tn, split; };
 // are a least-squares fit (microseconds) to sweeps of every shape and split over M = 128 ...
 // 4096 on the four Llama-3-8B layer shapes and a square 8192 layer.
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
-static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};    // tokens x weight rows
+static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};   // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
     {{1.320, 0.0}, {1.014, 0.0}, {1.094, 0.40}, {0.812, 0.0}},      // plain FP16
     {{1.296, 1.01}, {0.942, 0.03}, {0.926, 1.56}, {0.673, 0.0}},    // NestedFP16
@@ -680,10 +680,42 @@ static const TileCost kTileCost[3][4] = {
 };
 static const double kPairSpeedup[3] = {1.47, 1.18, 1.41};
 
+// split-K cost: the reduction kernel's launch plus its traffic
+static double split_cost(int64_t M, int64_t N, int slices) {
+    return 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
+}
+
+// NestedFP16 with at most 64 tokens: one 64 x 128 tile shape, two workgroups per CU, and only the split to
+// choose. Such a launch is bound by the weight stream, whose rate depends on how many workgroups pull on it.
+static LargeConfig choose_tile64(int64_t M, int64_t N, int kt) {
+    const Tuning &t = tuning();
+    LargeConfig c;
+    c.tm = 64;  c.tn = 128;  c.split = 1;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
+    double best = 1e30;
+    for (int split = 1; split <= 8; split *= 2) {
+        if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
+        else if (split > 1 && split > kt / 4) break;
+        const int per = (kt + split - 1) / split;
+        const int slices = (kt + per - 1) / per;
+        const int64_t wgs = tiles * slices;
+        double time = (double)((wgs + 511) / 512) * (0.4 + per * 0.5);
+        double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? 5.0e6 : 5.5e6);
+        if (wgs < 256) floor_t *= std::sqrt(256.0 / (double)wgs);
+        if (time < floor_t) time = floor_t;
+        if (slices > 1) time += split_cost(M, N, slices);
+        if (time < best) { best = time;  c.split = split; }
+        if (t.large_split > 0) break;
+    }
+    return c;
+}
+
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
     const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
+    if (kind == kNestedF16 && (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0)))
+        return choose_tile64(M, N, kt);
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
@@ -705,7 +737,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
+            if (slices > 1) time += split_cost(M, N, slices);
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
@@ -752,7 +784,8 @@ static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid
 }
 
 static void launch_nested(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256>(p, grid, stream);
+    if (c.tm == 64) launch_bypass<64, 128>(p, grid, stream);
+    else if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256>(p, grid, stream);
     else if (c.tm == 256) launch_bypass<256, 128>(p, grid, stream);
     else if (c.tn == 256) launch_bypass<128, 256>(p, grid, stream);
     else launch_bypass<128, 128>(p, grid, stream);

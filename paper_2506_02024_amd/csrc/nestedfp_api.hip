@@ -35,6 +35,8 @@ static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) 
     // measured: with three or four token tiles per wave the streaming kernel falls behind the
     // tiled NestedFP kernel (whose weights bypass LDS) on the widest layers (gate/up projections)
     if (kind == kNestedF16 && M > 32 && N >= 16384 && tuning().small_max_m < 0) return false;
+    // and from 49 tokens on everywhere but on the smallest layers (64-token tiles, split along K)
+    if (kind == kNestedF16 && M > 48 && (N > 4096 || K > 4096) && tuning().small_max_m < 0) return false;
     return true;
 }
 

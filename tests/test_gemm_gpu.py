@@ -121,6 +121,8 @@ def test_prefill_sized_batches(nfp, M, N, K):
     {"large_bm": 128, "large_bn": 256, "large_split": 1},
     {"large_bm": 256, "large_bn": 128, "large_split": 2},
     {"large_bm": 128, "large_bn": 256, "large_split": 3},
+    {"large_bm": 64, "large_split": 1},       # 64 x 128 tiles: NestedFP16 only, the other kinds ignore it
+    {"large_bm": 64, "large_split": 4},
     {"small_max_m": 0},                       # route a decode-sized batch through the tiled kernel
 ])
 def test_prefill_launch_shapes(nfp, knobs):
@@ -147,7 +149,7 @@ def test_random_shapes_and_launch_shapes(nfp, seed):
         K = 16 * int(rng.choice([rng.integers(1, 9), rng.integers(9, 70), rng.integers(70, 120)]))
         knobs = {}
         if rng.random() < 0.75:
-            knobs = {"large_bm": int(rng.choice([128, 256])), "large_bn": int(rng.choice([128, 256])),
+            knobs = {"large_bm": int(rng.choice([64, 128, 256])), "large_bn": int(rng.choice([128, 256])),
                      "large_split": int(rng.choice([1, 1, 2, 3, 5]))}
         W = workloads.weight_host(N, K, seed=100 * seed + case)
         X = workloads.act_host(M, K, seed=100 * seed + case + 50)
@@ -159,6 +161,16 @@ def test_random_shapes_and_launch_shapes(nfp, seed):
         finally:
             for k in knobs:
                 nfp.tune(k, -1)
+
+
+@pytest.mark.parametrize("M", [49, 57, 64])
+def test_tiled_route_of_49_to_64_tokens(nfp, M):
+    # from 49 tokens on, FP16 mode leaves the streaming kernel for 64-token tiles split along K
+    # (on all but the smallest layers): default routing, ragged N, against the oracle
+    N, K = 4100 + 24, 1024 + 48
+    W = workloads.weight_host(N, K, seed=410)
+    X = workloads.act_host(M, K, seed=411)
+    run_both_modes(nfp, X, W, "M=%d" % M, check_plain=False)
 
 
 def test_one_hot_tokens_return_weights_exactly(nfp):
