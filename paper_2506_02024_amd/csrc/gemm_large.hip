@@ -685,10 +685,14 @@ static double split_cost(int64_t M, int64_t N, int slices) {
     return 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
 }
 
-// NestedFP16 with at most 64 tokens: one 64 x 128 tile shape, two workgroups per CU, and only the split to
-// choose. Such a launch is bound by the weight stream, whose rate depends on how many workgroups pull on it.
-static LargeConfig choose_tile64(int64_t M, int64_t N, int kt) {
+// FP16 kinds with at most 64 tokens: one 64 x 128 tile shape, two or three workgroups per CU, and only
+// the split to choose.  Such a launch is bound by the weight stream, whose rate depends on how many
+// workgroups pull on it.  Constants from timings of the four splits on six layer shapes at M = 64.
+struct Tile64Cost { double tk, tfix, rate, rate512; };
+static const Tile64Cost kTile64Cost[2] = {{0.7, 0.4, 4.5e6, 5.5e6}, {0.5, 0.4, 5.0e6, 5.5e6}};   // plain FP16, NestedFP16
+static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
     const Tuning &t = tuning();
+    const Tile64Cost &tc = kTile64Cost[kind];
     LargeConfig c;
     c.tm = 64;  c.tn = 128;  c.split = 1;
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
@@ -699,8 +703,8 @@ static LargeConfig choose_tile64(int64_t M, int64_t N, int kt) {
         const int per = (kt + split - 1) / split;
         const int slices = (kt + per - 1) / per;
         const int64_t wgs = tiles * slices;
-        double time = (double)((wgs + 511) / 512) * (0.4 + per * 0.5);
-        double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? 5.0e6 : 5.5e6);
+        double time = (double)((wgs + 511) / 512) * (tc.tfix + per * tc.tk);
+        double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? tc.rate : tc.rate512);
         if (wgs < 256) floor_t *= std::sqrt(256.0 / (double)wgs);
         if (time < floor_t) time = floor_t;
         if (slices > 1) time += split_cost(M, N, slices);
@@ -714,8 +718,8 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
     const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
-    if (kind == kNestedF16 && (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0)))
-        return choose_tile64(M, N, kt);
+    if (kind <= kNestedF16 && (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0)))
+        return choose_tile64(kind, M, N, kt);
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
@@ -777,7 +781,9 @@ static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
 
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
+    if (c.tm == 64) {
+        if constexpr (KIND == kPlainF16) launch_large_t<KIND, 64, 128, 2, 4>(p, grid, stream);
+    } else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
     else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
     else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
     else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);

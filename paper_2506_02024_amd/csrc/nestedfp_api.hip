@@ -37,6 +37,9 @@ static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) 
     if (kind == kNestedF16 && M > 32 && N >= 16384 && tuning().small_max_m < 0) return false;
     // and from 49 tokens on everywhere but on the smallest layers (64-token tiles, split along K)
     if (kind == kNestedF16 && M > 48 && (N > 4096 || K > 4096) && tuning().small_max_m < 0) return false;
+    // the plain FP16 kernels: the same from 49 tokens on, and from 33 on where both N and K are large
+    if (kind == kPlainF16 && tuning().small_max_m < 0 &&
+        ((M > 48 && (N > 4096 || K > 4096)) || (M > 32 && N >= 8192 && K >= 8192))) return false;
     return true;
 }
 

@@ -328,15 +328,18 @@ def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
     up, lo = nfp.decompose(Wd)
     y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
     # same kernel family and launch shape for both: then FP16 mode and the plain FP16 GEMM agree bit for bit
-    pins = {"small_max_m": 64, "small_spw": 4} if M <= 64 else {"large_bm": 256, "large_bn": 256, "large_split": 1}
-    for k, v in pins.items():
-        nfp.tune(k, v)
-    try:
-        assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd)), \
-            tag + ": FP16 mode differs from plain fp16"
-    finally:
-        for k in pins:
-            nfp.tune(k, -1)
+    pin_sets = [{"small_max_m": 64, "small_spw": 4}] if M <= 64 else [{"large_bm": 256, "large_bn": 256, "large_split": 1}]
+    if 32 < M <= 64:
+        pin_sets.append({"small_max_m": 0, "large_bm": 64, "large_split": 4})      # 64-token tiles of the tiled kernels
+    for pins in pin_sets:
+        for k, v in pins.items():
+            nfp.tune(k, v)
+        try:
+            assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd)), \
+                tag + ": FP16 mode differs from plain fp16 under %s" % pins
+        finally:
+            for k in pins:
+                nfp.tune(k, -1)
     y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
     rows, cols = workloads.sample_indices(M, N, 16, 64, seed=seed)
     ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
