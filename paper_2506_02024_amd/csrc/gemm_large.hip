@@ -75,11 +75,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base
 // MB: rows of an MFMA block (16 or 32).  Accumulator layout: lane l holds token l % MB of a block
 // and, for v = 0 .. MB*MB/256 - 1, the four consecutive weight rows
 // (MB == 32 ? 8 v + 4 (l / 32) : 4 (l / 16)) .. +3.
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int MB_ = (KIND == kE4M3 ? 32 : 16)>
 struct TileStore {
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
-    static constexpr int MB = KIND == kE4M3 ? 32 : 16;
+    static constexpr int MB = MB_;
     static constexpr int FMB = WTM / MB, FNB = WTN / MB;
     typedef typename std::conditional<MB == 32, floatx16, floatx4>::type AccT;
 
@@ -569,7 +569,13 @@ struct BypassKernel {
         // reads them (from the tail of kt+1 on).  Younger than them in this wave: the loads of
         // this K-tile (XG token loads, 2 FNB plane loads).
         if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(XG + 2 * FNB) : "memory");
-        __syncthreads();
+        // a bare barrier: __syncthreads() carries a release fence, which would drain the token loads
+        // issued in this K-tile.  What the fence would order is ordered by the wait above (loads
+        // that have to be visible) and by the MFMAs, which have consumed every LDS read of the
+        // stage that is refilled next.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     }
 
     template <bool OLDER>
@@ -662,6 +668,202 @@ nested_bypass_kernel(LargeParams p) {
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
+// ---- FP8 mode on at most 64 tokens per tile: E4M3 weights through registers ---------------------
+// The same layout of work as nested_bypass_kernel (eight waves side by side along the weight rows,
+// packed 1 KB blocks loaded 16 bytes per lane, token tile in a ring of four LDS stages), for
+// batches where the weight stream is the bound.  A K-tile is 128 bytes of a token row and two
+// blocks of the upper plane; lane group g = l / 16 holds columns 16 g .. + 15 of both blocks, 32
+// bytes, which is one operand of v_mfma_f32_16x16x128_f8f6f4, and reads the same bytes of its token
+// (chunks g and 4 + g of the row).  A token block's fragment of K-tile kt + 1 is read right behind
+// the block's MFMAs of K-tile kt, into the same registers.
+template <int TM, int TN>
+struct E4m3BypassKernel {
+    typedef TileStore<kE4M3, TM, TN, 1, 8, 16> Store;
+    static constexpr int DW = 4;                               // waves that issue the token loads
+    static constexpr int WTN = TN / 8;
+    static constexpr int FMB = TM / 16, FNB = WTN / 16;
+    static constexpr int NST = 8;                              // LDS stages of the token tile
+    static constexpr int XA = 6;                               // token loads run this many K-tiles ahead
+    static constexpr int NRAW = 4;                             // plane blocks are loaded this many K-tiles ahead
+    static constexpr int STAGE = TM * 128;
+    static constexpr int LDS_BYTES = NST * STAGE > TM * TN * 2 ? NST * STAGE : TM * TN * 2;
+    static constexpr int XG = TM / 8 / DW;                     // loads per loading wave per K-tile
+    static_assert(XG >= 1 && FNB >= 1 && FNB <= 2, "tile shape");
+    static_assert(XA >= 3 && XA < NST && NRAW <= XA, "the stage being filled is neither the one in use nor the next");
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    struct Raw { intx4 u[FNB][2]; };                           // one K-tile of the wave's plane blocks
+    struct Tok { intx4 q[FMB][2]; };                           // one K-tile of token fragments
+
+    struct Ctx {
+        floatx4 (&acc)[FNB][FMB];
+        Raw (&raw)[NRAW];
+        Tok &tok;                                              // block J is re-read for the next K-tile right behind its MFMAs
+        __amdgpu_buffer_rsrc_t rx, rw;
+        uint32_t x_off, x_step, x_kpos, x_lim;
+        uint32_t w_off, w_lim;
+        const uint8_t *lds;
+        lds_byte *lds3;
+        int wave, lane, kblocks;
+        int kt;
+    };
+
+    static __device__ __forceinline__ void load_raw(Raw &r, const Ctx &c, int kt) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t kill = ((uint32_t)(2 * kt + h) < c.w_lim) ? 0u : 0x80000000u;
+#pragma unroll
+            for (int i = 0; i < FNB; ++i)
+                r.u[i][h] = __builtin_bit_cast(intx4, __builtin_amdgcn_raw_buffer_load_b128(
+                    c.rw, (c.w_off + (uint32_t)(i * c.kblocks + 2 * kt + h) * 1024u) | kill, 0, 0));
+        }
+    }
+
+    static __device__ __forceinline__ void dma_x(const Ctx &c, int i, int kt) {
+        const uint32_t kb = (uint32_t)kt * 128u;
+        const uint32_t kill = (kb + c.x_kpos < c.x_lim) ? 0u : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rx, (__attribute__((address_space(3))) void *)(c.lds3 + (kt & (NST - 1)) * STAGE + (i * DW + c.wave) * 1024),
+                                                 16, (c.x_off + (uint32_t)i * c.x_step + kb) | kill, 0, 0, 0);
+    }
+
+    template <int J>
+    static __device__ __forceinline__ void read_tok(Tok &t, const uint8_t *stage, int lane) {
+        t.q[J][0] = *reinterpret_cast<const intx4 *>(stage + swz(16 * J + (lane & 15), lane >> 4));
+        t.q[J][1] = *reinterpret_cast<const intx4 *>(stage + swz(16 * J + (lane & 15), 4 + (lane >> 4)));
+    }
+
+    template <int J>
+    static __device__ __forceinline__ void block(Ctx &c, const Raw &r, const uint8_t *next_stage) {
+        const intx8 b = __builtin_shufflevector(c.tok.q[J][0], c.tok.q[J][1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int i = 0; i < FNB; ++i) {
+            const intx8 a = __builtin_shufflevector(r.u[i][0], r.u[i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            c.acc[i][J] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c.acc[i][J], 0, 0, 0, 0, 0, 0);
+        }
+        read_tok<J>(c.tok, next_stage, c.lane);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (J + 1 < FMB) block<J + 1>(c, r, next_stage);
+    }
+
+    // PAR: which register set holds this K-tile's plane blocks
+    template <bool OLDER, int PAR>
+    static __device__ __forceinline__ void k_tile(Ctx &c) {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (OLDER) {
+#pragma unroll
+            for (int i = 0; i < XG; ++i) dma_x(c, i, c.kt + XA);
+        }
+        block<0>(c, c.raw[PAR], c.lds + ((c.kt + 1) & (NST - 1)) * STAGE);
+        load_raw(c.raw[PAR], c, c.kt + NRAW);                  // its blocks are used up
+        // The token loads of K-tile kt+2 (issued during kt+2-XA) must have landed before anybody
+        // reads them (during kt+1).  Younger than them in this wave, and allowed to be in flight:
+        // the plane loads of that K-tile and all loads of the XA-2 K-tiles since.
+        if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * FNB + (XA - 2) * (XG + 2 * FNB)) : "memory");
+        // a bare barrier: __syncthreads() carries a release fence, which would drain the token loads
+        // just issued.  What the fence would order is ordered by the wait above (loads that have to
+        // be visible) and by the MFMAs that consumed every LDS read of the stage refilled next.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+
+    template <bool OLDER>
+    static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
+        static_assert(NRAW == 4, "unrolled by the number of register sets");
+        int kt = kt_begin;
+        for (; kt + 4 <= kt_end; kt += 4) {
+            c.kt = kt;
+            k_tile<OLDER, 0>(c);
+            c.kt = kt + 1;
+            k_tile<OLDER, 1>(c);
+            c.kt = kt + 2;
+            k_tile<OLDER, 2>(c);
+            c.kt = kt + 3;
+            k_tile<OLDER, 3>(c);
+        }
+        if (kt < kt_end) {
+            c.kt = kt;
+            k_tile<OLDER, 0>(c);
+            if (kt + 1 < kt_end) {
+                c.kt = kt + 1;
+                k_tile<OLDER, 1>(c);
+                if (kt + 2 < kt_end) {
+                    c.kt = kt + 2;
+                    k_tile<OLDER, 2>(c);
+                }
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int tile = blockIdx.x;
+        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        const int m0 = tm * TM, n0 = tn * TN;
+        const int split = blockIdx.y;
+        const int kt_begin = split * p.ktiles_per_split;
+        const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
+
+        floatx4 acc[FNB][FMB];
+#pragma unroll
+        for (int i = 0; i < FNB; ++i)
+#pragma unroll
+            for (int j = 0; j < FMB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        Raw raw[NRAW];
+        Tok tok;
+        Ctx c{acc, raw, tok,
+              tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes),
+              plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks),
+              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, (uint32_t)p.kblocks, lds, lds3, wave, lane,
+              p.kblocks, kt_begin};
+        {
+            const int ch = (lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);    // (row >> 1) & 7 for row = gid*8 + lane/8
+            c.x_kpos = 16u * ch;
+            c.x_off = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * ch;
+            c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+        }
+        // token tiles of the first XA K-tiles, plane blocks of the first NRAW
+        if (wave < DW) {
+#pragma unroll
+            for (int d = 0; d < XA; ++d)
+#pragma unroll
+                for (int i = 0; i < XG; ++i) dma_x(c, i, kt_begin + d);
+        }
+#pragma unroll
+        for (int d = 0; d < NRAW; ++d) load_raw(raw[d], c, kt_begin + d);
+        // the token tiles of the first two K-tiles: in order, everything but the later token loads
+        // and the plane loads has landed
+        if (wave < DW) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((XA - 2) * XG + NRAW * 2 * FNB) : "memory");
+        __syncthreads();
+        {
+            const uint8_t *st0 = lds + (kt_begin & (NST - 1)) * STAGE;
+            read_tok<0>(tok, st0, lane);
+            if constexpr (FMB > 1) read_tok<1>(tok, st0, lane);
+            if constexpr (FMB > 2) read_tok<2>(tok, st0, lane);
+            if constexpr (FMB > 3) read_tok<3>(tok, st0, lane);
+            static_assert(FMB <= 4, "prologue reads");
+        }
+        if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
+        else k_loop<false>(c, kt_begin, kt_end);
+        if (p.row_store && gridDim.y == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
+            __syncthreads();
+            Store::epilogue_lds(p, acc, m0, n0, 0, wave, lane, wave, lds);
+        } else {
+            Store::epilogue(p, acc, m0, n0, 0, wave, lane, split);
+        }
+    }
+};
+
+template <int TM, int TN>
+__global__ void __launch_bounds__(512)
+e4m3_bypass_kernel(LargeParams p) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    typedef E4m3BypassKernel<TM, TN> Kern;
+    Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
+}
+
 struct LargeConfig { int tm, tn, split; };
 
 // Tile shape and K split from a small cost model.  The workgroups are dealt round-robin to the
@@ -685,11 +887,20 @@ static double split_cost(int64_t M, int64_t N, int slices) {
     return 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
 }
 
-// FP16 kinds with at most 64 tokens: one 64 x 128 tile shape, two or three workgroups per CU, and only
-// the split to choose.  Such a launch is bound by the weight stream, whose rate depends on how many
-// workgroups pull on it.  Constants from timings of the four splits on six layer shapes at M = 64.
-struct Tile64Cost { double tk, tfix, rate, rate512; };
-static const Tile64Cost kTile64Cost[2] = {{0.7, 0.4, 4.5e6, 5.5e6}, {0.5, 0.4, 5.0e6, 5.5e6}};   // plain FP16, NestedFP16
+// At most 64 tokens: one 64 x 128 tile shape per weight kind and only the split to choose.  Such a
+// launch is bound by the weight stream, whose rate depends on how many workgroups pull on it.
+// Constants from timings of the four splits on six layer shapes at M = 64.
+struct Tile64Cost {
+    double tk, tfix;        // microseconds per K-tile and per workgroup
+    int slots;              // workgroups the chip holds at a time
+    double rate, rate512;   // bytes per microsecond of the weight stream (from 512 workgroups on)
+    double few;             // exponent of the rate's fall below 256 workgroups
+};
+static const Tile64Cost kTile64Cost[3] = {
+    {0.7, 0.4, 512, 4.5e6, 5.5e6, 0.5},       // plain FP16 (LDS kernel, three workgroups per CU)
+    {0.466, 0.4, 512, 5.25e6, 5.5e6, 0.5},    // NestedFP16 (register path, two per CU)
+    {0.35, 0.4, 256, 5.5e6, 5.5e6, 0.3},      // E4M3 (register path, one per CU)
+};
 static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
     const Tuning &t = tuning();
     const Tile64Cost &tc = kTile64Cost[kind];
@@ -703,9 +914,9 @@ static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
         const int per = (kt + split - 1) / split;
         const int slices = (kt + per - 1) / per;
         const int64_t wgs = tiles * slices;
-        double time = (double)((wgs + 511) / 512) * (tc.tfix + per * tc.tk);
+        double time = (double)((wgs + tc.slots - 1) / tc.slots) * (tc.tfix + per * tc.tk);
         double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? tc.rate : tc.rate512);
-        if (wgs < 256) floor_t *= std::sqrt(256.0 / (double)wgs);
+        if (wgs < 256) floor_t *= std::pow(256.0 / (double)wgs, tc.few);
         if (time < floor_t) time = floor_t;
         if (slices > 1) time += split_cost(M, N, slices);
         if (time < best) { best = time;  c.split = split; }
@@ -718,8 +929,8 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
     const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
-    if (kind <= kNestedF16 && (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0)))
-        return choose_tile64(kind, M, N, kt);
+    if (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0))
+        return choose_tile64(kind > kE4M3 ? kE4M3 : kind, M, N, kt);
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
@@ -779,10 +990,23 @@ static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
     kern<<<grid, 512, lds, stream>>>(p);
 }
 
+template <int TM, int TN>
+static void launch_e4m3_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
+    auto kern = e4m3_bypass_kernel<TM, TN>;
+    constexpr int lds = E4m3BypassKernel<TM, TN>::LDS_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    kern<<<grid, 512, lds, stream>>>(p);
+}
+
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
     if (c.tm == 64) {
         if constexpr (KIND == kPlainF16) launch_large_t<KIND, 64, 128, 2, 4>(p, grid, stream);
+        else launch_e4m3_bypass<64, 128>(p, grid, stream);
     } else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
     else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
     else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);

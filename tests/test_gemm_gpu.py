@@ -173,6 +173,15 @@ def test_tiled_route_of_49_to_64_tokens(nfp, M):
     run_both_modes(nfp, X, W, "M=%d" % M, check_plain=False)
 
 
+@pytest.mark.parametrize("M,N,K", [(50, 16384 + 40, 256 + 16), (64, 264, 14336 + 80)])
+def test_fp8_mode_tiled_route_of_49_to_64_tokens(nfp, M, N, K):
+    # FP8 mode takes 64-token tiles (E4M3 blocks through registers) on wide layers and on layers
+    # with a long K: default routing, ragged N and K, against the oracle
+    W = workloads.weight_host(N, K, seed=420)
+    X = workloads.act_host(M, K, seed=421)
+    run_both_modes(nfp, X, W, "M=%d N=%d K=%d" % (M, N, K), check_plain=False)
+
+
 def test_one_hot_tokens_return_weights_exactly(nfp):
     # FP16 mode with one-hot rows returns the reconstructed weights themselves: checks the
     # operand layout, the transposition and Alg. 1 bit-exactly inside the GEMM kernels
