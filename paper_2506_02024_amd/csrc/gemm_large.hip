@@ -474,7 +474,12 @@ struct BypassKernel {
     static constexpr int WTN = TN / 8;
     static constexpr int FMB = TM / 16, FNB = WTN / 16;
     static constexpr int MF = FMB * FNB;                       // MFMAs per substep
-    static constexpr int NST = 4;
+    // (a ring of eight stages with the token loads six and the plane loads three K-tiles ahead was
+    // no faster for the 64-token tiles)
+    static constexpr int NST = 4;                              // LDS stages of the token tile
+    static constexpr int XA = 3;                               // token loads run this many K-tiles ahead
+    static constexpr int NRAW = 2;                             // plane blocks are loaded this many K-tiles ahead
+    static_assert(XA >= 3 && XA < NST && NRAW <= XA && NRAW >= 2, "the stage being filled is neither the one in use nor the next");
     static constexpr int STAGE = TM * 128;
     static constexpr int LDS_BYTES = NST * STAGE > TM * TN * 2 ? NST * STAGE : TM * TN * 2;
     static constexpr int XG = TM / 8 / DW;                     // loads per loading wave per K-tile
@@ -491,7 +496,7 @@ struct BypassKernel {
         floatx4 (&acc)[FNB][FMB];
         intx4 (&a)[2][FNB];                                    // merged weight fragments of substeps 0 / 1
         intx4 (&b)[2][FMB];                                    // token fragments (a few are live at a time)
-        Raw (&raw)[2];
+        Raw (&raw)[NRAW];
         __amdgpu_buffer_rsrc_t rx, rw0, rw1;
         uint32_t x_off, x_step, x_kpos, x_lim;               // offset of the wave's first load, step between its loads
         uint32_t w_off, w_lim;
@@ -532,7 +537,7 @@ struct BypassKernel {
                                                  16, (c.x_off + (uint32_t)i * c.x_step + kb) | kill, 0, 0, 0);
     }
 
-    // PAR: which register set holds the plane blocks of this K-tile (the other one holds the next)
+    // PAR: which register set holds the plane blocks of this K-tile (the one after it holds the next)
     template <bool OLDER, int S, int PAR, int Q>
     static __device__ __forceinline__ void slot(Ctx &c) {
         constexpr int j = Q / FNB, i = Q % FNB;
@@ -552,10 +557,10 @@ struct BypassKernel {
             // substep 0 merges this K-tile's second half, substep 1 the next K-tile's first half
             constexpr int m = Q / MQS;
             if constexpr (S == 0) merge_part<1, m / 2, m % 2>(c.a[1][m / 2], c.raw[PAR]);
-            else merge_part<0, m / 2, m % 2>(c.a[0][m / 2], c.raw[PAR ^ 1]);
+            else merge_part<0, m / 2, m % 2>(c.a[0][m / 2], c.raw[(PAR + 1) % NRAW]);
         }
-        if constexpr (OLDER && S == 0 && Q % DQS == 0) dma_x(c, Q / DQS, c.kt + 3);
-        if constexpr (S == 1 && Q == 0) load_raw(c.raw[PAR], c, c.kt + 2);     // its blocks are merged; two K-tiles ahead
+        if constexpr (OLDER && S == 0 && Q % DQS == 0) dma_x(c, Q / DQS, c.kt + XA);
+        if constexpr (S == 1 && Q == 0) load_raw(c.raw[PAR], c, c.kt + NRAW);  // its blocks are merged
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
     }
@@ -565,10 +570,11 @@ struct BypassKernel {
         __builtin_amdgcn_sched_barrier(0);
         slot<OLDER, 0, PAR, 0>(c);
         slot<OLDER, 1, PAR, 0>(c);
-        // The token loads of K-tile kt+2 (issued during kt-1) must have landed before anybody
-        // reads them (from the tail of kt+1 on).  Younger than them in this wave: the loads of
-        // this K-tile (XG token loads, 2 FNB plane loads).
-        if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(XG + 2 * FNB) : "memory");
+        // The token loads of K-tile kt+2 (issued during kt+2-XA) must have landed before anybody
+        // reads them (from the tail of kt+1 on).  Younger than them in this wave, and allowed to
+        // be in flight: the plane loads of that K-tile and all loads of the XA-2 K-tiles since
+        // (for XA = 3 the count is rounded down to this K-tile's loads).
+        if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(XA == 3 ? XG + 2 * FNB : 2 * FNB + (XA - 2) * (XG + 2 * FNB)) : "memory");
         // a bare barrier: __syncthreads() carries a release fence, which would drain the token loads
         // issued in this K-tile.  What the fence would order is ordered by the wait above (loads
         // that have to be visible) and by the MFMAs, which have consumed every LDS read of the
@@ -580,14 +586,29 @@ struct BypassKernel {
 
     template <bool OLDER>
     static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
-        for (int kt = kt_begin; kt < kt_end; kt += 2) {
-            c.kt = kt;
-            c.st = kt & (NST - 1);
-            k_tile<OLDER, 0>(c);
-            if (kt + 1 < kt_end) {
-                c.kt = kt + 1;
-                c.st = (kt + 1) & (NST - 1);
-                k_tile<OLDER, 1>(c);
+        // no branch inside the loop body: the compiler then counts the loads in flight exactly
+        // instead of draining them at the loop head
+        int kt = kt_begin;
+        for (; kt + NRAW <= kt_end; kt += NRAW) k_tiles<OLDER, 0, NRAW>(c, kt);
+        tail<OLDER, 0>(c, kt, kt_end);
+    }
+
+    // K-tiles kt + P .. kt + END - 1, on register sets P .. END - 1
+    template <bool OLDER, int P, int END>
+    static __device__ __forceinline__ void k_tiles(Ctx &c, int kt) {
+        c.kt = kt + P;
+        c.st = (kt + P) & (NST - 1);
+        k_tile<OLDER, P>(c);
+        if constexpr (P + 1 < END) k_tiles<OLDER, P + 1, END>(c, kt);
+    }
+
+    // the last 0 .. NRAW - 1 K-tiles
+    template <bool OLDER, int P>
+    static __device__ __forceinline__ void tail(Ctx &c, int kt, int kt_end) {
+        if constexpr (P + 1 < NRAW) {
+            if (kt + P < kt_end) {
+                k_tiles<OLDER, P, P + 1>(c, kt);
+                tail<OLDER, P + 1>(c, kt, kt_end);
             }
         }
     }
@@ -609,7 +630,7 @@ struct BypassKernel {
 #pragma unroll
             for (int j = 0; j < FMB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
         intx4 a[2][FNB], b[2][FMB];
-        Raw raw[2];
+        Raw raw[NRAW];
         Ctx c{acc, a, b, raw,
               tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes),
               plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks), plane_rsrc(p.W1, n0, min(TN, p.N - n0), p.kblocks),
@@ -622,17 +643,17 @@ struct BypassKernel {
             c.x_off = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * ch;
             c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
         }
-        // token tiles of the first three K-tiles, plane blocks of the first two
+        // token tiles of the first XA K-tiles, plane blocks of the first NRAW
         if (wave < DW) {
 #pragma unroll
-            for (int d = 0; d < 3; ++d)
+            for (int d = 0; d < XA; ++d)
 #pragma unroll
                 for (int i = 0; i < XG; ++i) dma_x(c, i, kt_begin + d);
         }
-        load_raw(raw[0], c, kt_begin);
-        load_raw(raw[1], c, kt_begin + 1);
+#pragma unroll
+        for (int d = 0; d < NRAW; ++d) load_raw(raw[d], c, kt_begin + d);
         // (in order: once the first plane blocks are here, the token loads issued before them are too)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * FNB) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NRAW - 1) * 2 * FNB) : "memory");
         merge_part<0, 0, 0>(a[0][0], raw[0]);
         merge_part<0, 0, 1>(a[0][0], raw[0]);
         if constexpr (FNB > 1) {
@@ -650,12 +671,15 @@ struct BypassKernel {
         }
         if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
+        // (keeps the epilogue's address arithmetic behind the loop, where registers are free)
+        int lane_out = lane;
+        asm volatile("" : "+v"(lane_out));
         if (p.row_store && gridDim.y == 1) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
             __syncthreads();
-            Store::epilogue_lds(p, acc, m0, n0, 0, wave, lane, wave, lds);
+            Store::epilogue_lds(p, acc, m0, n0, 0, wave, lane_out, wave, lds);
         } else {
-            Store::epilogue(p, acc, m0, n0, 0, wave, lane, split);
+            Store::epilogue(p, acc, m0, n0, 0, wave, lane_out, split);
         }
     }
 };
@@ -876,15 +900,15 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};   // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.320, 0.0}, {1.014, 0.0}, {1.094, 0.40}, {0.812, 0.0}},      // plain FP16
-    {{1.296, 1.01}, {0.942, 0.03}, {0.926, 1.56}, {0.673, 0.0}},    // NestedFP16
-    {{1.335, 3.30}, {1.085, 1.08}, {1.103, 2.54}, {0.875, 0.63}},   // E4M3
+    {{1.322, 0.05}, {1.012, 0.0}, {1.096, 0.16}, {0.809, 0.0}},     // plain FP16
+    {{1.241, 1.29}, {0.865, 0.99}, {0.889, 2.32}, {0.563, 0.38}},   // NestedFP16
+    {{1.337, 3.09}, {1.094, 0.91}, {1.109, 2.32}, {0.875, 0.51}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.47, 1.18, 1.41};
+static const double kPairSpeedup[3] = {1.47, 1.00, 1.41};
 
 // split-K cost: the reduction kernel's launch plus its traffic
 static double split_cost(int64_t M, int64_t N, int slices) {
-    return 4.46 + 8.0 * (double)M * (double)N * slices / 4.31e6;
+    return 4.56 + 8.0 * (double)M * (double)N * slices / 4.24e6;
 }
 
 // At most 64 tokens: one 64 x 128 tile shape per weight kind and only the split to choose.  Such a
@@ -936,7 +960,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.75e6;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.51e6;
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
