@@ -133,7 +133,7 @@ size_t nestedfp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int mode);
  *     kernel, fp16 MFMA with fp32 accumulation, fp16 output.  Bitwise equal to
  *     nestedfp_plain_gemm_fp16 on the original weights whenever the two run with the same
  *     launch shape (the built-in choice is made per kernel and may differ; the knobs
- *     large_bm / large_bn / large_split and small_spw of nestedfp_tune pin it).
+ *     small_max_m, small_spw, large_bm / large_bn / large_split of nestedfp_tune pin it).
  *   FP8 mode: quantises X per token (or with *act_scale, device float, if non-NULL),
  *     multiplies E4M3 activations by the upper plane read as E4M3, fp32 accumulation,
  *     scales by scale[m] * 2^-8 (Sec. 4.1: the upper plane is the weight times 2^8),
