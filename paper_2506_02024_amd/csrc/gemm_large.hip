@@ -1,14 +1,16 @@
 // LDS-tiled MFMA GEMMs for prefill-sized batches: Y = X * W^T, compute-bound.
 //
-// Two kernels.  large_gemm_kernel multiplies plain FP16 weights or E4M3 weights (FP8 mode: the
+// Three kernels.  large_gemm_kernel multiplies plain FP16 weights or E4M3 weights (FP8 mode: the
 // upper plane as it is): TM tokens x TN weight rows x 128 bytes of K per row (64 halves or 128
 // E4M3 bytes) per stage, two LDS stages, 8 waves.  nested_bypass_kernel is FP16 mode: Sec. 4.2
 // puts the FP16 reconstruction between the shared-memory-to-register copy and the tensor-core
 // instruction of every warp and hides it with a third pipeline stage; here every weight belongs
 // to exactly one wave, which loads the packed plane blocks into registers, merges them there
-// (Alg. 1) and feeds them to the MFMA -- the weights never pass through LDS.
+// (Alg. 1) and feeds them to the MFMA -- the weights never pass through LDS.  e4m3_bypass_kernel
+// is the same register path for E4M3 weights, used for batches of 49 .. 64 tokens, where the
+// weight stream is the bound.
 //
-// In both, weight rows are the MFMA "A" operand and tokens the "B" operand, so a lane holds 4
+// In all of them, weight rows are the MFMA "A" operand and tokens the "B" operand, so a lane holds 4
 // consecutive output columns of one token.  Tokens and plain / E4M3 weights reach LDS by
 // direct-to-LDS buffer loads; FP16 rows are 128 bytes with the 16-byte chunk index XOR-swizzled
 // with the row so that the MFMA fragment reads are free of bank conflicts, packed E4M3 blocks

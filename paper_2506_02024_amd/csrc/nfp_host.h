@@ -41,7 +41,7 @@ struct Tuning {
     int64_t small_tiles;     // 16-row weight tiles per workgroup
     int64_t small_interleave;  // 1: a workgroup's tiles are strided by the grid size
     int64_t large_split;     // grid-level split-K of the tiled kernel
-    int64_t large_bm;        // tokens per tile of the tiled kernel (64 for the FP16 kinds only, 128 or 256)
+    int64_t large_bm;        // tokens per tile of the tiled kernel (64, 128 or 256)
     int64_t large_bn;        // weight rows per tile (128 or 256; unset: same as large_bm)
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
     int64_t small_fuse_quant;  // 1: quantise activations inside the streaming kernel where it can
