@@ -673,6 +673,9 @@ struct BypassKernel {
         }
         if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
+        // token loads of K-tiles past the end are still in flight: they must have landed before the
+        // LDS is reused for the output tile or handed back
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         // (keeps the epilogue's address arithmetic behind the loop, where registers are free)
         int lane_out = lane;
         asm volatile("" : "+v"(lane_out));
@@ -872,6 +875,9 @@ struct E4m3BypassKernel {
         }
         if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
+        // token loads of K-tiles past the end are still in flight: they must have landed before the
+        // LDS is reused for the output tile or handed back
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (p.row_store && gridDim.y == 1) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
             __syncthreads();
