@@ -440,6 +440,9 @@ struct LargeKernel {
         read_frags<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
         if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
+        // the loads of the two K-tiles past the end are still in flight: they must have landed
+        // before the LDS is reused for the output tile or handed back
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (p.row_store && gridDim.y == 1) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the look-ahead fragment reads
             __syncthreads();
