@@ -40,7 +40,32 @@ struct LargeParams {
     int ktiles_total, ktiles_per_split;
     int vec_store;
     int row_store;          // Y rows can be written 16 bytes per lane (N, ldy multiples of 8, Y 16-byte aligned)
+    int xcd_map;            // group the token tiles of a weight tile on one XCD (see tile_of_block)
 };
+
+// Which tile a workgroup takes.  The hardware deals consecutive workgroups to the 8 XCDs in turn,
+// and every XCD has an L2 of its own.  With few token tiles per weight tile (batches of up to about
+// 1000 tokens) the launch order "token tile fastest" puts the token tiles of one weight tile on
+// different XCDs, so each of them fetches those weights from memory again; instead, workgroup
+// b of XCD b % 8 takes token tile (b / 8) % tiles_m of weight tile 8 * ((b / 8) / tiles_m) + b % 8:
+// all token tiles of a weight tile follow each other on one XCD.  The last tiles_n % 8 weight tiles
+// keep the launch order.  With many token tiles per weight tile the launch order already gives
+// every XCD a near-square block of tiles (tiles_m / 8 token tiles x 8 weight tiles at a time).
+__device__ __forceinline__ void tile_of_block(const LargeParams &p, int b, int &tm, int &tn) {
+    const int grouped = 8 * p.tiles_m * (p.tiles_n >> 3);
+    if (p.xcd_map && b < grouped) {
+        const int j = b >> 3;
+        tm = j % p.tiles_m;
+        tn = (j / p.tiles_m) * 8 + (b & 7);
+    } else if (p.xcd_map) {
+        const int r = b - grouped;
+        tm = r % p.tiles_m;
+        tn = (p.tiles_n & ~7) + r / p.tiles_m;
+    } else {
+        tm = b % p.tiles_m;
+        tn = b / p.tiles_m;
+    }
+}
 
 // LDS tiles are rows of 128 bytes; the 16-byte chunk index is XOR-ed with (row >> 1) & 7.
 // gfx950 serves ds_read_b128 at 256 B/clk only if 16 consecutive lanes hit 64 distinct
@@ -400,8 +425,8 @@ struct LargeKernel {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-        const int tile = blockIdx.x;
-        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        int tm, tn;
+        tile_of_block(p, blockIdx.x, tm, tn);
         const int m0 = tm * TM, n0 = tn * TN;
         const int split = blockIdx.y;
         const int kt_begin = split * p.ktiles_per_split;
@@ -621,8 +646,8 @@ struct BypassKernel {
     static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int tile = blockIdx.x;
-        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        int tm, tn;
+        tile_of_block(p, blockIdx.x, tm, tn);
         const int m0 = tm * TM, n0 = tn * TN;
         const int split = blockIdx.y;
         // the LDS stage of a K-tile is kt % 4: start the slice on a multiple of 4 as far as the ring goes
@@ -830,8 +855,8 @@ struct E4m3BypassKernel {
     static __device__ __forceinline__ void run(const LargeParams &p, uint8_t *lds, lds_byte *lds3) {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int tile = blockIdx.x;
-        const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+        int tm, tn;
+        tile_of_block(p, blockIdx.x, tm, tn);
         const int m0 = tm * TM, n0 = tn * TN;
         const int split = blockIdx.y;
         const int kt_begin = split * p.ktiles_per_split;
@@ -911,15 +936,15 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};   // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.322, 0.05}, {1.012, 0.0}, {1.096, 0.16}, {0.809, 0.0}},     // plain FP16
-    {{1.241, 1.29}, {0.865, 0.99}, {0.889, 2.32}, {0.563, 0.38}},   // NestedFP16
-    {{1.337, 3.09}, {1.094, 0.91}, {1.109, 2.32}, {0.875, 0.51}},   // E4M3
+    {{1.300, 1.39}, {1.021, 0.0}, {1.069, 0.0}, {0.804, 0.0}},      // plain FP16
+    {{1.237, 2.95}, {0.856, 1.85}, {0.874, 1.23}, {0.535, 0.0}},    // NestedFP16
+    {{1.283, 5.43}, {1.074, 2.01}, {1.078, 2.37}, {0.853, 0.74}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.47, 1.00, 1.41};
+static const double kPairSpeedup[3] = {1.50, 1.00, 1.43};
 
 // split-K cost: the reduction kernel's launch plus its traffic
-static double split_cost(int64_t M, int64_t N, int slices) {
-    return 4.56 + 8.0 * (double)M * (double)N * slices / 4.24e6;
+static double split_cost(int64_t M, int64_t N, int slices, double launch_us, double bytes_per_us) {
+    return launch_us + 8.0 * (double)M * (double)N * slices / bytes_per_us;
 }
 
 // At most 64 tokens: one 64 x 128 tile shape per weight kind and only the split to choose.  Such a
@@ -953,7 +978,7 @@ static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
         double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? tc.rate : tc.rate512);
         if (wgs < 256) floor_t *= std::pow(256.0 / (double)wgs, tc.few);
         if (time < floor_t) time = floor_t;
-        if (slices > 1) time += split_cost(M, N, slices);
+        if (slices > 1) time += split_cost(M, N, slices, 4.56, 4.24e6);
         if (time < best) { best = time;  c.split = split; }
         if (t.large_split > 0) break;
     }
@@ -971,7 +996,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 4.51e6;
+    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 3.68e6;
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
@@ -987,7 +1012,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += split_cost(M, N, slices);
+            if (slices > 1) time += split_cost(M, N, slices, 2.70, 4.44e6);
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
@@ -1076,6 +1101,7 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     p.ktiles_total = (p.k_bytes + 127) / 128;
     p.ktiles_per_split = (p.ktiles_total + c.split - 1) / c.split;
     c.split = (p.ktiles_total + p.ktiles_per_split - 1) / p.ktiles_per_split;   // no empty slices
+    p.xcd_map = (tuning().large_xcd_map != 0 && p.tiles_m >= 2 && p.tiles_m <= 8) ? 1 : 0;
     p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
     p.row_store = ((a.N & 7) == 0 && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0) ? 1 : 0;
     if (tuning().large_epilogue == 0) p.row_store = 0;

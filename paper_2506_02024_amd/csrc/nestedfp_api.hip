@@ -9,7 +9,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1, -1};
     return t;
 }
 
@@ -379,7 +379,7 @@ int nestedfp_linear(const uint16_t *X, int64_t M, int64_t ldx, const nestedfp_la
 }
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
-                                     "large_split", "large_bm", "large_bn", "large_epilogue", "small_fuse_quant", "quant_hw",
+                                     "large_split", "large_bm", "large_bn", "large_epilogue", "small_fuse_quant", "quant_hw", "large_xcd_map",
                                      nullptr};
 
 const char *nestedfp_tune_name(int index) {
@@ -402,6 +402,7 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "large_epilogue")) t.large_epilogue = value;
     else if (!strcmp(knob, "small_fuse_quant")) t.small_fuse_quant = value;
     else if (!strcmp(knob, "quant_hw")) t.quant_hw = value < 0 ? 1 : value;
+    else if (!strcmp(knob, "large_xcd_map")) t.large_xcd_map = value;
     else return NESTEDFP_ERR_ARG;
     return NESTEDFP_OK;
 }

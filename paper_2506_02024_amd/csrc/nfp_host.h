@@ -46,6 +46,7 @@ struct Tuning {
     int64_t large_epilogue;  // 0: store results straight from the MFMA layout instead of row-wise through LDS
     int64_t small_fuse_quant;  // 1: quantise activations inside the streaming kernel where it can
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
+    int64_t large_xcd_map;   // 0: tiles in launch order instead of grouped by XCD (tiled kernels)
 };
 Tuning &tuning();
 

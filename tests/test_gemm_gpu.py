@@ -182,6 +182,34 @@ def test_fp8_mode_tiled_route_of_49_to_64_tokens(nfp, M, N, K):
     run_both_modes(nfp, X, W, "M=%d N=%d K=%d" % (M, N, K), check_plain=False)
 
 
+@pytest.mark.parametrize("M,N,K,bm,bn", [(300, 1100, 512, 128, 128), (300, 600, 256, 128, 128), (700, 2300, 384, 256, 256),
+                                         (1000, 3000, 192, 128, 256), (520, 1160, 640, 256, 128)])
+def test_xcd_grouped_tile_order_changes_nothing(nfp, M, N, K, bm, bn):
+    # 2 .. 8 token tiles per weight tile: the workgroups take their tiles grouped by XCD (all token
+    # tiles of a weight tile on one XCD; the last tiles_n % 8 weight tiles in launch order).  Every
+    # tile is still computed exactly once: same bits as with the plain launch order, all kinds
+    W = workloads.weight_host(N, K, seed=430)
+    X = workloads.act_host(M, K, seed=431)
+    Xd, Wd = to_dev(X), to_dev(W)
+    up, lo = nfp.decompose(Wd)
+    pins = {"large_bm": bm, "large_bn": bn, "large_split": 1}
+    outs = {}
+    for order in (0, -1):
+        for k, v in pins.items():
+            nfp.tune(k, v)
+        nfp.tune("large_xcd_map", order)
+        try:
+            outs[order] = (bits(nfp.gemm(Xd, up, lo, nfp.MODE_FP16)), bits(nfp.plain_gemm_fp16(Xd, Wd)),
+                           bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8)))
+        finally:
+            for k in pins:
+                nfp.tune(k, -1)
+            nfp.tune("large_xcd_map", -1)
+    for a, b in zip(outs[0], outs[-1]):
+        assert np.array_equal(a, b)
+    assert_gemm_close(outs[-1][0].view(np.float16), oracle.gemm_fp16(X, W), "grouped tile order, FP16 mode")
+
+
 def test_one_hot_tokens_return_weights_exactly(nfp):
     # FP16 mode with one-hot rows returns the reconstructed weights themselves: checks the
     # operand layout, the transposition and Alg. 1 bit-exactly inside the GEMM kernels
