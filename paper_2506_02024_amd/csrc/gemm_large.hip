@@ -936,11 +936,11 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};   // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.300, 1.39}, {1.021, 0.0}, {1.069, 0.0}, {0.804, 0.0}},      // plain FP16
-    {{1.237, 2.95}, {0.856, 1.85}, {0.874, 1.23}, {0.535, 0.0}},    // NestedFP16
-    {{1.283, 5.43}, {1.074, 2.01}, {1.078, 2.37}, {0.853, 0.74}},   // E4M3
+    {{1.332, 0.0}, {1.050, 0.0}, {1.094, 0.0}, {0.834, 0.0}},       // plain FP16
+    {{1.214, 2.98}, {0.859, 1.44}, {0.880, 0.68}, {0.541, 0.0}},    // NestedFP16
+    {{1.304, 4.75}, {1.072, 2.17}, {1.094, 2.07}, {0.853, 0.98}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.50, 1.00, 1.43};
+static const double kPairSpeedup[3] = {1.54, 1.00, 1.47};
 
 // split-K cost: the reduction kernel's launch plus its traffic
 static double split_cost(int64_t M, int64_t N, int slices, double launch_us, double bytes_per_us) {
@@ -996,7 +996,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double mem_floor = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0) / 3.68e6;
+    const double w_bytes = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0);
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
@@ -1011,8 +1011,13 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             const int64_t rounds = (tiles * slices + 255) / 256;
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
+            // the weights' one pass over the memory bus: faster with two workgroups per CU pulling,
+            // slower while the chip is not full
+            const int64_t wgs = tiles * slices;
+            double mem_floor = w_bytes / (wgs < 512 ? 4.39e6 : 4.8e6);
+            if (wgs < 256) mem_floor *= std::sqrt(256.0 / (double)wgs);
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += split_cost(M, N, slices, 2.70, 4.44e6);
+            if (slices > 1) time += split_cost(M, N, slices, 3.16, 4.42e6);
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
