@@ -936,11 +936,11 @@ struct LargeConfig { int tm, tn, split; };
 struct TileCost { double tk, tfix; };                  // per K-tile, per workgroup
 static const int kTileShapes[4][2] = {{256, 256}, {256, 128}, {128, 256}, {128, 128}};   // tokens x weight rows
 static const TileCost kTileCost[3][4] = {
-    {{1.332, 0.0}, {1.050, 0.0}, {1.094, 0.0}, {0.834, 0.0}},       // plain FP16
-    {{1.214, 2.98}, {0.859, 1.44}, {0.880, 0.68}, {0.541, 0.0}},    // NestedFP16
-    {{1.304, 4.75}, {1.072, 2.17}, {1.094, 2.07}, {0.853, 0.98}},   // E4M3
+    {{1.353, 0.0}, {1.053, 0.07}, {1.098, 0.0}, {0.848, 0.0}},      // plain FP16
+    {{1.242, 2.30}, {0.873, 0.75}, {0.887, 0.17}, {0.542, 0.0}},    // NestedFP16
+    {{1.317, 4.39}, {1.061, 2.10}, {1.089, 2.28}, {0.864, 1.01}},   // E4M3
 };
-static const double kPairSpeedup[3] = {1.54, 1.00, 1.47};
+static const double kPairSpeedup[3] = {1.58, 1.02, 1.51};
 
 // split-K cost: the reduction kernel's launch plus its traffic
 static double split_cost(int64_t M, int64_t N, int slices, double launch_us, double bytes_per_us) {
@@ -1011,13 +1011,12 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             const int64_t rounds = (tiles * slices + 255) / 256;
             double time = (double)rounds * (tc.tfix + per * tc.tk);
             if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
-            // the weights' one pass over the memory bus: faster with two workgroups per CU pulling,
-            // slower while the chip is not full
+            // the weights' one pass over the memory bus (slower while the chip is not full)
             const int64_t wgs = tiles * slices;
-            double mem_floor = w_bytes / (wgs < 512 ? 4.39e6 : 4.8e6);
+            double mem_floor = w_bytes / (wgs < 512 ? 4.57e6 : 4.44e6);
             if (wgs < 256) mem_floor *= std::sqrt(256.0 / (double)wgs);
             if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += split_cost(M, N, slices, 3.16, 4.42e6);
+            if (slices > 1) time += split_cost(M, N, slices, 3.18, 4.44e6);
             if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
             if (t.large_split > 0) break;
         }
