@@ -40,8 +40,9 @@ static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) 
     // the plain FP16 kernels: the same from 49 tokens on, and from 33 on where both N and K are large
     if (kind == kPlainF16 && tuning().small_max_m < 0 &&
         ((M > 48 && (N > 4096 || K > 4096)) || (M > 32 && N >= 8192 && K >= 8192))) return false;
-    // E4M3 weights: from 49 tokens on where the layer is large enough for the 64-token tiles to pay
-    if (kind == kE4M3 && M > 48 && (N >= 16384 || K >= 14336) && tuning().small_max_m < 0) return false;
+    // E4M3 weights: where the layer is large enough for the 64-token tiles to pay, from 33 tokens on
+    // on the widest layers, from 49 on those with a long K
+    if (kind == kE4M3 && tuning().small_max_m < 0 && ((M > 32 && N >= 16384) || (M > 48 && K >= 14336))) return false;
     return true;
 }
 
