@@ -27,7 +27,8 @@
  *     ldy must be a multiple of 4 and >= N when N % 4 == 0, else any ldy >= N is taken
  *     by a slower store path; W, X, planes, Xq and workspace pointers must be 16-byte
  *     aligned, Y 8-byte aligned.  M >= 1 and N >= 1 are otherwise arbitrary (no padding
- *     is asked of the caller).  M == 0 or N == 0 is a no-op that returns NESTEDFP_OK.
+ *     is asked of the caller).  M == 0 or N == 0 is a no-op that returns NESTEDFP_OK
+ *     (the GEMM entry points then look at no pointer: empty operands may be NULL).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream except where stated.
  *   - Argument errors are found before anything is launched and reported as a status

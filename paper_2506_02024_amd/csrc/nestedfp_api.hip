@@ -250,10 +250,11 @@ int nestedfp_gemm(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const ui
                   const uint8_t *lower, int64_t N, int mode, const float *act_scale, uint16_t *Y,
                   int64_t ldy, void *workspace, size_t workspace_bytes, void *stream) {
     if (mode != NESTEDFP_MODE_FP16 && mode != NESTEDFP_MODE_FP8) return NESTEDFP_ERR_ARG;
-    if (upper == nullptr) return NESTEDFP_ERR_ARG;
-    if (mode == NESTEDFP_MODE_FP16 && lower == nullptr) return NESTEDFP_ERR_ARG;
     int st = check_dims(M, N, K);
     if (st != kOk) return st;
+    if (M == 0 || N == 0) return NESTEDFP_OK;         // nothing to read or write: no pointer is looked at
+    if (upper == nullptr) return NESTEDFP_ERR_ARG;
+    if (mode == NESTEDFP_MODE_FP16 && lower == nullptr) return NESTEDFP_ERR_ARG;
     st = check_mat(X, M, K, ldx, 8);
     if (st != kOk) return st;
     st = check_out(Y, N, ldy);
@@ -285,6 +286,7 @@ int nestedfp_plain_gemm_fp16(const uint16_t *X, int64_t M, int64_t K, int64_t ld
                              size_t workspace_bytes, void *stream) {
     int st = check_dims(M, N, K);
     if (st != kOk) return st;
+    if (M == 0 || N == 0) return NESTEDFP_OK;
     st = check_mat(X, M, K, ldx, 8);
     if (st != kOk) return st;
     st = check_mat(W, N, K, ldw, 8);
@@ -305,9 +307,10 @@ int nestedfp_plain_gemm_fp16(const uint16_t *X, int64_t M, int64_t K, int64_t ld
 int nestedfp_plain_gemm_fp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const uint8_t *Wq,
                             int64_t N, float w_scale, const float *act_scale, uint16_t *Y, int64_t ldy,
                             void *workspace, size_t workspace_bytes, void *stream) {
-    if (Wq == nullptr) return NESTEDFP_ERR_ARG;
     int st = check_dims(M, N, K);
     if (st != kOk) return st;
+    if (M == 0 || N == 0) return NESTEDFP_OK;
+    if (Wq == nullptr) return NESTEDFP_ERR_ARG;
     st = check_mat(X, M, K, ldx, 8);
     if (st != kOk) return st;
     st = check_out(Y, N, ldy);
@@ -327,9 +330,10 @@ int nestedfp_plain_gemm_fp8(const uint16_t *X, int64_t M, int64_t K, int64_t ldx
 int nestedfp_gemm_fp8_prequantized(const uint8_t *Xq, const float *scales, int64_t M, int64_t K,
                                    const uint8_t *upper, int64_t N, float w_scale, uint16_t *Y,
                                    int64_t ldy, void *workspace, size_t workspace_bytes, void *stream) {
-    if (Xq == nullptr || scales == nullptr || upper == nullptr) return NESTEDFP_ERR_ARG;
     int st = check_dims(M, N, K);
     if (st != kOk) return st;
+    if (M == 0 || N == 0) return NESTEDFP_OK;
+    if (Xq == nullptr || scales == nullptr || upper == nullptr) return NESTEDFP_ERR_ARG;
     st = check_out(Y, N, ldy);
     if (st != kOk) return st;
     if (!aligned(Xq, 16) || !aligned(upper, 16) || !aligned(scales, 4)) return NESTEDFP_ERR_SHAPE;

@@ -78,6 +78,24 @@ def test_decode_odd_layer_shapes(nfp, N, K):
     run_both_modes(nfp, X, W, "N=%d K=%d" % (N, K))
 
 
+def test_empty_batch_and_empty_layer(nfp):
+    # M = 0 and N = 0 are legal and launch nothing: the output keeps what it held
+    K = 64
+    W = workloads.weight_host(32, K, seed=5)
+    up, lo = nfp.decompose(to_dev(W))
+    X0 = torch.empty((0, K), dtype=torch.float16, device="cuda:0")
+    for mode in (nfp.MODE_FP16, nfp.MODE_FP8):
+        y = nfp.gemm(X0, up, lo if mode == nfp.MODE_FP16 else None, mode)
+        assert tuple(y.shape) == (0, 32)
+    assert tuple(nfp.plain_gemm_fp16(X0, to_dev(W)).shape) == (0, 32)
+    assert nfp.gemm_workspace_size(0, 32, K, nfp.MODE_FP16) == 0 and nfp.gemm_workspace_size(0, 32, K, nfp.MODE_FP8) == 0
+    W0 = torch.empty((0, K), dtype=torch.float16, device="cuda:0")
+    up0, lo0 = nfp.decompose(W0)
+    X = to_dev(workloads.act_host(3, K, seed=6))
+    assert tuple(nfp.gemm(X, up0, lo0, nfp.MODE_FP16).shape) == (3, 0)
+    assert tuple(nfp.gemm(X, up0, None, nfp.MODE_FP8).shape) == (3, 0)
+
+
 @pytest.mark.parametrize("knobs", [
     {"small_split": 1, "small_tiles": 1},
     {"small_split": 1, "small_tiles": 2, "small_spw": 2},
