@@ -414,6 +414,13 @@ def test_llama70b_shapes_sampled(nfp, name, M):
     _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_70B, "70B %s M=%d" % (name, M), seed=70 + M)
 
 
+@pytest.mark.parametrize("M", [4, 130])
+def test_vocabulary_sized_layer_sampled(nfp, M):
+    # a Llama-3 output projection (128256 x 4096): half a billion weights, a row count that is no
+    # multiple of any tile, 8-tile groups of the XCD order plus a tail
+    _sampled_full_size_check(nfp, 128256, 4096, M, workloads.SIGMA_W_8B, "lm_head M=%d" % M, seed=128 + M)
+
+
 @pytest.mark.parametrize("N,K,M", [(28672, 5120, 96), (65536, 5120, 1024), (35840, 5120, 32)])
 def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, M):
     # the (N, K) shapes of Sec. 5.2 / Fig. 6, M inside its 32..2048 sweep
