@@ -414,6 +414,13 @@ def test_llama70b_shapes_sampled(nfp, name, M):
     _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_70B, "70B %s M=%d" % (name, M), seed=70 + M)
 
 
+@pytest.mark.parametrize("N,K,M", [(40, 32, 70000), (256, 65536, 8), (264, 65536 + 16, 70), (1000, 16, 1000), (4096, 4096, 20000)])
+def test_extreme_aspect_ratios_sampled(nfp, N, K, M):
+    # tens of thousands of tokens on a sliver of a layer, the longest rows, the shortest K, a prefill
+    # of 20000 tokens: sampled against the oracle
+    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_8B, "N=%d K=%d M=%d" % (N, K, M), seed=N % 97 + M % 89)
+
+
 @pytest.mark.parametrize("M", [4, 130])
 def test_vocabulary_sized_layer_sampled(nfp, M):
     # a Llama-3 output projection (128256 x 4096): half a billion weights, a row count that is no
