@@ -78,6 +78,44 @@ def test_decode_odd_layer_shapes(nfp, N, K):
     run_both_modes(nfp, X, W, "N=%d K=%d" % (N, K))
 
 
+@pytest.mark.parametrize("M", [16, 64, 300])
+def test_replayed_graph_on_a_side_stream_equals_eager_calls(nfp, M):
+    # both modes captured into one HIP graph on a non-default stream (streaming kernel with its
+    # split reduction, 64-token tiles, tiled kernels, activation quantisation): every replay, with
+    # eager work and new activations in between, must give what the eager calls give
+    N, K = 16384 + 72, 1024 + 64
+    W = workloads.weight_host(N, K, seed=M)
+    up, lo = nfp.decompose(to_dev(W))
+    X = to_dev(workloads.act_host(M, K, seed=M + 1))
+    Y16 = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    Y8 = torch.empty_like(Y16)
+    ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dtype=torch.uint8, device="cuda:0")
+
+    def both():
+        nfp.gemm(X, up, lo, nfp.MODE_FP16, out=Y16, workspace=ws)
+        nfp.gemm(X, up, None, nfp.MODE_FP8, out=Y8, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        both()                                         # warm-up outside the capture
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        both()
+    for rep in range(3):
+        X.copy_(to_dev(workloads.act_host(M, K, seed=100 * M + rep)))     # eager work between the replays
+        both()
+        torch.cuda.synchronize()
+        want16, want8 = Y16.clone(), Y8.clone()
+        Y16.zero_()
+        Y8.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y16, want16) and torch.equal(Y8, want8), "replay %d" % rep
+    assert_gemm_close(Y16.cpu().numpy(), oracle.gemm_fp16(X.cpu().numpy(), W), "graph replay, FP16 mode")
+
+
 def test_empty_batch_and_empty_layer(nfp):
     # M = 0 and N = 0 are legal and launch nothing: the output keeps what it held
     K = 64
