@@ -116,6 +116,29 @@ def test_replayed_graph_on_a_side_stream_equals_eager_calls(nfp, M):
     assert_gemm_close(Y16.cpu().numpy(), oracle.gemm_fp16(X.cpu().numpy(), W), "graph replay, FP16 mode")
 
 
+def test_calls_on_two_streams_do_not_interfere(nfp):
+    # the library holds no device state: two streams, each with its own workspace and output,
+    # run different problems at the same time and get what they get alone
+    probs = []
+    for j, (M, N, K) in enumerate([(16, 4096 + 8, 14336), (200, 2048 + 24, 1024)]):
+        W = workloads.weight_host(N, K, seed=60 + j)
+        up, lo = nfp.decompose(to_dev(W))
+        X = to_dev(workloads.act_host(M, K, seed=70 + j))
+        ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dtype=torch.uint8, device="cuda:0")
+        alone = (nfp.gemm(X, up, lo, nfp.MODE_FP16, workspace=ws).clone(), nfp.gemm(X, up, None, nfp.MODE_FP8, workspace=ws).clone())
+        outs = (torch.empty_like(alone[0]), torch.empty_like(alone[1]))
+        probs.append((X, up, lo, ws, alone, outs, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(8):
+        for X, up, lo, ws, alone, outs, st in probs:
+            with torch.cuda.stream(st):
+                nfp.gemm(X, up, lo, nfp.MODE_FP16, out=outs[0], workspace=ws)
+                nfp.gemm(X, up, None, nfp.MODE_FP8, out=outs[1], workspace=ws)
+    torch.cuda.synchronize()
+    for X, up, lo, ws, alone, outs, st in probs:
+        assert torch.equal(outs[0], alone[0]) and torch.equal(outs[1], alone[1])
+
+
 def test_empty_batch_and_empty_layer(nfp):
     # M = 0 and N = 0 are legal and launch nothing: the output keeps what it held
     K = 64
