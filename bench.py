@@ -10,12 +10,17 @@ steps.  The decomposition is offline in the paper (Sec. 4.1) and is timed separa
 
 Prints ONE JSON line: the whole-step algorithmic GB/s as `value`, the roofline of the
 dominant kernel (FP16-mode streaming GEMM), the CPU oracle timed on the host cores, and
-under `extra` the per-mode numbers, the plain same-family baselines and the
-compute-bound (prefill) TFLOP/s of the same linears.
+under `extra`: both plane layouts (row-major planes as the format defines them, and the
+library's optional packed pre-pack) next to plain FP16 / FP8 GEMMs of the same kernel
+family in both layouts, what the chip sustains for a pure read stream and a pure MFMA
+loop in the same run, the compute-bound (prefill) table, a subset of the Llama-3-70B
+sweep and the mode-alternation run.  Every comparison is timed interleaved, burst by
+burst, and reported as the median over the bursts with the spread beside it.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -34,13 +39,16 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tokens", type=int, default=16, help="decode batch M (tokens per step)")
     ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--layout", choices=("packed", "rowmajor"), default="packed",
+                    help="plane storage the timed step runs on (the other one is reported under extra)")
+    ap.add_argument("--bursts", type=int, default=7, help="repetitions per comparison (median is reported)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the compute-bound extras")
+    ap.add_argument("--no-70b", action="store_true", help="skip the Llama-3-70B subset (configs[3])")
+    ap.add_argument("--no-mode-switch", action="store_true", help="skip the mode-alternation run (configs[4])")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--sweep-70b", action="store_true",
-                    help="extra: roofline curve on the Llama-3-70B shapes, M = 1 ... 8192 (configs[3])")
-    ap.add_argument("--mode-switch", action="store_true",
-                    help="extra: per-step mode switching on the stack at M = 64 and 2048 (configs[4])")
+                    help="extra: full roofline curve on the Llama-3-70B shapes, M = 1 ... 8192 (configs[3])")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="extra: FP16-mode overhead over the plain FP16 GEMM on the shapes of the "
                          "paper's kernel benchmark, M = 32 ... 2048 step 32")
@@ -56,6 +64,46 @@ def gemm_bytes(M, N, K, mode):
     """Algorithmic bytes of one GEMM call: planes read + X read + Y written."""
     w = 2 * N * K if mode == "fp16" else N * K
     return w + 2 * M * K + 2 * M * N
+
+
+def bound_seconds(M, N, K, mode):
+    """max(algorithmic bytes / HBM peak, flops / MFMA peak of the mode)."""
+    return max(gemm_bytes(M, N, K, mode) / (HBM_PEAK_GBPS * 1e9), 2.0 * M * N * K / (MFMA_PEAK_TFLOPS[mode] * 1e12))
+
+
+def stats(ts):
+    """median / min / max of a list of seconds, in microseconds."""
+    return {"us": statistics.median(ts) * 1e6, "min_us": min(ts) * 1e6, "max_us": max(ts) * 1e6, "bursts": len(ts)}
+
+
+class Timer:
+    """Interleaved timing: for every burst, each named call runs `launches` times back to back
+    between two events; the kinds alternate burst by burst, so drift (clocks, temperature) hits
+    all of them alike.  Returns per kind the list of seconds per launch, one entry per burst."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def run(self, calls, launches, bursts, warm=1):
+        torch = self.torch
+        for _ in range(warm):
+            for fn in calls.values():
+                fn(0)
+        torch.cuda.synchronize()
+        out = {k: [] for k in calls}
+        pairs = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(bursts)]
+                 for k in calls}
+        for b in range(bursts):
+            for k, fn in calls.items():
+                a, e = pairs[k][b]
+                a.record()
+                for i in range(launches):
+                    fn(b * launches + i)
+                e.record()
+        torch.cuda.synchronize()
+        for k in calls:
+            out[k] = [a.elapsed_time(e) * 1e-3 / launches for a, e in pairs[k]]
+        return out
 
 
 def main():
@@ -77,78 +125,72 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     nfp.lib()                                   # fail loudly if the HIP library is missing
+    timer = Timer(torch)
 
     M = args.tokens
     shapes = workloads.LLAMA3_8B
     names = list(shapes)
 
     # ---- build the stack: decompose once (offline step, timed on its own) -------------
-    t_dec = 0.0
+    t_dec = {"rowmajor": 0.0, "packed": 0.0}
     dec_bytes = 0
-    planes, plain_w = [], []
+    stack = []                                  # per linear: name, W, row-major planes, packed planes, packed FP16
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for layer in range(args.layers):
         for j, name in enumerate(names):
             N, K = shapes[name]
             W = workloads.weight_device(N, K, workloads.SIGMA_W_8B, seed=layer * 4 + j)
-            up = nfp.PackedPlane(N, K, dev)
-            lo = nfp.PackedPlane(N, K, dev)
-            if layer == 0:
-                nfp.decompose(W, up, lo, check=True)      # warm + applicability check
-            e0.record()
-            nfp.decompose(W, up, lo, check=False)
-            e1.record()
-            torch.cuda.synchronize()
-            t_dec += e0.elapsed_time(e1) * 1e-3
+            ent = {"name": name, "W": W}
+            for key, packed in (("rowmajor", False), ("packed", True)):
+                up, lo = nfp.decompose(W, packed=packed, check=(layer == 0))     # warm + applicability check
+                e0.record()
+                nfp.decompose(W, up, lo, check=False)
+                e1.record()
+                torch.cuda.synchronize()
+                t_dec[key] += e0.elapsed_time(e1) * 1e-3
+                ent[key] = (up, lo)
+            ent["Wp"] = nfp.pack_fp16(W)
             dec_bytes += 4 * N * K
-            planes.append((name, up, lo))
-            plain_w.append(W)
-    # reconstruct timing on one layer
-    t_rec, rec_bytes = 0.0, 0
+            stack.append(ent)
+    # reconstruct timing on one layer, both layouts
+    t_rec = {"rowmajor": 0.0, "packed": 0.0}
+    rec_bytes = 0
     for j, name in enumerate(names):
         N, K = shapes[name]
-        _, up, lo = planes[j]
         out = torch.empty((N, K), dtype=torch.float16, device=dev)
-        nfp.reconstruct(up, lo, out)
-        e0.record()
-        nfp.reconstruct(up, lo, out)
-        e1.record()
-        torch.cuda.synchronize()
-        assert torch.equal(out, plain_w[j])
-        t_rec += e0.elapsed_time(e1) * 1e-3
+        for key in ("rowmajor", "packed"):
+            up, lo = stack[j][key]
+            nfp.reconstruct(up, lo, out)
+            e0.record()
+            nfp.reconstruct(up, lo, out)
+            e1.record()
+            torch.cuda.synchronize()
+            assert torch.equal(out, stack[j]["W"])
+            t_rec[key] += e0.elapsed_time(e1) * 1e-3
         rec_bytes += 4 * N * K
         del out
 
     X = {name: workloads.act_device(M, shapes[name][1], seed=7 + j) for j, name in enumerate(names)}
     Y = {name: torch.empty((M, shapes[name][0]), dtype=torch.float16, device=dev) for name in names}
     ws_bytes = max(nfp.gemm_workspace_size(M, N, K, m) for (N, K) in shapes.values() for m in (0, 1))
-    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
-    # the same call on ONE layer over and over: its planes (48 MB for qkv) stay in the 256 MB
-    # memory-side cache, so this is the hot-cache number, not an HBM rate
-    hot = {}
-    for j, name in enumerate(names[:4] if M <= 64 else []):
-        N, K = shapes[name]
-        _, up, lo = planes[j]
-        t_hot = _time(torch, lambda i: nfp.gemm(X[name], up, lo, nfp.MODE_FP16, out=Y[name], workspace=ws))
-        hot[name] = {"us": t_hot * 1e6, "GBps": gemm_bytes(M, N, K, "fp16") / t_hot / 1e9}
+    ws = nfp.new_workspace(ws_bytes + 256, dev)
 
-    def run_fp16():
-        for name, up, lo in planes:
-            nfp.gemm(X[name], up, lo, nfp.MODE_FP16, out=Y[name], workspace=ws)
+    def leg(kind, layout):
+        def run():
+            for ent in stack:
+                n = ent["name"]
+                if kind == "fp16":
+                    up, lo = ent[layout]
+                    nfp.gemm(X[n], up, lo, nfp.MODE_FP16, out=Y[n], workspace=ws)
+                elif kind == "fp8":
+                    nfp.gemm(X[n], ent[layout][0], None, nfp.MODE_FP8, out=Y[n], workspace=ws)
+                elif kind == "plain_fp16":
+                    nfp.plain_gemm_fp16(X[n], ent["Wp"] if layout == "packed" else ent["W"], out=Y[n], workspace=ws)
+                else:
+                    nfp.plain_gemm_fp8(X[n], ent[layout][0], 2.0 ** -8, out=Y[n], workspace=ws)
+        return run
 
-    def run_fp8():
-        for name, up, lo in planes:
-            nfp.gemm(X[name], up, None, nfp.MODE_FP8, out=Y[name], workspace=ws)
-
-    def run_plain16():
-        for (name, _, _), W in zip(planes, plain_w):
-            nfp.plain_gemm_fp16(X[name], W, out=Y[name], workspace=ws)
-
-    def run_plain8():
-        for name, up, lo in planes:
-            nfp.plain_gemm_fp8(X[name], up, 2.0 ** -8, out=Y[name], workspace=ws)
-
-    legs = {"fp16": run_fp16, "fp8": run_fp8, "plain_fp16": run_plain16, "plain_fp8": run_plain8}
+    legs = {"%s/%s" % (k, l): leg(k, l) for l in ("packed", "rowmajor") for k in ("fp16", "fp8", "plain_fp16", "plain_fp8")}
     for fn in legs.values():                    # eager warm-up (also sets kernel attributes)
         fn()
     torch.cuda.synchronize()
@@ -164,13 +206,14 @@ def main():
             replay[key] = g.replay
     torch.cuda.synchronize()
 
-    n_calls = len(planes)
-    step_bytes = {m: sum(gemm_bytes(M, *shapes[name], m) for name, _, _ in planes) for m in ("fp16", "fp8")}
-    step_flops = sum(2.0 * M * shapes[name][0] * shapes[name][1] for name, _, _ in planes)
+    n_calls = len(stack)
+    step_bytes = {m: sum(gemm_bytes(M, *shapes[e["name"]], m) for e in stack) for m in ("fp16", "fp8")}
+    step_flops = sum(2.0 * M * shapes[e["name"]][0] * shapes[e["name"]][1] for e in stack)
+    L = args.layout
 
     def step():
-        replay["fp16"]()
-        replay["fp8"]()
+        replay["fp16/" + L]()
+        replay["fp8/" + L]()
 
     for _ in range(args.warmup):
         step()
@@ -180,58 +223,73 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        replay["fp16"]()
+        replay["fp16/" + L]()
         ev[i][1].record()
-        replay["fp8"]()
+        replay["fp8/" + L]()
         ev[i][2].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    t_fp16 = sum(e[0].elapsed_time(e[1]) for e in ev) * 1e-3 / args.steps
-    t_fp8 = sum(e[1].elapsed_time(e[2]) for e in ev) * 1e-3 / args.steps
+    t_fp16 = statistics.median(e[0].elapsed_time(e[1]) for e in ev) * 1e-3
+    t_fp8 = statistics.median(e[1].elapsed_time(e[2]) for e in ev) * 1e-3
     ms_per_step = wall / args.steps * 1e3
     value = (step_bytes["fp16"] + step_bytes["fp8"]) / (wall / args.steps) / 1e9
 
-    # plain same-family baselines, same stack, same graphs
-    def time_leg(key, reps):
-        replay[key]()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            replay[key]()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e-3 / reps
+    # all eight legs (NestedFP and plain, both modes, both layouts), interleaved: one graph replay
+    # (128 launches) per kind and burst
+    burst = timer.run({k: (lambda i, r=r: r()) for k, r in replay.items()}, 1, args.bursts)
+    legs_out = {}
+    for key, ts in burst.items():
+        kind = key.split("/")[0]
+        nbytes = step_bytes["fp16" if "16" in kind else "fp8"]
+        st = stats(ts)
+        legs_out[key] = {"ms": st["us"] * 1e-3, "min_ms": st["min_us"] * 1e-3, "max_ms": st["max_us"] * 1e-3,
+                         "GBps": nbytes / (st["us"] * 1e-6) / 1e9, "frac_hbm": nbytes / (st["us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+    ratios = {}
+    for l in ("packed", "rowmajor"):
+        ratios["fp16_vs_plain_fp16/" + l] = legs_out["plain_fp16/" + l]["ms"] / legs_out["fp16/" + l]["ms"]
+        ratios["fp8_vs_plain_fp8/" + l] = legs_out["plain_fp8/" + l]["ms"] / legs_out["fp8/" + l]["ms"]
 
-    reps = max(3, args.steps // 3)
-    t_plain16 = time_leg("plain_fp16", reps)
-    t_plain8 = time_leg("plain_fp8", reps)
+    # the same call on ONE layer over and over: its planes (48 MB for qkv) stay in the 256 MB
+    # memory-side cache, so this is the hot-cache number, not an HBM rate
+    hot = {}
+    if M <= 64:
+        calls = {}
+        for j, name in enumerate(names):
+            up, lo = stack[j][L]
+            calls[name] = (lambda i, name=name, up=up, lo=lo: nfp.gemm(X[name], up, lo, nfp.MODE_FP16, out=Y[name], workspace=ws))
+        for name, ts in timer.run(calls, 50, 5).items():
+            N, K = shapes[name]
+            st = stats(ts)
+            hot[name] = {"us": st["us"], "GBps": gemm_bytes(M, N, K, "fp16") / (st["us"] * 1e-6) / 1e9}
+
+    achievable = achievable_rates(torch, nfp, workloads, stack, timer, dev)
 
     extra = {
         "tokens": M,
         "gemm_calls_per_mode": n_calls,
+        "timed_layout": L,
         "fp16_mode": {"ms": t_fp16 * 1e3, "GBps": step_bytes["fp16"] / t_fp16 / 1e9,
                       "TFLOPs": step_flops / t_fp16 / 1e12,
                       "frac_hbm": step_bytes["fp16"] / t_fp16 / 1e9 / HBM_PEAK_GBPS,
-                      "vs_plain_fp16": t_plain16 / t_fp16},
+                      "frac_of_stream_read": step_bytes["fp16"] / t_fp16 / 1e9 / achievable["hbm_GBps"]},
         "fp8_mode": {"ms": t_fp8 * 1e3, "GBps": step_bytes["fp8"] / t_fp8 / 1e9,
                      "TFLOPs": step_flops / t_fp8 / 1e12,
                      "frac_hbm": step_bytes["fp8"] / t_fp8 / 1e9 / HBM_PEAK_GBPS,
-                     "vs_plain_fp8": t_plain8 / t_fp8},
-        "plain_fp16": {"ms": t_plain16 * 1e3, "GBps": step_bytes["fp16"] / t_plain16 / 1e9},
-        "plain_fp8": {"ms": t_plain8 * 1e3, "GBps": step_bytes["fp8"] / t_plain8 / 1e9},
-        "decompose_offline": {"GBps": dec_bytes / t_dec / 1e9, "ms_total": t_dec * 1e3,
-                              "frac_hbm": dec_bytes / t_dec / 1e9 / HBM_PEAK_GBPS},
-        "reconstruct": {"GBps": rec_bytes / t_rec / 1e9, "frac_hbm": rec_bytes / t_rec / 1e9 / HBM_PEAK_GBPS},
+                     "frac_of_stream_read": step_bytes["fp8"] / t_fp8 / 1e9 / achievable["hbm_GBps"]},
+        "legs_interleaved": legs_out,
+        "ratios": ratios,
+        "achievable": achievable,
+        "decompose_offline": {k: {"GBps": dec_bytes / t_dec[k] / 1e9, "ms_total": t_dec[k] * 1e3,
+                                  "frac_hbm": dec_bytes / t_dec[k] / 1e9 / HBM_PEAK_GBPS} for k in t_dec},
+        "reconstruct": {k: {"GBps": rec_bytes / t_rec[k] / 1e9, "frac_hbm": rec_bytes / t_rec[k] / 1e9 / HBM_PEAK_GBPS}
+                        for k in t_rec},
         "fp16_mode_hot_cache_one_layer": hot,
-        "mode_switch": "mode is a per-call argument on the same plane pointers; "
-                       "torch.cuda.memory_allocated is constant across the timed region",
     }
 
     # roofline of the dominant kernel: the FP16-mode streaming GEMM (one launch per linear)
     traffic = read_traffic()
     roofline = {
-        "kernel": "small_gemm_kernel<kNestedF16> (FP16-mode streaming GEMM, %d launches/step)" % n_calls,
+        "kernel": "small_gemm_kernel, NestedFP16 over %s planes (FP16-mode streaming GEMM, %d launches/step)" % (L, n_calls),
         "bound": "hbm",
         "achieved": step_bytes["fp16"] / t_fp16 / 1e9,
         "peak": HBM_PEAK_GBPS,
@@ -240,6 +298,7 @@ def main():
         "traffic": traffic,
         "avg_launch_us": t_fp16 / n_calls * 1e6,
         "algorithmic_bytes_per_launch": step_bytes["fp16"] / n_calls,
+        "frac_of_stream_read_same_run": step_bytes["fp16"] / t_fp16 / 1e9 / achievable["hbm_GBps"],
     }
 
     if args.calibrate_copy:
@@ -249,20 +308,24 @@ def main():
             torch.add(src, 0.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    del replay, legs
     if not args.no_prefill:
-        del replay, legs
-        extra["prefill"] = prefill_extras(torch, nfp, workloads, planes, plain_w, dev)
-    if args.mode_switch:
-        extra["mode_switch_steps"] = mode_switch_extras(torch, nfp, workloads, planes, dev)
+        extra["prefill"] = prefill_extras(torch, nfp, workloads, stack, timer, dev, args.bursts)
+    if not args.no_mode_switch:
+        extra["mode_switch_steps"] = mode_switch_extras(torch, nfp, workloads, stack, L, dev)
     if args.switch_demo:
-        extra["switch_demo"] = switch_demo_extras(torch, nfp, workloads, planes, dev)
-    del plain_w, planes
+        extra["switch_demo"] = switch_demo_extras(torch, nfp, workloads, stack, L, dev)
+    del stack
     torch.cuda.empty_cache()
+    if not args.no_70b and not args.sweep_70b:
+        sub = [(n, workloads.LLAMA3_70B[n]) for n in ("qkv", "gate_up")]
+        extra["llama70b_subset"] = sweep_extras(torch, nfp, workloads, timer, dev, sub, workloads.SIGMA_W_70B,
+                                                [1, 16, 64, 512, 8192], args.bursts)
     if args.sweep_70b:
-        extra["sweep_70b"] = sweep_extras(torch, nfp, workloads, dev, workloads.LLAMA3_70B.items(),
-                                          workloads.SIGMA_W_70B, [1 << i for i in range(14)])
+        extra["sweep_70b"] = sweep_extras(torch, nfp, workloads, timer, dev, list(workloads.LLAMA3_70B.items()),
+                                          workloads.SIGMA_W_70B, [1 << i for i in range(14)], 5)
     if args.paper_shapes:
-        extra["paper_shapes"] = paper_shape_extras(torch, nfp, workloads, dev)
+        extra["paper_shapes"] = paper_shape_extras(torch, nfp, workloads, timer, dev)
 
     cpu = None if args.no_cpu else cpu_baseline(workloads, M)
 
@@ -281,8 +344,8 @@ def main():
         "dtype": "f16/e4m3 operands, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-3-8B-shaped linears qkv/o/gate_up/down x %d layers, "
-                               "decode M=%d, FP16 mode then FP8 mode per step" % (args.layers, M),
-                   "tokens": M, "layers": args.layers, "hip_graph": not args.no_graph},
+                               "decode M=%d, FP16 mode then FP8 mode per step, %s planes" % (args.layers, M, L),
+                   "tokens": M, "layers": args.layers, "hip_graph": not args.no_graph, "plane_layout": L},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "extra": extra,
@@ -303,144 +366,181 @@ def read_traffic():
     return None
 
 
-def prefill_extras(torch, nfp, workloads, planes, plain_w, dev):
-    """Compute-bound regime (configs[2]): the same four linears at M in {512, 2048, 8192}."""
+def achievable_rates(torch, nfp, workloads, stack, timer, dev):
+    """What this chip sustains, in this run, for the two resources the GEMMs are bound by: a pure
+    read stream (1 GiB buffers rotated so that no cache serves them) and a loop of nothing but
+    MFMAs on operands with the workload's bit patterns (weights of the stack / their upper plane
+    against Gaussian activations / their E4M3 codes)."""
+    bufs = [torch.empty(1 << 30, dtype=torch.uint8, device=dev) for _ in range(4)]
+    for i, b in enumerate(bufs):
+        b.view(torch.int32).random_(0, 1 << 30)
+    ts = timer.run({"read": lambda i: nfp.probe_stream_read(bufs[i % 4])}, 8, 5)["read"]
+    hbm = (1 << 30) / statistics.median(ts) / 1e9
+    del bufs
+    # operand blocks: 8 x 8 KB = weights, activations, weights, ... (see nestedfp_probe_mfma)
+    w16 = stack[0]["W"].reshape(-1)[:16384].view(torch.uint8)
+    x16 = workloads.act_device(4, 4096, seed=3).reshape(-1)[:16384].view(torch.uint8)
+    ops16 = torch.cat([w16[i * 8192:(i + 1) * 8192] if s == 0 else x16[i * 8192:(i + 1) * 8192]
+                       for i in range(4) for s in (0, 1)]).contiguous()
+    up = stack[0]["rowmajor"][0].reshape(-1)[:32768]
+    xq, _ = nfp.quantize_act(workloads.act_device(8, 4096, seed=4))
+    xq = xq.reshape(-1)[:32768]
+    ops8 = torch.cat([up[i * 8192:(i + 1) * 8192] if s == 0 else xq[i * 8192:(i + 1) * 8192]
+                      for i in range(4) for s in (0, 1)]).contiguous()
+    out = {"hbm_GBps": hbm, "hbm_frac_of_peak": hbm / HBM_PEAK_GBPS,
+           "hbm_probe": "read-only kernel, 8 x 128-bit loads per lane, 1 GiB per launch, 4 buffers rotated"}
+    for key, ops, fp8 in (("fp16", ops16, 0), ("fp8", ops8, 1)):
+        iters = 4000
+        flops = [0.0]
+
+        def call(i, ops=ops, fp8=fp8):
+            flops[0] = nfp.probe_mfma(ops, fp8, iters)
+        ts = timer.run({"m": call}, 4, 5)["m"]
+        tf = flops[0] / statistics.median(ts) / 1e12
+        out["mfma_%s_TFLOPs" % key] = tf
+        out["mfma_%s_frac_of_peak" % key] = tf / MFMA_PEAK_TFLOPS[key]
+    out["mfma_probe"] = "nothing but MFMAs (16x16x32 f16 / 16x16x128 f8f6f4), 16 waves per CU, operands with the workload's bit patterns"
+    return out
+
+
+def prefill_extras(torch, nfp, workloads, stack, timer, dev, bursts):
+    """Compute-bound regime (configs[2]): the same four linears at M in {512, 2048, 8192}; both
+    modes, both plane layouts and the plain baselines, interleaved; layers rotated so that the
+    weights are cold."""
     shapes = workloads.LLAMA3_8B
     out = {}
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_layers = len(planes) // 4
+    n_layers = len(stack) // 4
     for M in workloads.PREFILL_M:
         row = {}
         for j, name in enumerate(shapes):
             N, K = shapes[name]
             X = workloads.act_device(M, K, seed=70 + j)
             Yb = torch.empty((M, N), dtype=torch.float16, device=dev)
-            ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256,
-                             dtype=torch.uint8, device=dev)
+            ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dev)
             flops = 2.0 * M * N * K
+
+            def ent(i):
+                return stack[(i % n_layers) * 4 + j]
+            calls = {
+                "fp16/packed": lambda i: nfp.gemm(X, *ent(i)["packed"], nfp.MODE_FP16, out=Yb, workspace=ws),
+                "plain_fp16/packed": lambda i: nfp.plain_gemm_fp16(X, ent(i)["Wp"], out=Yb, workspace=ws),
+                "fp16/rowmajor": lambda i: nfp.gemm(X, *ent(i)["rowmajor"], nfp.MODE_FP16, out=Yb, workspace=ws),
+                "plain_fp16/rowmajor": lambda i: nfp.plain_gemm_fp16(X, ent(i)["W"], out=Yb, workspace=ws),
+                "fp8/packed": lambda i: nfp.gemm(X, ent(i)["packed"][0], None, nfp.MODE_FP8, out=Yb, workspace=ws),
+                "plain_fp8/packed": lambda i: nfp.plain_gemm_fp8(X, ent(i)["packed"][0], 2.0 ** -8, out=Yb, workspace=ws),
+                "fp8/rowmajor": lambda i: nfp.gemm(X, ent(i)["rowmajor"][0], None, nfp.MODE_FP8, out=Yb, workspace=ws),
+                "plain_fp8/rowmajor": lambda i: nfp.plain_gemm_fp8(X, ent(i)["rowmajor"][0], 2.0 ** -8, out=Yb, workspace=ws),
+            }
+            launches = 50 if M <= 2048 else 20
             res = {}
-            for key in ("fp16", "plain_fp16", "fp8", "plain_fp8"):
-                reps = 8 if M >= 2048 else 16
-
-                def call(i):
-                    _, up, lo = planes[(i % n_layers) * 4 + j]     # rotate layers: cold weights
-                    if key == "fp16":
-                        nfp.gemm(X, up, lo, nfp.MODE_FP16, out=Yb, workspace=ws)
-                    elif key == "plain_fp16":
-                        nfp.plain_gemm_fp16(X, plain_w[(i % n_layers) * 4 + j], out=Yb, workspace=ws)
-                    elif key == "fp8":
-                        nfp.gemm(X, up, None, nfp.MODE_FP8, out=Yb, workspace=ws)
-                    else:
-                        nfp.plain_gemm_fp8(X, up, 2.0 ** -8, out=Yb, workspace=ws)
-
-                call(0)
-                call(1)
-                torch.cuda.synchronize()
-                a.record()
-                for i in range(reps):
-                    call(i)
-                b.record()
-                torch.cuda.synchronize()
-                t = a.elapsed_time(b) * 1e-3 / reps
-                peak = MFMA_PEAK_TFLOPS["fp16" if "16" in key else "fp8"]
-                res[key] = {"us": t * 1e6, "TFLOPs": flops / t / 1e12, "frac_mfma": flops / t / 1e12 / peak}
-            res["fp16_vs_plain"] = res["plain_fp16"]["us"] / res["fp16"]["us"]
-            res["fp8_vs_plain"] = res["plain_fp8"]["us"] / res["fp8"]["us"]
+            for key, ts in timer.run(calls, launches, bursts).items():
+                st = stats(ts)
+                mode = "fp16" if "16" in key else "fp8"
+                t = st["us"] * 1e-6
+                st.update({"TFLOPs": flops / t / 1e12, "frac_mfma": flops / t / 1e12 / MFMA_PEAK_TFLOPS[mode],
+                           "frac_of_bound": bound_seconds(M, N, K, mode) / t})
+                res[key] = st
+            for l in ("packed", "rowmajor"):
+                res["fp16_vs_plain/" + l] = res["plain_fp16/" + l]["us"] / res["fp16/" + l]["us"]
+                res["fp8_vs_plain/" + l] = res["plain_fp8/" + l]["us"] / res["fp8/" + l]["us"]
             row[name] = res
             del X, Yb, ws
         out["M=%d" % M] = row
     return out
 
 
-def _time(torch, call, budget_s=0.03, max_reps=64):
-    """Seconds per call: two warm-up calls, then enough back-to-back calls for ~budget_s."""
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    call(0)
-    torch.cuda.synchronize()
-    a.record()
-    call(1)
-    b.record()
-    torch.cuda.synchronize()
-    one = max(a.elapsed_time(b) * 1e-3, 1e-6)
-    reps = int(min(max_reps, max(3, budget_s / one)))
-    a.record()
-    for i in range(reps):
-        call(2 + i)
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) * 1e-3 / reps
-
-
 def _layer_copies(torch, nfp, workloads, N, K, sigma, dev, seed0):
     """Enough copies of one layer that neither L2 nor the 256 MB cache can serve the weights."""
     copies = int(min(8, max(2, -(-600e6 // (2 * N * K)))))
     Ws = [workloads.weight_device(N, K, sigma, seed=seed0 + i) for i in range(copies)]
-    return Ws, [nfp.decompose(W, check=(i == 0)) for i, W in enumerate(Ws)]
+    return Ws, [nfp.decompose(W, check=(i == 0), packed=True) for i, W in enumerate(Ws)], \
+        [nfp.decompose(W, check=False) for W in Ws]
 
 
-def sweep_extras(torch, nfp, workloads, dev, shapes, sigma, Ms):
-    """Roofline curve: both modes and the plain FP16 baseline over M on each shape; the bound of
-    a point is max(algorithmic bytes / 8 TB/s, flops / MFMA peak of the mode)."""
+def sweep_extras(torch, nfp, workloads, timer, dev, shapes, sigma, Ms, bursts):
+    """Roofline curve (configs[3]): both modes over packed and row-major planes and the plain FP16
+    baselines over M on each shape; the bound of a point is max(algorithmic bytes / 8 TB/s, flops /
+    MFMA peak of the mode)."""
     out = {}
     for j, (name, (N, K)) in enumerate(shapes):
-        Ws, planes = _layer_copies(torch, nfp, workloads, N, K, sigma, dev, 300 + 10 * j)
+        Ws, packed, rowmajor = _layer_copies(torch, nfp, workloads, N, K, sigma, dev, 300 + 10 * j)
+        Wps = [nfp.pack_fp16(W) for W in Ws]
         R = len(Ws)
         row = {}
         for M in Ms:
             X = workloads.act_device(M, K, seed=90 + j)
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
-            ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256,
-                             dtype=torch.uint8, device=dev)
-            t16 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], planes[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws))
-            t8 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], None, nfp.MODE_FP8, out=Y, workspace=ws))
-            tp = _time(torch, lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws))
+            ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dev)
+            calls = {
+                "fp16/packed": lambda i: nfp.gemm(X, packed[i % R][0], packed[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws),
+                "plain_fp16/packed": lambda i: nfp.plain_gemm_fp16(X, Wps[i % R], out=Y, workspace=ws),
+                "fp16/rowmajor": lambda i: nfp.gemm(X, rowmajor[i % R][0], rowmajor[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws),
+                "plain_fp16/rowmajor": lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws),
+                "fp8/packed": lambda i: nfp.gemm(X, packed[i % R][0], None, nfp.MODE_FP8, out=Y, workspace=ws),
+                "fp8/rowmajor": lambda i: nfp.gemm(X, rowmajor[i % R][0], None, nfp.MODE_FP8, out=Y, workspace=ws),
+            }
+            t_guess = max(bound_seconds(M, N, K, "fp16") * 2.5, 20e-6)
+            launches = int(min(50, max(5, 0.05 / t_guess)))
+            res = {}
             fl = 2.0 * M * N * K
-            lb16 = max(gemm_bytes(M, N, K, "fp16") / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_PEAK_TFLOPS["fp16"] * 1e12))
-            lb8 = max(gemm_bytes(M, N, K, "fp8") / (HBM_PEAK_GBPS * 1e9), fl / (MFMA_PEAK_TFLOPS["fp8"] * 1e12))
-            row["M=%d" % M] = {
-                "fp16_us": t16 * 1e6, "fp8_us": t8 * 1e6, "plain_fp16_us": tp * 1e6,
-                "fp16_GBps": gemm_bytes(M, N, K, "fp16") / t16 / 1e9, "fp8_GBps": gemm_bytes(M, N, K, "fp8") / t8 / 1e9,
-                "fp16_TFLOPs": fl / t16 / 1e12, "fp8_TFLOPs": fl / t8 / 1e12,
-                "fp16_frac_roofline": lb16 / t16, "fp8_frac_roofline": lb8 / t8,
-                "fp16_vs_plain": tp / t16}
+            for key, ts in timer.run(calls, launches, bursts).items():
+                st = stats(ts)
+                mode = "fp16" if "16" in key else "fp8"
+                t = st["us"] * 1e-6
+                st.update({"GBps": gemm_bytes(M, N, K, mode) / t / 1e9, "TFLOPs": fl / t / 1e12,
+                           "frac_roofline": bound_seconds(M, N, K, mode) / t})
+                res[key] = st
+            res["fp16_vs_plain/packed"] = res["plain_fp16/packed"]["us"] / res["fp16/packed"]["us"]
+            res["fp16_vs_plain/rowmajor"] = res["plain_fp16/rowmajor"]["us"] / res["fp16/rowmajor"]["us"]
+            row["M=%d" % M] = res
             del X, Y, ws
         out["%s (%d,%d)" % (name, N, K)] = row
-        del Ws, planes
+        del Ws, packed, rowmajor, Wps
         torch.cuda.empty_cache()
     return out
 
 
-def paper_shape_extras(torch, nfp, workloads, dev):
+def paper_shape_extras(torch, nfp, workloads, timer, dev):
     """Sec. 5.2 / App. C of the paper sweep M = 32 ... 2048 in steps of 32 on four (N,K) shapes
-    and quote the mean slowdown of FP16 mode against a plain FP16 GEMM; same sweep here."""
+    and quote the mean slowdown of FP16 mode against a plain FP16 GEMM; same sweep here, against
+    the plain GEMM on packed FP16 weights (same kernel minus the reconstruction) and on row-major ones."""
     out = {}
     for j, (N, K) in enumerate(workloads.PAPER_KERNEL_SHAPES):
-        Ws, planes = _layer_copies(torch, nfp, workloads, N, K, workloads.SIGMA_W_8B, dev, 500 + 10 * j)
+        Ws, packed, rowmajor = _layer_copies(torch, nfp, workloads, N, K, workloads.SIGMA_W_8B, dev, 500 + 10 * j)
+        Wps = [nfp.pack_fp16(W) for W in Ws]
         R = len(Ws)
         over = []
         for M in range(32, 2049, 32):
             X = workloads.act_device(M, K, seed=95 + j)
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
-            ws = torch.empty(nfp.gemm_workspace_size(M, N, K, 0) + 256, dtype=torch.uint8, device=dev)
-            t16 = _time(torch, lambda i: nfp.gemm(X, planes[i % R][0], planes[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws), 0.01, 16)
-            tp = _time(torch, lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws), 0.01, 16)
-            over.append((M, t16 / tp - 1.0, 2.0 * M * N * K / t16 / 1e12))
+            ws = nfp.new_workspace(nfp.gemm_workspace_size(M, N, K, 0) + 256, dev)
+            calls = {
+                "fp16": lambda i: nfp.gemm(X, packed[i % R][0], packed[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws),
+                "plain_packed": lambda i: nfp.plain_gemm_fp16(X, Wps[i % R], out=Y, workspace=ws),
+                "fp16_rowmajor": lambda i: nfp.gemm(X, rowmajor[i % R][0], rowmajor[i % R][1], nfp.MODE_FP16, out=Y, workspace=ws),
+                "plain_rowmajor": lambda i: nfp.plain_gemm_fp16(X, Ws[i % R], out=Y, workspace=ws),
+            }
+            r = {k: statistics.median(v) for k, v in timer.run(calls, 8, 3).items()}
+            over.append((M, r["fp16"] / r["plain_packed"] - 1.0, r["fp16_rowmajor"] / r["plain_rowmajor"] - 1.0,
+                         2.0 * M * N * K / r["fp16"] / 1e12))
             del X, Y, ws
         o = [x[1] for x in over]
-        big = [x[1] for x in over if x[0] > 64]
+        o2 = [x[2] for x in over]
         out["(%d,%d)" % (N, K)] = {
-            "mean_overhead": sum(o) / len(o), "min_overhead": min(o), "max_overhead": max(o),
-            "mean_overhead_tiled_kernel_M>64": sum(big) / len(big),
-            "fp16_TFLOPs_at_M=2048": over[-1][2],
-            "overhead_at": {"M=%d" % m: ov for m, ov, _ in over if m in (32, 64, 128, 256, 512, 1024, 2048)}}
-        del Ws, planes
+            "mean_overhead_vs_plain_packed": sum(o) / len(o), "min": min(o), "max": max(o),
+            "mean_overhead_rowmajor_vs_plain_rowmajor": sum(o2) / len(o2),
+            "fp16_TFLOPs_at_M=2048": over[-1][3],
+            "overhead_at": {"M=%d" % m: ov for m, ov, _, _ in over if m in (32, 64, 128, 256, 512, 1024, 2048)}}
+        del Ws, packed, rowmajor, Wps
         torch.cuda.empty_cache()
     return out
 
 
-def _run_stack(nfp, planes, X, Y, ws, mode):
-    for name, up, lo in planes:
-        nfp.gemm(X[name], up, None if mode == nfp.MODE_FP8 else lo, mode, out=Y[name], workspace=ws)
+def _run_stack(nfp, stack, layout, X, Y, ws, mode):
+    for ent in stack:
+        up, lo = ent[layout]
+        n = ent["name"]
+        nfp.gemm(X[n], up, None if mode == nfp.MODE_FP8 else lo, mode, out=Y[n], workspace=ws)
 
 
 def _stack_buffers(torch, nfp, workloads, M, dev):
@@ -448,18 +548,18 @@ def _stack_buffers(torch, nfp, workloads, M, dev):
     X = {n: workloads.act_device(M, shapes[n][1], seed=60 + j) for j, n in enumerate(shapes)}
     Y = {n: torch.empty((M, shapes[n][0]), dtype=torch.float16, device=dev) for n in shapes}
     need = max(nfp.gemm_workspace_size(M, N, K, m) for (N, K) in shapes.values() for m in (0, 1))
-    return X, Y, torch.empty(need + 256, dtype=torch.uint8, device=dev)
+    return X, Y, nfp.new_workspace(need + 256, dev)
 
 
-def mode_switch_extras(torch, nfp, workloads, planes, dev):
-    """Sec. 5.4: the mode is chosen per iteration.  64 steps over the whole stack, the mode
-    flipping every 8 steps, at M = 64 and M = 2048: step time by mode, the first step after a
+def mode_switch_extras(torch, nfp, workloads, stack, layout, dev):
+    """Sec. 5.4: the mode is chosen per iteration (configs[4]).  64 steps over the whole stack, the
+    mode flipping every 8 steps, at M = 64 and M = 2048: step time by mode, the first step after a
     flip against the steady state, allocated device memory before and after."""
-    out = {}
+    out = {"plane_layout": layout}
     for M in (64, 2048):
         X, Y, ws = _stack_buffers(torch, nfp, workloads, M, dev)
         for mode in (nfp.MODE_FP16, nfp.MODE_FP8):
-            _run_stack(nfp, planes, X, Y, ws, mode)
+            _run_stack(nfp, stack, layout, X, Y, ws, mode)
         torch.cuda.synchronize()
         before = torch.cuda.memory_allocated()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(65)]
@@ -468,24 +568,25 @@ def mode_switch_extras(torch, nfp, workloads, planes, dev):
         for step in range(64):
             mode = nfp.MODE_FP8 if (step // 8) % 2 else nfp.MODE_FP16
             modes.append(mode)
-            _run_stack(nfp, planes, X, Y, ws, mode)
+            _run_stack(nfp, stack, layout, X, Y, ws, mode)
             ev[step + 1].record()
         torch.cuda.synchronize()
         t = [ev[i].elapsed_time(ev[i + 1]) for i in range(64)]
-        first = [t[i] for i in range(8, 64) if i % 8 == 0]
+        first = {m: [t[i] for i in range(8, 64) if i % 8 == 0 and modes[i] == m] for m in (nfp.MODE_FP16, nfp.MODE_FP8)}
         steady = {m: [t[i] for i in range(64) if modes[i] == m and i % 8 != 0] for m in (nfp.MODE_FP16, nfp.MODE_FP8)}
         out["M=%d" % M] = {
-            "fp16_step_ms": sum(steady[nfp.MODE_FP16]) / len(steady[nfp.MODE_FP16]),
-            "fp8_step_ms": sum(steady[nfp.MODE_FP8]) / len(steady[nfp.MODE_FP8]),
-            "first_step_after_switch_ms": first,
+            "fp16_step_ms": statistics.median(steady[nfp.MODE_FP16]),
+            "fp8_step_ms": statistics.median(steady[nfp.MODE_FP8]),
+            "first_fp16_step_after_switch_ms": statistics.median(first[nfp.MODE_FP16]),
+            "first_fp8_step_after_switch_ms": statistics.median(first[nfp.MODE_FP8]),
             "allocated_bytes_before": before, "allocated_bytes_after": torch.cuda.memory_allocated()}
         del X, Y, ws
     return out
 
 
-def switch_demo_extras(torch, nfp, workloads, planes, dev):
+def switch_demo_extras(torch, nfp, workloads, stack, layout, dev):
     """Sec. 5.4's policy on a synthetic arrival sequence (the paper's trace is not available):
-    a step whose token count reaches 1024 runs in FP8 mode, the others in FP16 mode."""
+    a step whose token count exceeds 1024 runs in FP8 mode, the others in FP16 mode."""
     import numpy as np
 
     rng = np.random.default_rng(7)
@@ -500,14 +601,14 @@ def switch_demo_extras(torch, nfp, workloads, planes, dev):
                 return nfp.MODE_FP16
             if policy == "always_fp8":
                 return nfp.MODE_FP8
-            return nfp.MODE_FP8 if M >= 1024 else nfp.MODE_FP16
+            return nfp.select_mode(M, 1024)
         for M in bufs:                                   # warm every kernel once
-            _run_stack(nfp, planes, *bufs[M], mode_of(M))
+            _run_stack(nfp, stack, layout, *bufs[M], mode_of(M))
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for M in seq:
-            _run_stack(nfp, planes, *bufs[M], mode_of(M))
+            _run_stack(nfp, stack, layout, *bufs[M], mode_of(M))
         b.record()
         torch.cuda.synchronize()
         res[policy] = {"total_ms": a.elapsed_time(b), "fp8_steps": sum(1 for M in seq if mode_of(M) == nfp.MODE_FP8)}
@@ -530,7 +631,15 @@ def cpu_baseline(workloads, M):
         W = workloads.weight_host(N, K, workloads.SIGMA_W_8B, seed=j)
         Xh = workloads.act_host(M, K, seed=7 + j)
         inputs.append((W, Xh))
-    ups = [oracle.decompose(W)[0] for W, _ in inputs]   # offline step, not timed
+    # the upper planes for the FP8 leg: the offline step, not timed (row blocks on a few threads:
+    # ctypes releases the interpreter lock during the oracle call)
+    from concurrent.futures import ThreadPoolExecutor
+
+    def upper_of(W):
+        blocks = [W[i:i + 256] for i in range(0, W.shape[0], 256)]
+        with ThreadPoolExecutor(max_workers=min(16, cores)) as pool:
+            return np.concatenate(list(pool.map(lambda b: oracle.decompose(b)[0], blocks)))
+    ups = [upper_of(W) for W, _ in inputs]
     t_fp16 = t_fp8 = 0.0
     passes = 0
     while passes < 16 and t_fp16 + t_fp8 < 10.0:        # about 10-20 s of CPU work

@@ -13,6 +13,9 @@ from . import build as _build
 
 MODE_FP16 = 0
 MODE_FP8 = 1
+LAYOUT_ROWMAJOR = 0
+LAYOUT_PACKED = 1
+WORKSPACE_COUNTER_BYTES = 16384
 
 OK, ERR_ARG, ERR_SHAPE, ERR_RANGE, ERR_WORKSPACE, ERR_HIP = range(6)
 
@@ -44,10 +47,18 @@ def lib():
     L.nestedfp_status_string.argtypes = [ci]
     L.nestedfp_range_check.restype = ci
     L.nestedfp_range_check.argtypes = [vp, i64, i64, i64, vp, vp, vp]
-    L.nestedfp_decompose.restype = ci
-    L.nestedfp_decompose.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
-    L.nestedfp_reconstruct.restype = ci
-    L.nestedfp_reconstruct.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    for name in ("nestedfp_decompose", "nestedfp_decompose_packed"):
+        getattr(L, name).restype = ci
+        getattr(L, name).argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    for name in ("nestedfp_reconstruct", "nestedfp_reconstruct_packed"):
+        getattr(L, name).restype = ci
+        getattr(L, name).argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    L.nestedfp_packed_fp16_bytes.restype = sz
+    L.nestedfp_packed_fp16_bytes.argtypes = [i64, i64]
+    L.nestedfp_pack_fp16.restype = ci
+    L.nestedfp_pack_fp16.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.nestedfp_workspace_init.restype = ci
+    L.nestedfp_workspace_init.argtypes = [vp, sz, vp]
     L.nestedfp_plane_bytes.restype = sz
     L.nestedfp_plane_bytes.argtypes = [i64, i64]
     L.nestedfp_pack_plane.restype = ci
@@ -58,16 +69,26 @@ def lib():
     L.nestedfp_quantize_act.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     L.nestedfp_gemm_workspace_size.restype = sz
     L.nestedfp_gemm_workspace_size.argtypes = [i64, i64, i64, ci]
-    L.nestedfp_gemm.restype = ci
-    L.nestedfp_gemm.argtypes = [vp, i64, i64, i64, vp, vp, i64, ci, vp, vp, i64, vp, sz, vp]
+    for name in ("nestedfp_gemm", "nestedfp_gemm_packed"):
+        getattr(L, name).restype = ci
+        getattr(L, name).argtypes = [vp, i64, i64, i64, vp, vp, i64, ci, vp, vp, i64, vp, sz, vp]
     L.nestedfp_plain_gemm_fp16.restype = ci
     L.nestedfp_plain_gemm_fp16.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, sz, vp]
-    L.nestedfp_plain_gemm_fp8.restype = ci
-    L.nestedfp_plain_gemm_fp8.argtypes = [vp, i64, i64, i64, vp, i64, f32, vp, vp, i64, vp, sz, vp]
+    L.nestedfp_plain_gemm_fp16_packed.restype = ci
+    L.nestedfp_plain_gemm_fp16_packed.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, sz, vp]
+    for name in ("nestedfp_plain_gemm_fp8", "nestedfp_plain_gemm_fp8_packed"):
+        getattr(L, name).restype = ci
+        getattr(L, name).argtypes = [vp, i64, i64, i64, vp, i64, f32, vp, vp, i64, vp, sz, vp]
     L.nestedfp_gemm_fp8_prequantized.restype = ci
-    L.nestedfp_gemm_fp8_prequantized.argtypes = [vp, vp, i64, i64, vp, i64, f32, vp, i64, vp, sz, vp]
+    L.nestedfp_gemm_fp8_prequantized.argtypes = [vp, vp, i64, i64, vp, i64, ci, f32, vp, i64, vp, sz, vp]
     L.nestedfp_layer_prepare.restype = ci
-    L.nestedfp_layer_prepare.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+    L.nestedfp_layer_prepare.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, vp, vp]
+    L.nestedfp_select_mode.restype = ci
+    L.nestedfp_select_mode.argtypes = [i64, i64]
+    L.nestedfp_probe_stream_read.restype = ci
+    L.nestedfp_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    L.nestedfp_probe_mfma.restype = ci
+    L.nestedfp_probe_mfma.argtypes = [vp, ci, ci, vp, c.POINTER(c.c_double), vp]
     L.nestedfp_linear_workspace_size.restype = sz
     L.nestedfp_linear_workspace_size.argtypes = [i64, vp, ci]
     L.nestedfp_linear.restype = ci
@@ -113,8 +134,16 @@ def _rowmajor(t, name):
     return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
-def _workspace(nbytes, device):
-    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+def new_workspace(nbytes, device):
+    """A workspace of at least nbytes for the GEMM calls, its arrival counters cleared
+    (nestedfp_workspace_init).  Calls that may overlap in time need workspaces of their own."""
+    ws = torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+    st = lib().nestedfp_workspace_init(_ptr(ws), ws.numel(), _stream())
+    _check(st, "nestedfp_workspace_init")
+    return ws
+
+
+_workspace = new_workspace
 
 
 def range_check(W):
@@ -129,7 +158,7 @@ def range_check(W):
 
 
 class PackedPlane:
-    """One byte plane of an [N,K] layer in the library's packed storage (1 KB blocks of
+    """One byte plane of an [N,K] layer in the library's optional packed storage (1 KB blocks of
     16 rows x 64 columns, see include/nestedfp.h).  `data` is the flat uint8 device tensor."""
 
     def __init__(self, N, K, device=None, data=None):
@@ -156,12 +185,25 @@ class PackedPlane:
         return out
 
 
+class PackedFP16:
+    """FP16 weights of an [N,K] layer in packed storage (2 KB blocks), the operand of
+    plain_gemm_fp16 on packed weights."""
+
+    def __init__(self, N, K, data):
+        self.N, self.K, self.data = int(N), int(K), data
+
+    shape = property(lambda self: (self.N, self.K))
+
+    def data_ptr(self):
+        return self.data.data_ptr()
+
+
 def plane_bytes(N, K):
     return int(lib().nestedfp_plane_bytes(int(N), int(K)))
 
 
 def pack_plane(B):
-    """Row-major uint8 [N,K] (e.g. E4M3 codes) -> PackedPlane."""
+    """Row-major uint8 [N,K] (a byte plane, E4M3 codes) -> PackedPlane."""
     N, K, ld = _rowmajor(B, "B")
     P = PackedPlane(N, K, B.device)
     if N > 0:
@@ -170,35 +212,65 @@ def pack_plane(B):
     return P
 
 
-def _as_plane(B):
-    return B if isinstance(B, PackedPlane) or B is None else pack_plane(B)
-
-
-def decompose(W, upper=None, lower=None, check=True):
-    """fp16 W [N,K] -> (upper, lower) packed planes.  With check=True (default) waits for
-    the result and raises NestedFPError(ERR_RANGE) if the layer is not applicable."""
+def pack_fp16(W):
+    """Row-major fp16 [N,K] -> PackedFP16."""
     N, K, ldw = _rowmajor(W, "W")
-    if upper is None:
-        upper = PackedPlane(N, K, W.device)
-    if lower is None:
-        lower = PackedPlane(N, K, W.device)
+    nbytes = int(lib().nestedfp_packed_fp16_bytes(N, K))
+    data = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    if N > 0:
+        st = lib().nestedfp_pack_fp16(_ptr(W), N, K, ldw, _ptr(data), _stream())
+        _check(st, "nestedfp_pack_fp16")
+    return PackedFP16(N, K, data)
+
+
+def _is_packed(plane):
+    return isinstance(plane, PackedPlane)
+
+
+def _new_planes(N, K, device, packed):
+    if packed:
+        return PackedPlane(N, K, device), PackedPlane(N, K, device)
+    return (torch.empty((N, K), dtype=torch.uint8, device=device),
+            torch.empty((N, K), dtype=torch.uint8, device=device))
+
+
+def _check_plane(plane, N, K, name):
+    if _is_packed(plane):
+        if plane.shape != (N, K):
+            raise ValueError("%s plane has the wrong shape" % name)
+    elif (plane.dtype != torch.uint8 or tuple(plane.shape) != (N, K) or not plane.is_contiguous()):
+        raise ValueError("%s must be a contiguous uint8 [N,K] tensor or a PackedPlane" % name)
+
+
+def decompose(W, upper=None, lower=None, check=True, packed=False):
+    """fp16 W [N,K] -> (upper, lower): row-major uint8 [N,K] tensors, or PackedPlanes with
+    packed=True (or when PackedPlanes are passed in).  With check=True (default) waits for the
+    result and raises NestedFPError(ERR_RANGE) if the layer is not applicable."""
+    N, K, ldw = _rowmajor(W, "W")
+    if upper is not None:
+        packed = _is_packed(upper)
+    if upper is None or lower is None:
+        u2, l2 = _new_planes(N, K, W.device, packed)
+        upper = u2 if upper is None else upper
+        lower = l2 if lower is None else lower
+    _check_plane(upper, N, K, "upper")
+    _check_plane(lower, N, K, "lower")
     cnt = torch.empty(1, dtype=torch.int64, device=W.device)
     host = ctypes.c_uint64(0)
-    st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
-                                  ctypes.byref(host) if check else None, _stream())
+    fn = lib().nestedfp_decompose_packed if packed else lib().nestedfp_decompose
+    st = fn(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt), ctypes.byref(host) if check else None, _stream())
     _check(st, "nestedfp_decompose")
     return upper, lower
 
 
-def decompose_count(W):
+def decompose_count(W, packed=False):
     """Like decompose(check=False) but also returns the out-of-range count (synchronises)."""
     N, K, ldw = _rowmajor(W, "W")
-    upper = PackedPlane(N, K, W.device)
-    lower = PackedPlane(N, K, W.device)
+    upper, lower = _new_planes(N, K, W.device, packed)
     cnt = torch.empty(1, dtype=torch.int64, device=W.device)
     host = ctypes.c_uint64(0)
-    st = lib().nestedfp_decompose(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
-                                  ctypes.byref(host), _stream())
+    fn = lib().nestedfp_decompose_packed if packed else lib().nestedfp_decompose
+    st = fn(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt), ctypes.byref(host), _stream())
     if st not in (OK, ERR_RANGE):
         raise NestedFPError(st, "nestedfp_decompose")
     return upper, lower, int(host.value)
@@ -209,7 +281,8 @@ def reconstruct(upper, lower, out=None):
     if out is None:
         out = torch.empty((N, K), dtype=torch.float16, device=upper.device)
     _, _, ldw = _rowmajor(out, "out")
-    st = lib().nestedfp_reconstruct(_ptr(upper), _ptr(lower), N, K, _ptr(out), ldw, _stream())
+    fn = lib().nestedfp_reconstruct_packed if _is_packed(upper) else lib().nestedfp_reconstruct
+    st = fn(_ptr(upper), _ptr(lower), N, K, _ptr(out), ldw, _stream())
     _check(st, "nestedfp_reconstruct")
     return out
 
@@ -230,64 +303,82 @@ def gemm_workspace_size(M, N, K, mode):
 
 
 def gemm(X, upper, lower, mode, act_scale=None, out=None, workspace=None):
-    """Y = X @ W^T over the packed planes, in MODE_FP16 or MODE_FP8 (lower may be None in FP8)."""
+    """Y = X @ W^T over the planes (row-major uint8 tensors or PackedPlanes), in MODE_FP16 or
+    MODE_FP8 (lower may be None in FP8)."""
     M, K, ldx = _rowmajor(X, "X")
     N = upper.shape[0]
     if upper.shape[1] != K:
         raise ValueError("K of X and of the planes differ")
+    _check_plane(upper, N, K, "upper")
+    if lower is not None:
+        _check_plane(lower, N, K, "lower")
+        if _is_packed(lower) != _is_packed(upper):
+            raise ValueError("upper and lower must use the same storage")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     _, _, ldy = _rowmajor(out, "out")
     if workspace is None:
         workspace = _workspace(gemm_workspace_size(M, N, K, mode), X.device)
-    st = lib().nestedfp_gemm(_ptr(X), M, K, ldx, _ptr(upper), _ptr(lower), N, int(mode),
-                             _ptr(act_scale), _ptr(out), ldy, _ptr(workspace), workspace.numel(),
-                             _stream())
+    fn = lib().nestedfp_gemm_packed if _is_packed(upper) else lib().nestedfp_gemm
+    st = fn(_ptr(X), M, K, ldx, _ptr(upper), _ptr(lower), N, int(mode), _ptr(act_scale), _ptr(out), ldy,
+            _ptr(workspace), workspace.numel(), _stream())
     _check(st, "nestedfp_gemm")
     return out
 
 
 def plain_gemm_fp16(X, W, out=None, workspace=None):
+    """W: row-major fp16 [N,K] tensor, or PackedFP16."""
     M, K, ldx = _rowmajor(X, "X")
-    N, _, ldw = _rowmajor(W, "W")
+    packed = isinstance(W, PackedFP16)
+    if packed:
+        N, ldw = W.shape[0], K
+        if W.shape[1] != K:
+            raise ValueError("K of X and of W differ")
+    else:
+        N, _, ldw = _rowmajor(W, "W")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     _, _, ldy = _rowmajor(out, "out")
     if workspace is None:
         workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP16), X.device)
-    st = lib().nestedfp_plain_gemm_fp16(_ptr(X), M, K, ldx, _ptr(W), N, ldw, _ptr(out), ldy,
-                                        _ptr(workspace), workspace.numel(), _stream())
+    if packed:
+        st = lib().nestedfp_plain_gemm_fp16_packed(_ptr(X), M, K, ldx, _ptr(W), N, _ptr(out), ldy,
+                                                   _ptr(workspace), workspace.numel(), _stream())
+    else:
+        st = lib().nestedfp_plain_gemm_fp16(_ptr(X), M, K, ldx, _ptr(W), N, ldw, _ptr(out), ldy,
+                                            _ptr(workspace), workspace.numel(), _stream())
     _check(st, "nestedfp_plain_gemm_fp16")
     return out
 
 
 def plain_gemm_fp8(X, Wq, w_scale, act_scale=None, out=None, workspace=None):
-    """Wq: PackedPlane of E4M3 codes (a row-major uint8 [N,K] tensor is packed first)."""
+    """Wq: E4M3 codes as a row-major uint8 [N,K] tensor or a PackedPlane."""
     M, K, ldx = _rowmajor(X, "X")
-    Wq = _as_plane(Wq)
     N = Wq.shape[0]
+    _check_plane(Wq, N, K, "Wq")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     _, _, ldy = _rowmajor(out, "out")
     if workspace is None:
         workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP8), X.device)
-    st = lib().nestedfp_plain_gemm_fp8(_ptr(X), M, K, ldx, _ptr(Wq), N, float(w_scale),
-                                       _ptr(act_scale), _ptr(out), ldy, _ptr(workspace),
-                                       workspace.numel(), _stream())
+    fn = lib().nestedfp_plain_gemm_fp8_packed if _is_packed(Wq) else lib().nestedfp_plain_gemm_fp8
+    st = fn(_ptr(X), M, K, ldx, _ptr(Wq), N, float(w_scale), _ptr(act_scale), _ptr(out), ldy, _ptr(workspace),
+            workspace.numel(), _stream())
     _check(st, "nestedfp_plain_gemm_fp8")
     return out
 
 
 def gemm_fp8_prequantized(Xq, scales, upper, w_scale=2.0 ** -8, out=None, workspace=None):
     M, K = Xq.shape
-    upper = _as_plane(upper)
     N = upper.shape[0]
+    _check_plane(upper, N, K, "upper")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=Xq.device)
     _, _, ldy = _rowmajor(out, "out")
     if workspace is None:
         workspace = _workspace(gemm_workspace_size(M, N, K, MODE_FP8), Xq.device)
-    st = lib().nestedfp_gemm_fp8_prequantized(_ptr(Xq), _ptr(scales), M, K, _ptr(upper), N,
+    layout = LAYOUT_PACKED if _is_packed(upper) else LAYOUT_ROWMAJOR
+    st = lib().nestedfp_gemm_fp8_prequantized(_ptr(Xq), _ptr(scales), M, K, _ptr(upper), N, layout,
                                               float(w_scale), _ptr(out), ldy, _ptr(workspace),
                                               workspace.numel(), _stream())
     _check(st, "nestedfp_gemm_fp8_prequantized")
@@ -296,21 +387,22 @@ def gemm_fp8_prequantized(Xq, scales, upper, w_scale=2.0 ** -8, out=None, worksp
 
 class _LayerStruct(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int64), ("K", ctypes.c_int64), ("is_exception", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("upper", ctypes.c_void_p), ("lower", ctypes.c_void_p),
+                ("layout", ctypes.c_int32), ("upper", ctypes.c_void_p), ("lower", ctypes.c_void_p),
                 ("W", ctypes.c_void_p), ("ldw", ctypes.c_int64), ("out_of_range", ctypes.c_uint64)]
 
 
 class Layer:
-    """One linear as the library describes it: NestedFP planes, or the FP16 weights themselves
-    if the layer is an exception (some |w| > 1.75).  Keeps the device buffers alive."""
+    """One linear as the library describes it: NestedFP planes (row-major, or packed with
+    packed=True), or the FP16 weights themselves if the layer is an exception (some |w| > 1.75).
+    Keeps the device buffers alive."""
 
-    def __init__(self, W):
+    def __init__(self, W, packed=False):
         N, K, ldw = _rowmajor(W, "W")
         self.c = _LayerStruct()
-        upper, lower = PackedPlane(N, K, W.device), PackedPlane(N, K, W.device)
+        upper, lower = _new_planes(N, K, W.device, packed)
         cnt = torch.empty(1, dtype=torch.int64, device=W.device)
-        st = lib().nestedfp_layer_prepare(_ptr(W), N, K, ldw, _ptr(upper), _ptr(lower), _ptr(cnt),
-                                          ctypes.byref(self.c), _stream())
+        st = lib().nestedfp_layer_prepare(_ptr(W), N, K, ldw, LAYOUT_PACKED if packed else LAYOUT_ROWMAJOR,
+                                          _ptr(upper), _ptr(lower), _ptr(cnt), ctypes.byref(self.c), _stream())
         _check(st, "nestedfp_layer_prepare")
         if self.c.is_exception:
             self.W, self.upper, self.lower = W, None, None     # planes released
@@ -338,3 +430,24 @@ def linear(X, layer, mode, act_scale=None, out=None, workspace=None):
     _check(st, "nestedfp_linear")
     return out
 
+
+def select_mode(tokens, threshold=1024):
+    """The load-aware policy of Sec. 5.4: MODE_FP8 if tokens > threshold else MODE_FP16."""
+    return int(lib().nestedfp_select_mode(int(tokens), int(threshold)))
+
+
+def probe_stream_read(buf):
+    """Launches the read-only streaming probe over `buf` (uint8 device tensor, a multiple of 64 KiB)."""
+    sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    st = lib().nestedfp_probe_stream_read(_ptr(buf), buf.numel(), _ptr(sink), _stream())
+    _check(st, "nestedfp_probe_stream_read")
+
+
+def probe_mfma(operands, fp8, iters):
+    """Launches the MFMA-only probe; returns the flops of the launch."""
+    sink = torch.zeros(1, dtype=torch.int32, device=operands.device)
+    flops = ctypes.c_double(0.0)
+    st = lib().nestedfp_probe_mfma(_ptr(operands), int(bool(fp8)), int(iters), _ptr(sink), ctypes.byref(flops),
+                                   _stream())
+    _check(st, "nestedfp_probe_mfma")
+    return flops.value

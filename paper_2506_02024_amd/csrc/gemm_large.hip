@@ -1,12 +1,14 @@
 // LDS-tiled MFMA GEMMs for prefill-sized batches: Y = X * W^T, compute-bound.
 //
 // Three kernels.  large_gemm_kernel multiplies plain FP16 weights or E4M3 weights (FP8 mode: the
-// upper plane as it is): TM tokens x TN weight rows x 128 bytes of K per row (64 halves or 128
-// E4M3 bytes) per stage, two LDS stages, 8 waves.  nested_bypass_kernel is FP16 mode: Sec. 4.2
+// upper plane as it is, row-major or in packed blocks): TM tokens x TN weight rows x 128 bytes of K
+// per row (64 halves or 128 E4M3 bytes) per stage, two LDS stages, 8 waves.  nested_bypass_kernel is FP16 mode: Sec. 4.2
 // puts the FP16 reconstruction between the shared-memory-to-register copy and the tensor-core
 // instruction of every warp and hides it with a third pipeline stage; here every weight belongs
-// to exactly one wave, which loads the packed plane blocks into registers, merges them there
-// (Alg. 1) and feeds them to the MFMA -- the weights never pass through LDS.  e4m3_bypass_kernel
+// to exactly one wave, which loads its 16 bytes of each plane per lane (from row-major planes or
+// from packed blocks) into registers, merges them there (Alg. 1) and feeds them to the MFMA -- the
+// weights never pass through LDS; the same kernel without the merge multiplies FP16 weights stored
+// in packed blocks, the like-for-like baseline of Sec. 5.2.  e4m3_bypass_kernel
 // is the same register path for E4M3 weights, used for batches of 49 .. 64 tokens, where the
 // weight stream is the bound.
 //
@@ -24,12 +26,12 @@ namespace nfp {
 
 struct LargeParams {
     const uint8_t *X;       // fp16 X (bytes) or E4M3 Xq
-    int64_t x_row_bytes;    // < 2^24 (checked on the host): tile-local offsets fit in 31 bits
+    int64_t x_row_bytes;    // 256 rows of it stay below 2^31 (checked on the host): bit 31 of a tile-local offset marks a dead load
     const float *scales;
     float w_scale;
     const uint8_t *W0;
     const uint8_t *W1;
-    int64_t w_row_bytes;    // bytes per row of W0 (plain: 2*ldw, planes / E4M3: K)
+    int64_t w_row_bytes;    // bytes per row of W0 for row-major weights (plain: 2*ldw, planes / E4M3: K); same limit
     int M, N, K;
     int k_bytes;            // bytes per row along K for 8-chunk operands (2K or K)
     int kblocks;            // 64-column blocks per row tile of a packed plane: ceil(K / 64)
@@ -91,9 +93,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint8_t *base,
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + row0 * row_bytes), 0, bytes, 0x00020000);
 }
 
-// raw buffer over the 16-row tiles of a packed plane that hold rows row0 .. row0+rows-1
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base, int64_t row0, int rows, int kblocks) {
-    const int64_t tile_bytes = (int64_t)kblocks * 1024;
+// raw buffer over the 16-row tiles of a packed plane (blocks of block_bytes) that hold rows row0 .. row0+rows-1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base, int64_t row0, int rows, int kblocks,
+                                                             int block_bytes) {
+    const int64_t tile_bytes = (int64_t)kblocks * block_bytes;
     uint32_t bytes = rows > 0 ? (uint32_t)(((rows + 15) >> 4) * tile_bytes) : 0u;
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base + (row0 >> 4) * tile_bytes), 0, bytes, 0x00020000);
 }
@@ -102,7 +105,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t plane_rsrc(const uint8_t *base
 // MB: rows of an MFMA block (16 or 32).  Accumulator layout: lane l holds token l % MB of a block
 // and, for v = 0 .. MB*MB/256 - 1, the four consecutive weight rows
 // (MB == 32 ? 8 v + 4 (l / 32) : 4 (l / 16)) .. +3.
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int MB_ = (KIND == kE4M3 ? 32 : 16)>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int MB_ = (kind_is_fp8(KIND) ? 32 : 16)>
 struct TileStore {
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
@@ -126,7 +129,7 @@ struct TileStore {
         for (int j = 0; j < FMB; ++j) {
             const int row = wm * WTM + MB * j + r;
             float s = 1.0f;
-            if (KIND == kE4M3) {
+            if (kind_is_fp8(KIND)) {
                 const int m = m0 + row;
                 s = (m < p.M ? p.scales[m] : 0.f) * p.w_scale;
             }
@@ -164,7 +167,7 @@ struct TileStore {
             const int m = m0 + wm * WTM + MB * j + r;
             if (m >= p.M) continue;
             float s = 1.0f;
-            if (KIND == kE4M3 && gridDim.y == 1) s = p.scales[m] * p.w_scale;
+            if (kind_is_fp8(KIND) && gridDim.y == 1) s = p.scales[m] * p.w_scale;
 #pragma unroll
             for (int i = 0; i < FNB; ++i)
 #pragma unroll
@@ -201,7 +204,9 @@ struct TileStore {
 
 template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
 struct LargeKernel {
-    static_assert(KIND == kPlainF16 || KIND == kE4M3, "NestedFP16 has a kernel of its own");
+    static_assert(KIND == kPlainF16 || KIND == kE4M3 || KIND == kE4M3Row, "NestedFP16 has a kernel of its own");
+    static constexpr bool FP8 = kind_is_fp8(KIND);
+    static constexpr bool PACKED_W = KIND == kE4M3;    // weight stage = packed 1 KB blocks as they are
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static_assert(WAVES == 8, "two waves per SIMD: one loading (older), one not");
     static constexpr int THREADS = 64 * WAVES;
@@ -220,9 +225,9 @@ struct LargeKernel {
     // MB tokens; a K-tile (128 bytes per row) is two substeps of 64 bytes per row; a fragment is
     // NCH 16-byte chunks per lane: lane l supplies row l % MB and bytes 16 * NCH * (l / MB) .. of
     // the substep's 64.
-    static constexpr int MB = KIND == kE4M3 ? 32 : 16;
+    static constexpr int MB = FP8 ? 32 : 16;
     static constexpr int SUBS = 2;
-    static constexpr int NCH = KIND == kE4M3 ? 2 : 1;
+    static constexpr int NCH = FP8 ? 2 : 1;
     static constexpr int FMB = WTM / MB, FNB = WTN / MB;
     static constexpr int MF = FMB * FNB;                             // MFMAs per substep
     typedef typename std::conditional<MB == 32, floatx16, floatx4>::type AccT;
@@ -250,11 +255,11 @@ struct LargeKernel {
     static __device__ __forceinline__ int k_chunk(int s, int g, int q) { return 4 * s + NCH * g + q; }
 
     // LDS address of chunk q of a weight fragment: row, substep s, lane group g = l / MB.
-    // FP16 kinds: rows of 128 bytes, XOR-swizzled.  E4M3: the stage holds the packed 1 KB blocks
+    // Row-major weights: rows of 128 bytes, XOR-swizzled.  Packed E4M3: the stage holds the 1 KB blocks
     // as they are in memory, [row tile][2 blocks]; a substep is one block, and 16 lanes with
     // consecutive rows read 256 consecutive bytes.
     static __device__ __forceinline__ int w_addr(int row, int s, int g, int q) {
-        if (KIND == kE4M3) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (NCH * g + q)) << 4);
+        if (PACKED_W) return (((row >> 4) * 2 + s) << 10) + (((row & 15) + 16 * (NCH * g + q)) << 4);
         return swz(row, k_chunk(s, g, q));
     }
 
@@ -285,7 +290,7 @@ struct LargeKernel {
     template <int Q>
     static __device__ __forceinline__ void mfma_one(const Frags &f, AccT (&acc)[FNB][FMB]) {
         constexpr int j = Q / FNB, i = Q % FNB;
-        if constexpr (KIND == kE4M3) {
+        if constexpr (FP8) {
             intx8 a = {f.a[i][0].x, f.a[i][0].y, f.a[i][0].z, f.a[i][0].w, f.a[i][NCH - 1].x, f.a[i][NCH - 1].y, f.a[i][NCH - 1].z, f.a[i][NCH - 1].w};
             intx8 b = {f.b[j][0].x, f.b[j][0].y, f.b[j][0].z, f.b[j][0].w, f.b[j][NCH - 1].x, f.b[j][NCH - 1].y, f.b[j][NCH - 1].z, f.b[j][NCH - 1].w};
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i][j], 0, 0, 0, 0, 0, 0);
@@ -320,13 +325,13 @@ struct LargeKernel {
     static __device__ __forceinline__ void make_dma_offsets(DmaOffsets &o, const LargeParams &p, int wave, int lane) {
         const int pc = lane & 7;
         const int slot = pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);  // (row >> 1) & 7 for row = gid*8 + lane/8
-        const int c = KIND == kE4M3 ? slot : fp16_chunk_of_slot(slot);
+        const int c = FP8 ? slot : fp16_chunk_of_slot(slot);
         o.kpos = 16u * c;
 #pragma unroll
         for (int i = 0; i < XG; ++i) o.x[i] = (uint32_t)((i * DW + wave) * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * c;
 #pragma unroll
         for (int i = 0; i < WG8; ++i) {
-            if (KIND == kE4M3) {
+            if (PACKED_W) {
                 // packed upper plane: load i of wave w is block b = i*DW + w of the stage, i.e. block
                 // column (2*kt + b%2) of row tile b/2; lane l fetches chunk l
                 const int b = i * DW + wave;
@@ -352,7 +357,7 @@ struct LargeKernel {
                                                      16, (o.x[i] + kb) | kill, 0, 0, 0);
         } else {
             const int j = i - XG;
-            if (KIND == kE4M3) {
+            if (PACKED_W) {
                 // w_lim = block columns of the plane; past them the load is sent out of range
                 const uint32_t kill = ((uint32_t)(2 * kt + o.wbit) < w_lim) ? 0u : 0x80000000u;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)(stage + (j * DW + wave) * 1024),
@@ -433,13 +438,13 @@ struct LargeKernel {
         const int kt_end = min(kt_begin + p.ktiles_per_split, p.ktiles_total);
 
         const __amdgpu_buffer_rsrc_t rx = tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes);
-        const __amdgpu_buffer_rsrc_t rw = KIND == kPlainF16
-            ? tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes)
-            : plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks);
+        const __amdgpu_buffer_rsrc_t rw = PACKED_W
+            ? plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks, 1024)
+            : tile_rsrc(p.W0, n0, min(TN, p.N - n0), p.w_row_bytes, p.k_bytes);
         DmaOffsets dof;
         make_dma_offsets(dof, p, wave, lane);
         const uint32_t x_lim = (uint32_t)p.k_bytes;
-        const uint32_t w_lim = KIND == kE4M3 ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
+        const uint32_t w_lim = PACKED_W ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
 
         // Two LDS stages; tokens and weights go straight from global memory into LDS.
         if (wave < DW) {
@@ -489,16 +494,22 @@ large_gemm_kernel(LargeParams p) {
 
 // ---- NestedFP16 with the weights kept out of LDS ------------------------------------------------
 // Eight waves side by side along the weight rows: a wave owns TN/8 weight rows and all TM tokens
-// of the tile, so every weight is needed by exactly one wave.  The wave loads its packed plane
-// blocks straight into registers (lane l = chunk l: row l % 16, columns 16 * (l / 16) .. +15),
-// merges them there (Sec. 4.2, Alg. 1) and feeds the result to the MFMA as it is: the sum over k
+// of the tile, so every weight is needed by exactly one wave.  The wave loads 16 bytes of each
+// plane per lane straight into registers (lane l: row l % 16, columns 16 * (l / 16) .. +15 of a
+// 64-column block -- 16 rows x 64 bytes per instruction from row-major planes, one contiguous
+// kilobyte from packed ones), merges them there (Sec. 4.2, Alg. 1) and feeds the result to the MFMA
+// as it is (WK = kPlainF16Packed: FP16 weights in packed blocks, no merge): the sum over k
 // does not care about the order of k, so substep s of a K-tile takes columns 16 g + 8 s .. + 7
 // from lane group g, and the token fragments are read from LDS in the same order (chunk
 // 2 g + s of the 128-byte row, see fp16_chunk_of_slot).  No ds_write, no weight tile in LDS; LDS holds four stages of
 // the token tile only (loads run three K-tiles ahead), and the one barrier per K-tile sits
 // at its end and waits for no LDS read.
-template <int TM, int TN>
+template <int TM, int TN, int WK>
 struct BypassKernel {
+    static_assert(WK == kNestedF16 || WK == kNestedF16Row || WK == kPlainF16Packed, "weights that go through registers");
+    static constexpr bool MERGE = kind_is_nested(WK);
+    static constexpr bool ROWMAJOR = WK == kNestedF16Row;
+    static constexpr int BLOCK_BYTES = 1024 * kind_elem_bytes(WK);   // packed kinds: one 16 x 64 block
     typedef TileStore<kNestedF16, TM, TN, 1, 8> Store;
     static constexpr int DW = 4;                               // waves that issue the token loads
     static constexpr int WTN = TN / 8;
@@ -520,7 +531,8 @@ struct BypassKernel {
     static_assert(FNB <= 2 && FMB > LEAD && MF % NMQ == 0 && MF % XG == 0 && MQS >= 2, "slot plan");
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
-    struct Raw { u32x4 u[FNB], l[FNB]; };                      // one K-tile of the wave's plane blocks
+    // one K-tile of the wave's weights: 16 bytes of each plane, or the two halves of a packed FP16 block
+    struct Raw { u32x4 u[FNB], l[FNB]; };
 
     struct Ctx {
         floatx4 (&acc)[FNB][FMB];
@@ -529,10 +541,10 @@ struct BypassKernel {
         Raw (&raw)[NRAW];
         __amdgpu_buffer_rsrc_t rx, rw0, rw1;
         uint32_t x_off, x_step, x_kpos, x_lim;               // offset of the wave's first load, step between its loads
-        uint32_t w_off, w_lim;
+        uint32_t w_off, w_istep, w_kpos, w_lim;              // lane + wave part, step between row tiles, column test
         const uint8_t *lds;
         lds_byte *lds3;
-        int wave, lane, kblocks;
+        int wave, lane;
         int kt, st;                                            // K-tile, its LDS stage
     };
 
@@ -541,23 +553,33 @@ struct BypassKernel {
         dst = *reinterpret_cast<const intx4 *>(stage + swz(16 * J + (lane & 15), 4 * s + (lane >> 4)));
     }
 
+    // the lane's columns of K-tile kt lie inside K (w_kpos = 16 (l / 16) for row-major planes, whose
+    // rows have no padding; 0 for packed blocks, which are zero-padded to whole blocks); otherwise
+    // the load is sent out of the buffer's range and returns zero
     static __device__ __forceinline__ void load_raw(Raw &r, const Ctx &c, int kt) {
-        const uint32_t kill = ((uint32_t)kt < c.w_lim) ? 0u : 0x80000000u;
+        const uint32_t kill = ((uint32_t)kt * 64u + c.w_kpos < c.w_lim) ? 0u : 0x80000000u;
 #pragma unroll
         for (int i = 0; i < FNB; ++i) {
-            const uint32_t off = (c.w_off + (uint32_t)(i * c.kblocks + kt) * 1024u) | kill;
+            const uint32_t off = (c.w_off + (uint32_t)i * c.w_istep + (uint32_t)kt * (ROWMAJOR ? 64u : (uint32_t)BLOCK_BYTES)) | kill;
             r.u[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off, 0, 0);
-            r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, off, 0, 0);
+            if (MERGE) r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, off, 0, 0);
+            else r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off + 1024u, 0, 0);
         }
     }
 
-    // four weights of row tile I: dwords H (substep 0) or 2 + H (substep 1) of the lane's chunk
+    // four weights of row tile I: dwords H (substep 0) or 2 + H (substep 1) of the lane's chunk of
+    // each plane; packed FP16 weights are taken as they are (first half block = substep 0)
     template <int S, int I, int H>
     static __device__ __forceinline__ void merge_part(intx4 &dst, const Raw &r) {
-        uint32_t w01, w23;
-        merge4(r.u[I][2 * S + H], r.l[I][2 * S + H], w01, w23);
-        dst[2 * H] = (int)w01;
-        dst[2 * H + 1] = (int)w23;
+        if constexpr (MERGE) {
+            uint32_t w01, w23;
+            merge4(r.u[I][2 * S + H], r.l[I][2 * S + H], w01, w23);
+            dst[2 * H] = (int)w01;
+            dst[2 * H + 1] = (int)w23;
+        } else {
+            dst[2 * H] = (int)(S == 0 ? r.u[I][2 * H] : r.l[I][2 * H]);
+            dst[2 * H + 1] = (int)(S == 0 ? r.u[I][2 * H + 1] : r.l[I][2 * H + 1]);
+        }
     }
 
     static __device__ __forceinline__ void dma_x(const Ctx &c, int i, int kt) {
@@ -661,17 +683,30 @@ struct BypassKernel {
             for (int j = 0; j < FMB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
         intx4 a[2][FNB], b[2][FMB];
         Raw raw[NRAW];
+        const int w_rows = min(TN, p.N - n0);
         Ctx c{acc, a, b, raw,
               tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes),
-              plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks), plane_rsrc(p.W1, n0, min(TN, p.N - n0), p.kblocks),
-              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, (uint32_t)p.kblocks, lds, lds3, wave, lane,
-              p.kblocks, kt_begin, 0};
+              ROWMAJOR ? tile_rsrc(p.W0, n0, w_rows, p.w_row_bytes, p.K) : plane_rsrc(p.W0, n0, w_rows, p.kblocks, BLOCK_BYTES),
+              ROWMAJOR ? tile_rsrc(p.W1, n0, w_rows, p.w_row_bytes, p.K)
+                       : plane_rsrc(MERGE ? p.W1 : p.W0, n0, w_rows, p.kblocks, BLOCK_BYTES),
+              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, 0u, 0u, 0u, lds, lds3, wave, lane,
+              kt_begin, 0};
         {
             const int pc = lane & 7;
             const int ch = fp16_chunk_of_slot(pc ^ ((((wave & 1) << 2) + (lane >> 4)) & 7));   // (row >> 1) & 7 for row = gid*8 + lane/8
             c.x_kpos = 16u * ch;
             c.x_off = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * ch;
-            c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+            if (ROWMAJOR) {
+                c.w_off = (uint32_t)(FNB * wave * 16 + (lane & 15)) * (uint32_t)p.w_row_bytes + 16u * (uint32_t)(lane >> 4);
+                c.w_istep = 16u * (uint32_t)p.w_row_bytes;
+                c.w_kpos = 16u * (uint32_t)(lane >> 4);
+                c.w_lim = (uint32_t)p.K;
+            } else {
+                c.w_off = (uint32_t)(FNB * wave * p.kblocks) * (uint32_t)BLOCK_BYTES + (uint32_t)lane * 16u;
+                c.w_istep = (uint32_t)p.kblocks * (uint32_t)BLOCK_BYTES;
+                c.w_kpos = 0u;
+                c.w_lim = (uint32_t)p.kblocks * 64u;
+            }
         }
         // token tiles of the first XA K-tiles, plane blocks of the first NRAW
         if (wave < DW) {
@@ -717,11 +752,11 @@ struct BypassKernel {
     }
 };
 
-template <int TM, int TN>
+template <int TM, int TN, int WK>
 __global__ void __launch_bounds__(512)
 nested_bypass_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    typedef BypassKernel<TM, TN> Kern;
+    typedef BypassKernel<TM, TN, WK> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -733,7 +768,7 @@ nested_bypass_kernel(LargeParams p) {
 // bytes, which is one operand of v_mfma_f32_16x16x128_f8f6f4, and reads the same bytes of its token
 // (chunks g and 4 + g of the row).  A token block's fragment of K-tile kt + 1 is read right behind
 // the block's MFMAs of K-tile kt, into the same registers.
-template <int TM, int TN>
+template <int TM, int TN, bool ROWMAJOR>
 struct E4m3BypassKernel {
     typedef TileStore<kE4M3, TM, TN, 1, 8, 16> Store;
     static constexpr int DW = 4;                               // waves that issue the token loads
@@ -758,21 +793,21 @@ struct E4m3BypassKernel {
         Tok &tok;                                              // block J is re-read for the next K-tile right behind its MFMAs
         __amdgpu_buffer_rsrc_t rx, rw;
         uint32_t x_off, x_step, x_kpos, x_lim;
-        uint32_t w_off, w_lim;
+        uint32_t w_off, w_istep, w_kpos, w_lim;              // as in the NestedFP16 kernel
         const uint8_t *lds;
         lds_byte *lds3;
-        int wave, lane, kblocks;
+        int wave, lane;
         int kt;
     };
 
     static __device__ __forceinline__ void load_raw(Raw &r, const Ctx &c, int kt) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const uint32_t kill = ((uint32_t)(2 * kt + h) < c.w_lim) ? 0u : 0x80000000u;
+            const uint32_t kill = ((uint32_t)(2 * kt + h) * 64u + c.w_kpos < c.w_lim) ? 0u : 0x80000000u;
 #pragma unroll
             for (int i = 0; i < FNB; ++i)
                 r.u[i][h] = __builtin_bit_cast(intx4, __builtin_amdgcn_raw_buffer_load_b128(
-                    c.rw, (c.w_off + (uint32_t)(i * c.kblocks + 2 * kt + h) * 1024u) | kill, 0, 0));
+                    c.rw, (c.w_off + (uint32_t)i * c.w_istep + (uint32_t)(2 * kt + h) * (ROWMAJOR ? 64u : 1024u)) | kill, 0, 0));
         }
     }
 
@@ -869,16 +904,27 @@ struct E4m3BypassKernel {
             for (int j = 0; j < FMB; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
         Raw raw[NRAW];
         Tok tok;
+        const int w_rows = min(TN, p.N - n0);
         Ctx c{acc, raw, tok,
               tile_rsrc(p.X, m0, min(TM, p.M - m0), p.x_row_bytes, p.k_bytes),
-              plane_rsrc(p.W0, n0, min(TN, p.N - n0), p.kblocks),
-              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, (uint32_t)p.kblocks, lds, lds3, wave, lane,
-              p.kblocks, kt_begin};
+              ROWMAJOR ? tile_rsrc(p.W0, n0, w_rows, p.w_row_bytes, p.K) : plane_rsrc(p.W0, n0, w_rows, p.kblocks, 1024),
+              0u, (uint32_t)(DW * 8) * (uint32_t)p.x_row_bytes, 0u, (uint32_t)p.k_bytes, 0u, 0u, 0u, 0u, lds, lds3, wave, lane,
+              kt_begin};
         {
             const int ch = (lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);    // (row >> 1) & 7 for row = gid*8 + lane/8
             c.x_kpos = 16u * ch;
             c.x_off = (uint32_t)(wave * 8 + (lane >> 3)) * (uint32_t)p.x_row_bytes + 16u * ch;
-            c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+            if (ROWMAJOR) {
+                c.w_off = (uint32_t)(FNB * wave * 16 + (lane & 15)) * (uint32_t)p.w_row_bytes + 16u * (uint32_t)(lane >> 4);
+                c.w_istep = 16u * (uint32_t)p.w_row_bytes;
+                c.w_kpos = 16u * (uint32_t)(lane >> 4);
+                c.w_lim = (uint32_t)p.K;
+            } else {
+                c.w_off = (uint32_t)(FNB * wave * p.kblocks) * 1024u + (uint32_t)lane * 16u;
+                c.w_istep = (uint32_t)p.kblocks * 1024u;
+                c.w_kpos = 0u;
+                c.w_lim = (uint32_t)p.kblocks * 64u;
+            }
         }
         // token tiles of the first XA K-tiles, plane blocks of the first NRAW
         if (wave < DW) {
@@ -916,11 +962,11 @@ struct E4m3BypassKernel {
     }
 };
 
-template <int TM, int TN>
+template <int TM, int TN, bool ROWMAJOR>
 __global__ void __launch_bounds__(512)
 e4m3_bypass_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    typedef E4m3BypassKernel<TM, TN> Kern;
+    typedef E4m3BypassKernel<TM, TN, ROWMAJOR> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -961,9 +1007,9 @@ static const Tile64Cost kTile64Cost[3] = {
     {0.466, 0.4, 512, 5.25e6, 5.5e6, 0.5},    // NestedFP16 (register path, two per CU)
     {0.35, 0.4, 256, 5.5e6, 5.5e6, 0.3},      // E4M3 (register path, one per CU)
 };
-static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
+static LargeConfig choose_tile64(int cls, int64_t M, int64_t N, int kt) {
     const Tuning &t = tuning();
-    const Tile64Cost &tc = kTile64Cost[kind];
+    const Tile64Cost &tc = kTile64Cost[cls];
     LargeConfig c;
     c.tm = 64;  c.tn = 128;  c.split = 1;
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
@@ -988,20 +1034,21 @@ static LargeConfig choose_tile64(int kind, int64_t M, int64_t N, int kt) {
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
-    const int kt = (int)((((kind == kE4M3) ? K : 2 * K) + 127) / 128);
+    const int cls = kind_class(kind);                  // cost tables: plain FP16 through LDS, FP16 through registers, E4M3
+    const int kt = (int)(((kind_is_fp8(kind) ? K : 2 * K) + 127) / 128);
     if (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0))
-        return choose_tile64(kind > kE4M3 ? kE4M3 : kind, M, N, kt);
+        return choose_tile64(cls, M, N, kt);
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
-    const double w_bytes = (double)N * (double)K * (kind == kE4M3 ? 1.0 : 2.0);
+    const double w_bytes = (double)N * (double)K * (kind_is_fp8(kind) ? 1.0 : 2.0);
     for (int sh = 0; sh < 4; ++sh) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
         if (want_n && bn != want_n) continue;
-        const TileCost &tc = kTileCost[kind > 2 ? 2 : kind][sh];
+        const TileCost &tc = kTileCost[cls][sh];
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         for (int split = 1; split <= 8; split *= 2) {
             if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
@@ -1010,7 +1057,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
             const int slices = (kt + per - 1) / per;
             const int64_t rounds = (tiles * slices + 255) / 256;
             double time = (double)rounds * (tc.tfix + per * tc.tk);
-            if (sh == 3 && rounds >= 2) time /= kPairSpeedup[kind > 2 ? 2 : kind];
+            if (sh == 3 && rounds >= 2) time /= kPairSpeedup[cls];
             // the weights' one pass over the memory bus (slower while the chip is not full)
             const int64_t wgs = tiles * slices;
             double mem_floor = w_bytes / (wgs < 512 ? 4.57e6 : 4.44e6);
@@ -1042,10 +1089,10 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
     kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int WK>
 static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = nested_bypass_kernel<TM, TN>;
-    constexpr int lds = BypassKernel<TM, TN>::LDS_BYTES;
+    auto kern = nested_bypass_kernel<TM, TN, WK>;
+    constexpr int lds = BypassKernel<TM, TN, WK>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1054,10 +1101,10 @@ static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
     kern<<<grid, 512, lds, stream>>>(p);
 }
 
-template <int TM, int TN>
+template <int TM, int TN, bool ROWMAJOR>
 static void launch_e4m3_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = e4m3_bypass_kernel<TM, TN>;
-    constexpr int lds = E4m3BypassKernel<TM, TN>::LDS_BYTES;
+    auto kern = e4m3_bypass_kernel<TM, TN, ROWMAJOR>;
+    constexpr int lds = E4m3BypassKernel<TM, TN, ROWMAJOR>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1066,37 +1113,50 @@ static void launch_e4m3_bypass(const LargeParams &p, dim3 grid, hipStream_t stre
     kern<<<grid, 512, lds, stream>>>(p);
 }
 
+// weights through LDS: plain row-major FP16, E4M3 in either storage order
 template <int KIND>
 static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
     if (c.tm == 64) {
         if constexpr (KIND == kPlainF16) launch_large_t<KIND, 64, 128, 2, 4>(p, grid, stream);
-        else launch_e4m3_bypass<64, 128>(p, grid, stream);
+        else launch_e4m3_bypass<64, 128, KIND == kE4M3Row>(p, grid, stream);
     } else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
     else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
     else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
     else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
 }
 
+// weights through registers: NestedFP16 in either storage order, packed FP16
+template <int WK>
 static void launch_nested(const LargeParams &p, const LargeConfig &c, dim3 grid, hipStream_t stream) {
-    if (c.tm == 64) launch_bypass<64, 128>(p, grid, stream);
-    else if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256>(p, grid, stream);
-    else if (c.tm == 256) launch_bypass<256, 128>(p, grid, stream);
-    else if (c.tn == 256) launch_bypass<128, 256>(p, grid, stream);
-    else launch_bypass<128, 128>(p, grid, stream);
+    if (c.tm == 64) launch_bypass<64, 128, WK>(p, grid, stream);
+    else if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256, WK>(p, grid, stream);
+    else if (c.tm == 256) launch_bypass<256, 128, WK>(p, grid, stream);
+    else if (c.tn == 256) launch_bypass<128, 256, WK>(p, grid, stream);
+    else launch_bypass<128, 128, WK>(p, grid, stream);
+}
+
+// The kernels address a tile with 32-bit byte offsets whose bit 31 marks a dead load, so 256 rows
+// of any operand must stay below 2^31 bytes.
+bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw) {
+    const int64_t x_row = kind_is_fp8(kind) ? ldx : 2 * ldx;
+    const int64_t w_row = kind == kPlainF16 ? 2 * ldw : ((K + 63) / 64) * 64 * kind_elem_bytes(kind);
+    const int64_t lim = (int64_t)1 << 31;
+    return 256 * x_row + 4096 < lim && 256 * w_row + 4096 < lim;
 }
 
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
+    if (!large_gemm_supports(kind, a.K, a.ldx, a.ldw)) return kErrShape;
     LargeConfig c = choose_large(kind, a.M, a.N, a.K);
     LargeParams p;
     p.X = static_cast<const uint8_t *>(a.X);
-    p.x_row_bytes = (kind == kE4M3) ? a.ldx : 2 * a.ldx;
+    p.x_row_bytes = kind_is_fp8(kind) ? a.ldx : 2 * a.ldx;
     p.scales = a.scales;
     p.w_scale = a.w_scale;
     p.W0 = static_cast<const uint8_t *>(a.W0);
     p.W1 = static_cast<const uint8_t *>(a.W1);
-    p.w_row_bytes = (kind == kPlainF16) ? 2 * a.ldw : a.K;
+    p.w_row_bytes = (kind == kPlainF16) ? 2 * a.ldw : a.K;        // row-major kinds only
     p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
-    p.k_bytes = (kind == kE4M3) ? (int)a.K : (int)(2 * a.K);
+    p.k_bytes = kind_is_fp8(kind) ? (int)a.K : (int)(2 * a.K);
     p.kblocks = (int)((a.K + 63) / 64);
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;
@@ -1115,12 +1175,16 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)c.split);
     switch (kind) {
         case kPlainF16: launch_large_k<kPlainF16>(p, c, grid, stream); break;
-        case kNestedF16: launch_nested(p, c, grid, stream); break;
-        default: launch_large_k<kE4M3>(p, c, grid, stream); break;
+        case kNestedF16: launch_nested<kNestedF16>(p, c, grid, stream); break;
+        case kNestedF16Row: launch_nested<kNestedF16Row>(p, c, grid, stream); break;
+        case kPlainF16Packed: launch_nested<kPlainF16Packed>(p, c, grid, stream); break;
+        case kE4M3: launch_large_k<kE4M3>(p, c, grid, stream); break;
+        case kE4M3Row: launch_large_k<kE4M3Row>(p, c, grid, stream); break;
+        default: return kErrArg;
     }
     if (hipGetLastError() != hipSuccess) return kErrHip;
     if (c.split > 1)
-        return launch_splitk_reduce(a.partials, c.split, a.M, a.N, kind == kE4M3 ? a.scales : nullptr,
+        return launch_splitk_reduce(a.partials, c.split, a.M, a.N, kind_is_fp8(kind) ? a.scales : nullptr,
                                     a.w_scale, a.Y, a.ldy, stream);
     return kOk;
 }

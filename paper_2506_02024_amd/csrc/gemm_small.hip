@@ -8,11 +8,15 @@
 // Weight rows are the MFMA "A" operand (lane l: row l%16 of a 16-row tile, K-group l/16),
 // tokens (MT tiles of 16) the "B" operand, so each lane ends up with 4 consecutive output
 // columns of one token: 8-byte stores of fp16.
-//   kPlainF16 : lane loads 32 B of row-major FP16 weights    -> 2 x v_mfma_f32_16x16x32_f16
-//   kNestedF16: lane loads 16 B upper + 16 B lower, merges them (Sec. 4.2, Alg. 1) -> same
-//   kE4M3     : lane loads 2 x 16 B of E4M3 bytes (upper plane) -> 1 x v_mfma_f32_16x16x128_f8f6f4
-// The byte planes are stored in 1 KB blocks of 16 rows x 64 columns whose chunk order is the
-// lane order, so every plane load of a wave is one contiguous kilobyte.
+//   plain FP16 : lane loads 32 B of FP16 weights              -> 2 x v_mfma_f32_16x16x32_f16
+//   NestedFP16 : lane loads 16 B upper + 16 B lower, merges them (Sec. 4.2, Alg. 1) -> same
+//   E4M3       : lane loads 2 x 16 B of E4M3 bytes (upper plane) -> 1 x v_mfma_f32_16x16x128_f8f6f4
+// Every kind exists for two storage orders of the weights: row-major [N,K] (the two byte tensors
+// of Sec. 4 "Overview" as they are: a lane's 16 bytes are 16 consecutive columns of its row, a wave
+// instruction gathers 64-byte pieces of 16 rows) and packed blocks of 16 rows x 64 columns whose
+// chunk order is the lane order, so that every load of a wave is one contiguous kilobyte.
+// Columns past K and rows past N are never multiplied: their loads are sent out of the buffer's
+// range and return zero, whatever the memory behind them holds.
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -27,50 +31,59 @@ struct SmallParams {
     float w_scale;
     const uint8_t *W0;      // fp16 W (bytes) / upper plane / E4M3 weights
     const uint8_t *W1;      // lower plane
-    uint32_t w_row_bytes;   // row stride of W0 (and W1) in bytes
-    uint32_t w_bytes;       // addressable bytes of W0 (and W1): (N-1)*w_row_bytes + bytes per row
+    uint32_t w_row_bytes;   // row-major kinds: row stride of W0 (and W1) in bytes
+    uint32_t tile_bytes;    // distance between consecutive 16-row tiles in bytes
+    uint32_t w_bytes;       // addressable bytes of W0 (and W1), < 2^31
     int M, N, K;
     uint16_t *Y;
     int64_t ldy;
     float *partials;        // [S][M][N] when S > 1
+    uint32_t *counters;     // one arrival counter per workgroup column (zero between launches), or NULL
     int k_passes;           // K slices each wave walks through in turn
     int tiles_per_wg;       // 16-row weight tiles each workgroup walks through
     int tile_stride;        // distance between a workgroup's consecutive tiles (1 or gridDim.x)
     int vec_store;          // 1: 8-byte fp16 stores allowed
 };
 
-template <int KIND> struct StepK { static constexpr int value = (KIND == kE4M3 || KIND == kE4M3Quant) ? 128 : 64; };
+template <int KIND> struct StepK { static constexpr int value = kind_is_fp8(KIND) ? 128 : 64; };
 
 // One K-step of weights for one 16-row tile, as loaded (32 bytes per lane).
 struct WItem { u32x4 a, b; };   // plain: 32 B fp16; nested: upper, lower; e4m3: 32 B
 
 // Buffer resource over a weight array: raw (unstructured) addressing with a byte range
 // check, so reads past the end (N tail, look-ahead past the last tile) return zero
-// without touching memory.
+// without touching memory.  The arrays are smaller than 2 GiB (checked on the host), so an
+// offset with bit 31 set is out of range by construction.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t weight_rsrc(const uint8_t *base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base), 0, bytes, 0x00020000);
 }
 
-// Weights of K-step `s` of the wave's slice: `voff` = lane offset (row in tile, K position,
-// fixed for the whole kernel) + tile offset; the step is an immediate.  The whole offset is
-// in the range-checked VGPR part of the address (the scalar offset is not range-checked).
-// Lanes past K read finite neighbours and are multiplied by zero activations.
+constexpr uint32_t kDead = 0x80000000u;               // an offset no weight array reaches
+
+// Where the weights of a K-step sit.  `voff` = lane part + tile part + the wave's slice; step S adds
+// an immediate.  Row-major kinds: lane l = row l % 16, columns 16 (l / 16) .. + 15 of the step's 64
+// (E4M3: of each 64-column half of the step's 128).  Packed kinds: lane l = chunk l of the block.
+template <int KIND> struct WLayout {
+    static constexpr bool PACKED = kind_is_packed(KIND);
+    static constexpr int EB = kind_elem_bytes(KIND);
+    static constexpr int KSTEP = StepK<KIND>::value;
+    // bytes between consecutive K-steps of one tile
+    static constexpr int STEP = PACKED ? (KSTEP / 64) * 1024 * EB : KSTEP * EB;
+    // the second 16 bytes of a lane's step, relative to the first (NestedFP: the other plane, same offset)
+    static constexpr int SECOND = kind_is_nested(KIND) ? 0
+                                  : (KIND == kPlainF16 ? 16 : (PACKED ? 1024 : 64));
+};
+
+// Weights of K-step `S` of the wave's slice.  The whole offset is in the range-checked VGPR part of
+// the address (the scalar offset is not range-checked).  va / vb: the lane's columns of the first /
+// second 16 bytes lie inside K; otherwise the load is sent out of range and returns zero.
 template <int KIND, int S>
 __device__ __forceinline__ void load_w(WItem &r, __amdgpu_buffer_rsrc_t r0, __amdgpu_buffer_rsrc_t r1,
-                                       uint32_t voff) {
-    if (KIND == kPlainF16) {
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128, 0, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 128 + 16, 0, 0);
-    } else if (KIND == kNestedF16) {
-        // packed planes: one 1 KB block per K-step, lane l owns chunk l of it
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 1024, 0, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, voff + S * 1024, 0, 0);
-    } else {
-        // packed E4M3: a K-step of 128 is two blocks; the lane takes its chunk of each, so its
-        // 32 operand bytes are columns 16g..16g+15 of the first and of the second block
-        r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 2048, 0, 0);
-        r.b = __builtin_amdgcn_raw_buffer_load_b128(r0, voff + S * 2048 + 1024, 0, 0);
-    }
+                                       uint32_t voff, bool va, bool vb) {
+    typedef WLayout<KIND> L;
+    const uint32_t oa = va ? voff : kDead, ob = vb ? voff : kDead;
+    r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, oa + S * L::STEP, 0, 0);
+    r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, ob + S * L::STEP + L::SECOND, 0, 0);
 }
 
 // Activations of one K-step for 16 tokens (32 bytes per lane); zero outside M and K.
@@ -78,7 +91,7 @@ template <int KIND>
 __device__ __forceinline__ void load_x(u32x4 &xa, u32x4 &xb, const SmallParams &p, int m, int k) {
     const u32x4 zero = {0u, 0u, 0u, 0u};
     bool row_ok = m < p.M;
-    if (KIND == kE4M3) {
+    if (kind_is_fp8(KIND)) {
         // same column order as the weight operand: 16 columns of each 64-column half
         const uint8_t *src = p.X + (int64_t)m * p.x_row_bytes + k;
         xa = (row_ok && k < p.K) ? *reinterpret_cast<const u32x4 *>(src) : zero;
@@ -100,7 +113,7 @@ __device__ __forceinline__ half8 as_half8(const u32x4 &v) {
 // Turns the raw weight bytes of one step into MFMA operands (merges the planes if nested).
 template <int KIND>
 __device__ __forceinline__ void prep_w(const WItem &w, u32x4 &w_lo, u32x4 &w_hi) {
-    if (KIND == kNestedF16) {
+    if (kind_is_nested(KIND)) {
         merge16(w.a, w.b, w_lo, w_hi);             // Sec. 4.2, Alg. 1
     } else {
         w_lo = w.a;
@@ -111,7 +124,7 @@ __device__ __forceinline__ void prep_w(const WItem &w, u32x4 &w_lo, u32x4 &w_hi)
 template <int KIND>
 __device__ __forceinline__ floatx4 mma_step(const u32x4 &w_lo, const u32x4 &w_hi, const u32x4 &xa,
                                             const u32x4 &xb, floatx4 acc) {
-    if (KIND == kE4M3 || KIND == kE4M3Quant) {
+    if (kind_is_fp8(KIND)) {
         intx8 a, b;
         a[0] = w_lo.x; a[1] = w_lo.y; a[2] = w_lo.z; a[3] = w_lo.w;
         a[4] = w_hi.x; a[5] = w_hi.y; a[6] = w_hi.z; a[7] = w_hi.w;
@@ -129,15 +142,16 @@ __device__ __forceinline__ floatx4 mma_step(const u32x4 &w_lo, const u32x4 &w_hi
 template <int KIND, int SPW, int S = 0>
 struct FetchTile {
     static __device__ __forceinline__ void run(WItem (&w)[SPW], __amdgpu_buffer_rsrc_t r0,
-                                               __amdgpu_buffer_rsrc_t r1, uint32_t voff) {
-        load_w<KIND, S>(w[S], r0, r1, voff);
-        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff);
+                                               __amdgpu_buffer_rsrc_t r1, uint32_t voff,
+                                               const bool (&va)[SPW], const bool (&vb)[SPW]) {
+        load_w<KIND, S>(w[S], r0, r1, voff, va[S], vb[S]);
+        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff, va, vb);
     }
 };
 template <int KIND, int SPW>
 struct FetchTile<KIND, SPW, SPW> {
     static __device__ __forceinline__ void run(WItem (&)[SPW], __amdgpu_buffer_rsrc_t, __amdgpu_buffer_rsrc_t,
-                                               uint32_t) {}
+                                               uint32_t, const bool (&)[SPW], const bool (&)[SPW]) {}
 };
 
 // Activation-stationary streaming kernel.
@@ -169,8 +183,9 @@ small_gemm_kernel(SmallParams p) {
                                : (tiles_total - tile0 + tstride - 1) / tstride;
     floatx4 *slots = reinterpret_cast<floatx4 *>(lds);
     const __amdgpu_buffer_rsrc_t rs0 = weight_rsrc(p.W0, p.w_bytes);
-    const __amdgpu_buffer_rsrc_t rs1 = weight_rsrc(KIND == kNestedF16 ? p.W1 : p.W0, p.w_bytes);
-    const uint32_t tile_bytes = 16u * p.w_row_bytes;
+    const __amdgpu_buffer_rsrc_t rs1 = weight_rsrc(kind_is_nested(KIND) ? p.W1 : p.W0, p.w_bytes);
+    const uint32_t tile_bytes = p.tile_bytes;
+    typedef WLayout<KIND> L;
 
     // with several K passes this wave's partial tiles live in LDS and start at zero
     // (the spare slot of an odd T included)
@@ -185,11 +200,12 @@ small_gemm_kernel(SmallParams p) {
     // to its partial tiles in LDS.
     u32x4 xa[SPW][MT], xb[SPW][MT];
     uint32_t voff = 0;
+    bool va[SPW], vb[SPW];                            // this lane's columns of step s lie inside K
 
     auto fetch = [&](WItem (&w)[SPW], int tile) {
-        // past the last tile the offset is the end of the array: every lane is out of range
-        uint32_t toff = tile < T ? (uint32_t)(tile0 + tile * tstride) * tile_bytes : p.w_bytes;
-        FetchTile<KIND, SPW>::run(w, rs0, rs1, voff + toff);
+        // past the last tile every lane is sent out of range
+        const uint32_t base = tile < T ? voff + (uint32_t)(tile0 + tile * tstride) * tile_bytes : kDead;
+        FetchTile<KIND, SPW>::run(w, rs0, rs1, base, va, vb);
     };
     auto consume = [&](const WItem (&w)[SPW], int tile) {
         floatx4 acc[MT];
@@ -213,8 +229,13 @@ small_gemm_kernel(SmallParams p) {
     const int passes = MULTIPASS ? p.k_passes : 1;
     for (int pass = 0; pass < passes; ++pass) {
         const int k_wave = ((slice * passes + pass) * waves + wave) * (SPW * KSTEP) + KLANE * g;
-        if (KIND == kPlainF16) voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * 2u;
-        else voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * 1024u;   // block column of the slice
+        if (L::PACKED) voff = (uint32_t)lane * 16u + (uint32_t)((k_wave - KLANE * g) >> 6) * (1024u * L::EB);   // block column of the slice
+        else voff = (uint32_t)r16 * p.w_row_bytes + (uint32_t)k_wave * (uint32_t)L::EB;
+#pragma unroll
+        for (int s = 0; s < SPW; ++s) {
+            va[s] = k_wave + s * KSTEP < p.K;
+            vb[s] = kind_is_fp8(KIND) ? k_wave + s * KSTEP + 64 < p.K : va[s];
+        }
         if (KIND == kE4M3Quant) {
             // Fused activation quantisation (Sec. 2.2 per-token scaling; one token tile, the
             // workgroup covers all of K): every wave loads the FP16 activations of its own slice,
@@ -297,6 +318,27 @@ small_gemm_kernel(SmallParams p) {
     __syncthreads();
 
     // ---- fixed-order reduction over the waves of the workgroup -----------------------------
+    auto store_y = [&](floatx4 sum, int m, int n) {
+        if (kind_is_fp8(KIND)) {
+            float sc = (KIND == kE4M3Quant ? row_scale : p.scales[m]) * p.w_scale;
+            sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
+        }
+        uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
+        if (p.vec_store && n + 3 < p.N) {
+            u32x2 o;
+            o.x = float2_to_half2_bits(sum.x, sum.y);
+            o.y = float2_to_half2_bits(sum.z, sum.w);
+            *reinterpret_cast<u32x2 *>(dst) = o;
+        } else {
+            float v[4] = {sum.x, sum.y, sum.z, sum.w};
+            for (int q = 0; q < 4 && n + q < p.N; ++q) {
+                union { _Float16 f; uint16_t u; } cv;
+                cv.f = (_Float16)v[q];
+                dst[q] = cv.u;
+            }
+        }
+    };
+    const bool part_vec = (p.N & 3) == 0;
     for (int item = wave; item < T * MT; item += waves) {
         const int tile = item / MT, i = item - tile * MT;
         floatx4 sum = slots[((tile * waves) * MT + i) * 64 + lane];
@@ -309,33 +351,55 @@ small_gemm_kernel(SmallParams p) {
         if (m >= p.M || n >= p.N) continue;
         if (gridDim.y > 1) {
             float *dst = p.partials + ((int64_t)slice * p.M + m) * p.N + n;
-            if (n + 3 < p.N && (p.N & 3) == 0) {
+            if (part_vec) {
                 *reinterpret_cast<floatx4 *>(dst) = sum;
             } else {
                 float v[4] = {sum.x, sum.y, sum.z, sum.w};
                 for (int q = 0; q < 4 && n + q < p.N; ++q) dst[q] = v[q];
             }
         } else {
-            if (KIND == kE4M3 || KIND == kE4M3Quant) {
-                float sc = (KIND == kE4M3Quant ? row_scale : p.scales[m]) * p.w_scale;
-                sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
-            }
-            uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
-            if (p.vec_store && n + 3 < p.N) {
-                u32x2 o;
-                o.x = float2_to_half2_bits(sum.x, sum.y);
-                o.y = float2_to_half2_bits(sum.z, sum.w);
-                *reinterpret_cast<u32x2 *>(dst) = o;
-            } else {
-                float v[4] = {sum.x, sum.y, sum.z, sum.w};
-                for (int q = 0; q < 4 && n + q < p.N; ++q) {
-                    union { _Float16 f; uint16_t u; } cv;
-                    cv.f = (_Float16)v[q];
-                    dst[q] = cv.u;
-                }
-            }
+            store_y(sum, m, n);
         }
     }
+    if (gridDim.y == 1 || p.counters == nullptr) return;
+
+    // ---- grid-level K split finished by the last workgroup to arrive -------------------------
+    // Every workgroup of a tile column publishes its partial sums (release), then takes a ticket;
+    // the one that draws the last ticket (acquire) adds the slices in slice order -- the order of
+    // the stand-alone reduction kernel, so the result does not depend on who came last -- and
+    // leaves the counter at zero for the next launch.  Nobody waits for anybody.
+    __shared__ uint32_t ticket;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) ticket = atomicAdd(&p.counters[blockIdx.x], 1u);
+    __syncthreads();
+    if (ticket != gridDim.y - 1) return;
+    __threadfence();
+    const int64_t slice_elems = (int64_t)p.M * p.N;
+    for (int item = wave; item < T * MT; item += waves) {
+        const int tile = item / MT, i = item - tile * MT;
+        const int m = 16 * i + r16;
+        const int n = (tile0 + tile * tstride) * 16 + 4 * g;
+        if (m >= p.M || n >= p.N) continue;
+        const float *src = p.partials + (int64_t)m * p.N + n;
+        floatx4 sum;
+        if (part_vec) {
+            sum = *reinterpret_cast<const floatx4 *>(src);
+            for (int s2 = 1; s2 < (int)gridDim.y; ++s2) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(src + s2 * slice_elems);
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+        } else {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < 4 && n + q < p.N; ++q) {
+                v[q] = src[q];
+                for (int s2 = 1; s2 < (int)gridDim.y; ++s2) v[q] += src[s2 * slice_elems + q];
+            }
+            sum = floatx4{v[0], v[1], v[2], v[3]};
+        }
+        store_y(sum, m, n);
+    }
+    if (threadIdx.x == 0) p.counters[blockIdx.x] = 0u;
 }
 
 // Sums the S split-K partials in slice order, applies the FP8-mode scale, writes fp16.
@@ -397,8 +461,8 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const Tuning &t = tuning();
     SmallConfig c;
     c.mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-    if (kind == kE4M3Quant) kind = kE4M3;             // same launch shapes
-    const int kstep = (kind == kE4M3) ? 128 : 64;
+    const bool fp8 = kind_is_fp8(kind), nested = kind_class(kind) == 1;
+    const int kstep = fp8 ? 128 : 64;
     const int steps = (int)((K + kstep - 1) / kstep);
     // Row-major FP16 weights (the plain baseline) stream best in long runs per row: 8 K-steps per
     // wave (512 contiguous bytes of each row), 8 waves (measured: 8-10 % faster than 4 x 16);
@@ -411,7 +475,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     // otherwise 4, or 2 if that still lets one workgroup cover all of K
     c.spw = 4;
     if ((steps + 3) / 4 < 16 && steps >= 2) c.spw = 2;
-    if (tiles >= 1024 && kind != kNestedF16) c.spw = 2;
+    if (tiles >= 1024 && !nested) c.spw = 2;
     if ((t.small_spw == 2 || t.small_spw == 4)) c.spw = (int)t.small_spw;
     if (c.mt > 1) c.spw = 2;
     if (long_slices) c.spw = 8;
@@ -422,7 +486,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     // below 8*M*N floats).  What 16 waves x split do not cover is walked in passes.
     const int rounds = (slices + max_waves - 1) / max_waves;
     // E4M3 layers move half the bytes: half as many workgroups, unless K needs passes anyway
-    const int64_t wg_target = (kind == kE4M3 && rounds == 1) ? 512 : 1024;
+    const int64_t wg_target = (fp8 && rounds == 1) ? 512 : 1024;
     int split = 1;
     while (split < 8 && tiles * (split * 2) <= wg_target) split *= 2;
     // measured with packed planes: a single token tile whose K fits one pass is as fast
@@ -449,10 +513,10 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
 }
 
 bool small_gemm_supports(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) {
-    // the weight array must be addressable with 32-bit byte offsets (a few tiles of slack)
+    // the weight array must be addressable with 31-bit byte offsets (bit 31 marks a load as dead),
+    // a few tiles of slack included
     (void)M;
-    const int64_t row_bytes = (kind == kPlainF16) ? 2 * ldw : ((K + 63) / 64) * 64;
-    return (N + 48) * row_bytes < ((int64_t)1 << 32);
+    return weight_array_bytes(kind, N + 48, K, ldw) < ((int64_t)1 << 31);
 }
 
 size_t small_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
@@ -518,28 +582,33 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     SmallConfig c = choose_small(kind, a.M, a.N, a.K);
     SmallParams p;
     p.X = static_cast<const uint8_t *>(a.X);
-    p.x_row_bytes = (kind == kE4M3) ? a.ldx : 2 * a.ldx;
+    p.x_row_bytes = (kind == kE4M3 || kind == kE4M3Row) ? a.ldx : 2 * a.ldx;
     p.scales = a.scales;
     p.static_scale = a.static_scale;
     p.quant_hw = tuning().quant_hw != 0 ? 1 : 0;
     p.w_scale = a.w_scale;
     p.W0 = static_cast<const uint8_t *>(a.W0);
     p.W1 = static_cast<const uint8_t *>(a.W1);
-    if (kind == kPlainF16) {
-        p.w_row_bytes = (uint32_t)(2 * a.ldw);
-        p.w_bytes = (uint32_t)((a.N - 1) * (int64_t)p.w_row_bytes + 2 * a.K);
+    if (kind_is_packed(kind)) {
+        // 16 rows of a tile take 16 * Kp contiguous elements (Kp = K rounded up to 64)
+        p.w_row_bytes = 0;
+        p.tile_bytes = (uint32_t)(((a.K + 63) / 64) * 1024 * kind_elem_bytes(kind));
     } else {
-        // packed planes: 16 rows of a tile take 16 * Kp contiguous bytes (Kp = K rounded up to 64)
-        p.w_row_bytes = (uint32_t)(((a.K + 63) / 64) * 64);
-        p.w_bytes = (uint32_t)plane_bytes(a.N, a.K);
+        p.w_row_bytes = (uint32_t)(kind == kPlainF16 ? 2 * a.ldw : a.K);
+        p.tile_bytes = 16u * p.w_row_bytes;
     }
+    p.w_bytes = (uint32_t)weight_array_bytes(kind, a.N, a.K, a.ldw);
     p.M = (int)a.M;  p.N = (int)a.N;  p.K = (int)a.K;
     p.Y = a.Y;  p.ldy = a.ldy;
     p.partials = a.partials;
     p.tiles_per_wg = c.tiles_per_wg;
-    p.k_passes = c.passes;
     const int64_t tiles = (a.N + 15) / 16;
     const unsigned grid_x = (unsigned)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
+    // the last workgroup of a tile column sums the K slices itself where there is a counter for it
+    const bool fused_reduce = c.split > 1 && a.counters != nullptr && grid_x <= (unsigned)kMaxCounters &&
+                              tuning().fused_reduce != 0;
+    p.counters = fused_reduce ? a.counters : nullptr;
+    p.k_passes = c.passes;
     p.tile_stride = (tuning().small_interleave != 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;
     p.vec_store = ((a.N & 3) == 0 && (a.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 7) == 0) ? 1 : 0;
     if (c.split > 1 && (a.partials == nullptr ||
@@ -549,13 +618,17 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     if (kind == kE4M3Quant && !(c.mt == 1 && c.split == 1 && c.passes == 1)) return kErrArg;   // caller checks first
     switch (kind) {
         case kPlainF16: launch_small_k<kPlainF16>(p, c, grid, stream); break;
+        case kPlainF16Packed: launch_small_k<kPlainF16Packed>(p, c, grid, stream); break;
         case kNestedF16: launch_small_k<kNestedF16>(p, c, grid, stream); break;
+        case kNestedF16Row: launch_small_k<kNestedF16Row>(p, c, grid, stream); break;
         case kE4M3Quant: launch_small_quant(p, c, grid, stream); break;
-        default: launch_small_k<kE4M3>(p, c, grid, stream); break;
+        case kE4M3Row: launch_small_k<kE4M3Row>(p, c, grid, stream); break;
+        case kE4M3: launch_small_k<kE4M3>(p, c, grid, stream); break;
+        default: return kErrArg;
     }
     if (hipGetLastError() != hipSuccess) return kErrHip;
-    if (c.split > 1)
-        return launch_splitk_reduce(a.partials, c.split, a.M, a.N, kind == kE4M3 ? a.scales : nullptr,
+    if (c.split > 1 && !fused_reduce)
+        return launch_splitk_reduce(a.partials, c.split, a.M, a.N, kind_is_fp8(kind) ? a.scales : nullptr,
                                     a.w_scale, a.Y, a.ldy, stream);
     return kOk;
 }

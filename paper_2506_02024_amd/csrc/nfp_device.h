@@ -70,6 +70,23 @@ __device__ __forceinline__ uint32_t pack_even_bytes(uint32_t a, uint32_t b) {
     return byte_perm(b, a, 0x06040200u);
 }
 
+// 16 FP16 words (two 16-byte vectors) -> 16 upper bytes and 16 lower bytes, in order.
+__device__ __forceinline__ void decompose16(const u32x4 &a, const u32x4 &b, u32x4 &up, u32x4 &lo, uint32_t &bad) {
+    uint32_t u[8], l[8];
+    decompose2(a.x, u[0], l[0], bad);
+    decompose2(a.y, u[1], l[1], bad);
+    decompose2(a.z, u[2], l[2], bad);
+    decompose2(a.w, u[3], l[3], bad);
+    decompose2(b.x, u[4], l[4], bad);
+    decompose2(b.y, u[5], l[5], bad);
+    decompose2(b.z, u[6], l[6], bad);
+    decompose2(b.w, u[7], l[7], bad);
+    up.x = pack_even_bytes(u[0], u[1]);  lo.x = pack_even_bytes(l[0], l[1]);
+    up.y = pack_even_bytes(u[2], u[3]);  lo.y = pack_even_bytes(l[2], l[3]);
+    up.z = pack_even_bytes(u[4], u[5]);  lo.z = pack_even_bytes(l[4], l[5]);
+    up.w = pack_even_bytes(u[6], u[7]);  lo.w = pack_even_bytes(l[6], l[7]);
+}
+
 // ---- E4M3 encode (OCP "FN": bias 7, max 448, no Inf) from binary32 -----------------
 // Round-to-nearest-even in integer arithmetic; |r| must already be clamped to <= 448.
 __device__ __forceinline__ uint32_t e4m3_from_float_sw(float r) {

@@ -12,8 +12,34 @@ enum { kOk = 0, kErrArg = 1, kErrShape = 2, kErrRange = 3, kErrWorkspace = 4, kE
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? kOk : kErrHip; }
 
 // weight operand kinds of the GEMM kernels
-// kE4M3Quant: packed E4M3 weights, FP16 activations quantised per token inside the kernel
-enum WeightKind { kPlainF16 = 0, kNestedF16 = 1, kE4M3 = 2, kE4M3Quant = 3 };
+//   kPlainF16      : FP16 weights, row-major [N,K] (row stride ldw)
+//   kNestedF16     : the two byte planes in packed 1 KB blocks
+//   kE4M3          : E4M3 bytes (the upper plane) in packed 1 KB blocks
+//   kE4M3Quant     : as kE4M3, FP16 activations quantised per token inside the kernel
+//   kNestedF16Row  : the two byte planes row-major [N,K], regrouped into operand order in flight
+//   kE4M3Row       : E4M3 bytes row-major [N,K]
+//   kPlainF16Packed: FP16 weights in packed 2 KB blocks (the like-for-like partner of kNestedF16)
+enum WeightKind { kPlainF16 = 0, kNestedF16 = 1, kE4M3 = 2, kE4M3Quant = 3,
+                  kNestedF16Row = 4, kE4M3Row = 5, kPlainF16Packed = 6, kNumKinds = 7 };
+
+constexpr bool kind_is_fp8(int k) { return k == kE4M3 || k == kE4M3Quant || k == kE4M3Row; }
+constexpr bool kind_is_nested(int k) { return k == kNestedF16 || k == kNestedF16Row; }
+// weights stored in blocks of 16 rows x 64 columns, lane order inside
+constexpr bool kind_is_packed(int k) { return k == kNestedF16 || k == kE4M3 || k == kE4M3Quant || k == kPlainF16Packed; }
+// bytes of one weight in the array(s) the kernel reads
+constexpr int kind_elem_bytes(int k) { return (k == kPlainF16 || k == kPlainF16Packed) ? 2 : 1; }
+// which cost table / routing rule a kind follows: 0 plain FP16 through LDS, 1 FP16 operands through
+// registers (both plane layouts, packed FP16), 2 E4M3
+constexpr int kind_class(int k) { return k == kPlainF16 ? 0 : (kind_is_fp8(k) ? 2 : 1); }
+
+// bytes of one weight array of an [N,K] layer as the kernels address it (plain row-major FP16:
+// row stride ldw elements; row-major planes are dense; packed kinds are padded to whole blocks)
+inline int64_t weight_array_bytes(int kind, int64_t N, int64_t K, int64_t ldw) {
+    if (N <= 0) return 0;
+    if (kind_is_packed(kind)) return ((N + 15) / 16 * 16) * ((K + 63) / 64 * 64) * kind_elem_bytes(kind);
+    if (kind == kPlainF16) return (N - 1) * 2 * ldw + 2 * K;
+    return N * K;
+}
 
 struct GemmArgs {
     // activations: fp16 X (kPlainF16 / kNestedF16) or E4M3 Xq with per-row scales (kE4M3)
@@ -31,7 +57,12 @@ struct GemmArgs {
     int64_t ldy;
     float *partials;      // split-K scratch (may be NULL if split == 1)
     size_t partial_bytes;
+    uint32_t *counters;   // kMaxCounters arrival counters, all zero between calls (NULL: reduce in a second launch)
 };
+
+// arrival counters at the start of every workspace: one per output tile of a split launch
+constexpr int kMaxCounters = 4096;
+constexpr size_t kCounterBytes = kMaxCounters * sizeof(uint32_t);
 
 // tuning knobs (negative = built-in choice)
 struct Tuning {
@@ -47,16 +78,19 @@ struct Tuning {
     int64_t small_fuse_quant;  // 1: quantise activations inside the streaming kernel where it can
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
     int64_t large_xcd_map;   // 0: tiles in launch order instead of grouped by XCD (tiled kernels)
+    int64_t fused_reduce;    // 0: split-K partials are summed by a second launch instead of the last workgroup
 };
 Tuning &tuning();
 
 int launch_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *upper,
-                     uint8_t *lower, uint64_t *counter, hipStream_t stream);
+                     uint8_t *lower, uint64_t *counter, bool packed, hipStream_t stream);
 int launch_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint64_t *counter,
                        hipStream_t stream);
 int launch_zero_u64(uint64_t *p, hipStream_t stream);
 int launch_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
-                       uint16_t *W, int64_t ldw, hipStream_t stream);
+                       uint16_t *W, int64_t ldw, bool packed, hipStream_t stream);
+int launch_pack_fp16(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *dst, hipStream_t stream);
+int launch_zero_words(uint32_t *p, int n, hipStream_t stream);
 size_t plane_bytes(int64_t N, int64_t K);
 int launch_pack_plane(const uint8_t *src, int64_t N, int64_t K, int64_t ld, uint8_t *dst, hipStream_t stream);
 int launch_unpack_plane(const uint8_t *src, int64_t N, int64_t K, uint8_t *dst, int64_t ld, hipStream_t stream);
@@ -73,6 +107,11 @@ int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream);
 
 int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, const float *scales,
                          float w_scale, uint16_t *Y, int64_t ldy, hipStream_t stream);
+
+bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw);
+int launch_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
+int launch_probe_mfma(const void *operands, int fp8, int iters, uint32_t *sink, double *flops_host,
+                      hipStream_t stream);
 
 bool use_small_gemm(int64_t M);
 

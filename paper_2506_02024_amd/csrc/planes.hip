@@ -1,6 +1,8 @@
 // Element-wise kernels of the NestedFP format (Sec. 4.1): applicability count,
 // decomposition into byte planes, lossless reconstruction.  All three are HBM-bound:
-// every lane moves 16 weights per step with 128-bit loads and stores.
+// every lane moves 16 weights per step with 128-bit loads and stores.  The planes are
+// row-major [N,K] byte matrices (the two tensors of Sec. 4 "Overview" as they are); the
+// packed form below is an optional pre-pack of the same bytes for the GEMM kernels.
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -68,19 +70,7 @@ decompose_kernel(const uint16_t *__restrict__ W, int64_t ldw, BlockMap map,
             const u32x4 *src = reinterpret_cast<const u32x4 *>(W + c.row * ldw + c.col);
             u32x4 a = __builtin_nontemporal_load(src);
             u32x4 b = __builtin_nontemporal_load(src + 1);
-            uint32_t u[8], l[8];
-            decompose2(a.x, u[0], l[0], bad);
-            decompose2(a.y, u[1], l[1], bad);
-            decompose2(a.z, u[2], l[2], bad);
-            decompose2(a.w, u[3], l[3], bad);
-            decompose2(b.x, u[4], l[4], bad);
-            decompose2(b.y, u[5], l[5], bad);
-            decompose2(b.z, u[6], l[6], bad);
-            decompose2(b.w, u[7], l[7], bad);
-            up.x = pack_even_bytes(u[0], u[1]);  lo.x = pack_even_bytes(l[0], l[1]);
-            up.y = pack_even_bytes(u[2], u[3]);  lo.y = pack_even_bytes(l[2], l[3]);
-            up.z = pack_even_bytes(u[4], u[5]);  lo.z = pack_even_bytes(l[4], l[5]);
-            up.w = pack_even_bytes(u[6], u[7]);  lo.w = pack_even_bytes(l[6], l[7]);
+            decompose16(a, b, up, lo, bad);
         }
         __builtin_nontemporal_store(up, reinterpret_cast<u32x4 *>(upper + c.offset));
         __builtin_nontemporal_store(lo, reinterpret_cast<u32x4 *>(lower + c.offset));
@@ -134,6 +124,66 @@ reconstruct_kernel(const uint8_t *__restrict__ upper, const uint8_t *__restrict_
     }
 }
 
+// ---- row-major planes: chunk c (16 weights) of the matrix is row c / (K/16), columns 16 * (c % (K/16)) .. +15
+__global__ void __launch_bounds__(kPlaneThreads)
+decompose_rows_kernel(const uint16_t *__restrict__ W, int64_t ldw, ChunkMap map, int64_t K,
+                      uint8_t *__restrict__ upper, uint8_t *__restrict__ lower,
+                      uint64_t *__restrict__ counter) {
+    uint32_t bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * kPlaneThreads;
+    for (int64_t c = (int64_t)blockIdx.x * kPlaneThreads + threadIdx.x; c < map.total; c += stride) {
+        const int64_t row = c / map.chunks_per_row;
+        const int64_t col = (c - row * map.chunks_per_row) * 16;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(W + row * ldw + col);
+        const u32x4 a = __builtin_nontemporal_load(src);
+        const u32x4 b = __builtin_nontemporal_load(src + 1);
+        u32x4 up, lo;
+        decompose16(a, b, up, lo, bad);
+        __builtin_nontemporal_store(up, reinterpret_cast<u32x4 *>(upper + row * K + col));
+        __builtin_nontemporal_store(lo, reinterpret_cast<u32x4 *>(lower + row * K + col));
+    }
+    if (counter) add_count(counter, bad);
+}
+
+__global__ void __launch_bounds__(kPlaneThreads)
+reconstruct_rows_kernel(const uint8_t *__restrict__ upper, const uint8_t *__restrict__ lower,
+                        ChunkMap map, int64_t K, uint16_t *__restrict__ W, int64_t ldw) {
+    const int64_t stride = (int64_t)gridDim.x * kPlaneThreads;
+    for (int64_t c = (int64_t)blockIdx.x * kPlaneThreads + threadIdx.x; c < map.total; c += stride) {
+        const int64_t row = c / map.chunks_per_row;
+        const int64_t col = (c - row * map.chunks_per_row) * 16;
+        const u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(upper + row * K + col));
+        const u32x4 l = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(lower + row * K + col));
+        u32x4 w0, w1;
+        merge16(u, l, w0, w1);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(W + row * ldw + col);
+        __builtin_nontemporal_store(w0, dst);
+        __builtin_nontemporal_store(w1, dst + 1);
+    }
+}
+
+// FP16 weights in packed storage: one 2 KB block per 16-row x 64-column sub-matrix, made of two
+// halves of 1 KB; lane l (row l % 16, column group l / 16) owns chunk l of each half: columns
+// 16 g .. 16 g + 7 in the first, 16 g + 8 .. 16 g + 15 in the second -- what a lane of the
+// NestedFP kernels holds after merging its 16 bytes of each plane.  Padding is zero.
+__global__ void __launch_bounds__(kPlaneThreads)
+pack_fp16_kernel(const uint16_t *__restrict__ W, int64_t ldw, BlockMap map, uint8_t *__restrict__ dst) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kPlaneThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPlaneThreads) >> 6;
+    for (int64_t blk = wave; blk < map.blocks; blk += waves) {
+        const LaneChunk c = lane_chunk(map, blk, lane);
+        u32x4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+        if (c.inside) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(W + c.row * ldw + c.col);
+            a = __builtin_nontemporal_load(src);
+            b = __builtin_nontemporal_load(src + 1);
+        }
+        __builtin_nontemporal_store(a, reinterpret_cast<u32x4 *>(dst + blk * 2048 + lane * 16));
+        __builtin_nontemporal_store(b, reinterpret_cast<u32x4 *>(dst + blk * 2048 + 1024 + lane * 16));
+    }
+}
+
 // Row-major bytes <-> packed plane (for E4M3 weights that do not come from a decomposition,
 // and for reading a plane back in matrix order).
 template <bool PACK>
@@ -156,6 +206,17 @@ repack_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst, int64_
 
 __global__ void zero_u64_kernel(uint64_t *p) { *p = 0; }
 
+__global__ void zero_words_kernel(uint32_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+int launch_zero_words(uint32_t *p, int n, hipStream_t stream) {
+    if (n <= 0) return kOk;
+    zero_words_kernel<<<(n + 255) / 256, 256, 0, stream>>>(p, n);
+    return hip_ok(hipGetLastError());
+}
+
 int launch_zero_u64(uint64_t *p, hipStream_t stream) {
     zero_u64_kernel<<<1, 1, 0, stream>>>(p);
     return hip_ok(hipGetLastError());
@@ -174,11 +235,17 @@ size_t plane_bytes(int64_t N, int64_t K) {
 }
 
 int launch_decompose(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *upper,
-                     uint8_t *lower, uint64_t *counter, hipStream_t stream) {
-    BlockMap map = block_map(N, K);
+                     uint8_t *lower, uint64_t *counter, bool packed, hipStream_t stream) {
     if (counter) zero_u64_kernel<<<1, 1, 0, stream>>>(counter);
-    decompose_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(W, ldw, map, upper, lower,
-                                                                              counter);
+    if (packed) {
+        BlockMap map = block_map(N, K);
+        decompose_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(W, ldw, map, upper, lower,
+                                                                                  counter);
+    } else {
+        ChunkMap map{K / 16, N * (K / 16)};
+        decompose_rows_kernel<<<plane_grid(map.total), kPlaneThreads, 0, stream>>>(W, ldw, map, K, upper, lower,
+                                                                                 counter);
+    }
     return hip_ok(hipGetLastError());
 }
 
@@ -191,9 +258,20 @@ int launch_range_check(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uin
 }
 
 int launch_reconstruct(const uint8_t *upper, const uint8_t *lower, int64_t N, int64_t K,
-                       uint16_t *W, int64_t ldw, hipStream_t stream) {
+                       uint16_t *W, int64_t ldw, bool packed, hipStream_t stream) {
+    if (packed) {
+        BlockMap map = block_map(N, K);
+        reconstruct_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(upper, lower, map, W, ldw);
+    } else {
+        ChunkMap map{K / 16, N * (K / 16)};
+        reconstruct_rows_kernel<<<plane_grid(map.total), kPlaneThreads, 0, stream>>>(upper, lower, map, K, W, ldw);
+    }
+    return hip_ok(hipGetLastError());
+}
+
+int launch_pack_fp16(const uint16_t *W, int64_t N, int64_t K, int64_t ldw, uint8_t *dst, hipStream_t stream) {
     BlockMap map = block_map(N, K);
-    reconstruct_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(upper, lower, map, W, ldw);
+    pack_fp16_kernel<<<plane_grid(map.blocks * 64), kPlaneThreads, 0, stream>>>(W, ldw, map, dst);
     return hip_ok(hipGetLastError());
 }
 

@@ -49,10 +49,78 @@ def pack_plane_ref(a):
     return np.ascontiguousarray(p.transpose(0, 2, 3, 1, 4)).reshape(-1)
 
 
+def pack_fp16_ref(w):
+    """Packed FP16 storage written out from its definition: 2 KB blocks of 16 rows x 64 columns,
+    each made of two halves of 1 KB; chunk r + 16 g of half h holds columns 16 g + 8 h .. + 7 of
+    row r (8 FP16 words); rows and columns past the matrix are zero."""
+    w = np.asarray(w).view(np.uint16)
+    N, K = w.shape
+    Np, Kp = -(-N // 16) * 16, -(-K // 64) * 64
+    p = np.zeros((Np, Kp), dtype=np.uint16)
+    p[:N, :K] = w
+    p = p.reshape(Np // 16, 16, Kp // 64, 4, 2, 8)      # i, r, j, g, h, word
+    return np.ascontiguousarray(p.transpose(0, 2, 4, 3, 1, 5)).reshape(-1).view(np.uint8)
+
+
 def assert_plane_equal(plane, ref):
-    """plane: PackedPlane from the library; ref: row-major uint8 [N,K] from the oracle.
-    Checks the raw packed bytes (padding included) and the library's own unpacking."""
-    want = pack_plane_ref(ref)
-    got = plane.data[:want.size].cpu().numpy()
-    assert np.array_equal(got, want)
-    assert np.array_equal(plane.unpack().cpu().numpy(), np.asarray(ref, dtype=np.uint8))
+    """plane: what the library wrote -- a row-major uint8 [N,K] tensor (compared with the
+    oracle's array as it is) or a PackedPlane (raw packed bytes, padding included, against the
+    layout's definition, and the library's own unpacking); ref: row-major uint8 [N,K] from the
+    oracle."""
+    ref = np.asarray(ref, dtype=np.uint8)
+    if hasattr(plane, "unpack"):
+        want = pack_plane_ref(ref)
+        got = plane.data[:want.size].cpu().numpy()
+        assert np.array_equal(got, want)
+        assert np.array_equal(plane.unpack().cpu().numpy(), ref)
+    else:
+        assert tuple(plane.shape) == ref.shape
+        assert np.array_equal(plane.cpu().numpy(), ref)
+
+
+def structured_sample(M, N, seed=0, full_rows=4, full_cols=4, band_rows=128, band_cols=256):
+    """Which outputs of a full-size [M,N] result are compared with the oracle: a few complete rows
+    (all N), a few complete columns (all M), and the first and last row / column of every 64-row
+    and 128-column band (the edges of every tile shape the kernels use), thinned to band_rows x
+    band_cols by a seeded choice that keeps the first and last band.  Returns three (rows, cols)
+    pairs of sorted index arrays."""
+    rng = np.random.default_rng(4099 + seed)
+    full_rows = max(full_rows, -(-32768 // max(N, 1)))          # at least 2^15 outputs in the complete rows alone
+
+    def pick(n, k, always):
+        k = min(k, n)
+        rest = np.setdiff1d(np.arange(n), always)
+        extra = rng.choice(rest, size=max(0, k - len(always)), replace=False) if len(rest) else []
+        return np.unique(np.concatenate([np.asarray(always, dtype=np.int64), np.asarray(extra, dtype=np.int64)]))
+
+    def edges(n, band):
+        e = np.unique(np.concatenate([np.arange(0, n, band), np.minimum(np.arange(0, n, band) + band - 1, n - 1)]))
+        return e
+
+    rows_full = pick(M, full_rows, [0, M - 1] if M > 1 else [0])
+    cols_full = pick(N, full_cols, [0, N - 1] if N > 1 else [0])
+    er, ec = edges(M, 64), edges(N, 128)
+    keep_r = np.unique(np.concatenate([er[:2], er[-2:]]))
+    keep_c = np.unique(np.concatenate([ec[:2], ec[-2:]]))
+    rows_band = er if len(er) <= band_rows else np.unique(np.concatenate([keep_r, rng.choice(er, band_rows - len(keep_r), replace=False)]))
+    cols_band = ec if len(ec) <= band_cols else np.unique(np.concatenate([keep_c, rng.choice(ec, band_cols - len(keep_c), replace=False)]))
+    return [(rows_full, np.arange(N)), (np.arange(M), cols_full), (rows_band, cols_band)]
+
+
+def decompose_ref(W, workers=16):
+    """oracle.decompose over row blocks of W on a few host threads (the oracle is called as it
+    stands; ctypes releases the interpreter lock during the call).  Returns (upper, lower, bad)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+
+    W = np.asarray(W)
+    N = W.shape[0]
+    workers = max(1, min(workers, os.cpu_count() or 1, (N + 255) // 256))
+    if workers == 1:
+        return oracle.decompose(W)
+    bounds = np.linspace(0, N, workers + 1).astype(np.int64)
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        parts = list(pool.map(lambda i: oracle.decompose(W[bounds[i]:bounds[i + 1]]), range(workers)))
+    return (np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts]), sum(p[2] for p in parts))

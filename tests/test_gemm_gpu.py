@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2506_02024_amd import workloads
-from helpers import assert_gemm_close, assert_plane_equal, bits, to_dev
+from helpers import assert_gemm_close, assert_plane_equal, bits, decompose_ref, structured_sample, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -17,41 +17,58 @@ def nfp():
     return binding
 
 
-def run_both_modes(nfp, X, W, what, check_plain=True):
-    """Runs decompose + FP16 mode + FP8 mode on the GPU and checks all against the oracle."""
+def run_both_modes(nfp, X, W, what, check_plain=True, layouts=(False, True)):
+    """Runs decompose + FP16 mode + FP8 mode on the GPU, over row-major planes and over packed
+    ones, and checks all of it against the oracle."""
     Xd, Wd = to_dev(X), to_dev(W)
-    up, lo = nfp.decompose(Wd)
     up_ref, lo_ref, bad = oracle.decompose(W)
     assert bad == 0
-    assert_plane_equal(up, up_ref)
-    assert_plane_equal(lo, lo_ref)
-    # FP16 mode
-    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
     ref16 = oracle.gemm_fp16(X, W)
-    assert_gemm_close(y16.cpu().numpy(), ref16, what + " FP16 mode")
+    Xq, s = oracle.quantize_act(X)
+    ref8 = oracle.gemm_fp8(Xq, s, up_ref)
+    outs = {}
+    for packed in layouts:
+        tag = "%s, %s planes" % (what, "packed" if packed else "row-major")
+        up, lo = nfp.decompose(Wd, packed=packed)
+        assert_plane_equal(up, up_ref)
+        assert_plane_equal(lo, lo_ref)
+        y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+        assert_gemm_close(y16.cpu().numpy(), ref16, tag + " FP16 mode")
+        # FP8 mode: lower plane is not passed at all
+        y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
+        assert_gemm_close(y8.cpu().numpy(), ref8, tag + " FP8 mode")
+        if check_plain:
+            yp8 = nfp.plain_gemm_fp8(Xd, up, 2.0 ** -8)
+            assert np.array_equal(bits(yp8), bits(y8)), tag + ": FP8 mode differs from the plain fp8 GEMM"
+        outs[packed] = (y16, y8, up, lo)
+    if len(outs) == 2:
+        # the launch shape is chosen by the kind of weights, not by their storage order, and a
+        # lane holds the same 16 columns either way: same bits
+        assert np.array_equal(bits(outs[False][0]), bits(outs[True][0])), what + ": FP16 mode differs between the layouts"
+        assert np.array_equal(bits(outs[False][1]), bits(outs[True][1])), what + ": FP8 mode differs between the layouts"
     if check_plain:
-        # same launch shape for both kernels (tile shape and K split of the tiled ones, K-steps per
-        # wave of the streaming ones): then the sums run in the same order
+        if True in outs:
+            # FP16 weights in packed storage go through the kernel of FP16 mode minus the merge, in
+            # the launch shape chosen for it: bit-identical with no knob pinned
+            yp = nfp.plain_gemm_fp16(Xd, nfp.pack_fp16(Wd))
+            assert np.array_equal(bits(yp), bits(outs[True][0])), what + ": FP16 mode differs from the plain GEMM on packed FP16"
+        # row-major FP16 weights take kernels of their own; with the same launch shape for both
+        # (tile shape and K split of the tiled ones, K-steps per wave of the streaming ones) the
+        # sums run in the same order
         pins = {"large_bm": 128, "large_bn": 256, "large_split": 2, "small_spw": 4}
         for k, v in pins.items():
             nfp.tune(k, v)
         try:
             yp = nfp.plain_gemm_fp16(Xd, Wd)
-            yn = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
+            any_layout = next(iter(outs.values()))
+            yn = nfp.gemm(Xd, any_layout[2], any_layout[3], nfp.MODE_FP16)
         finally:
             for k in pins:
                 nfp.tune(k, -1)
         assert np.array_equal(bits(yp), bits(yn)), what + ": FP16 mode differs from the plain fp16 GEMM"
         assert_gemm_close(yn.cpu().numpy(), ref16, what + " FP16 mode, pinned launch shape")
-    # FP8 mode: lower plane is not passed at all
-    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
-    Xq, s = oracle.quantize_act(X)
-    ref8 = oracle.gemm_fp8(Xq, s, up_ref)
-    assert_gemm_close(y8.cpu().numpy(), ref8, what + " FP8 mode")
-    if check_plain:
-        yp8 = nfp.plain_gemm_fp8(Xd, up, 2.0 ** -8)
-        assert np.array_equal(bits(yp8), bits(y8)), what + ": FP8 mode differs from the plain fp8 GEMM"
-    return y16, y8
+    first = next(iter(outs.values()))
+    return first[0], first[1]
 
 
 def test_config1_single_linear(nfp):
@@ -85,11 +102,11 @@ def test_replayed_graph_on_a_side_stream_equals_eager_calls(nfp, M):
     # eager work and new activations in between, must give what the eager calls give
     N, K = 16384 + 72, 1024 + 64
     W = workloads.weight_host(N, K, seed=M)
-    up, lo = nfp.decompose(to_dev(W))
+    up, lo = nfp.decompose(to_dev(W), packed=(M != 64))
     X = to_dev(workloads.act_host(M, K, seed=M + 1))
     Y16 = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
     Y8 = torch.empty_like(Y16)
-    ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dtype=torch.uint8, device="cuda:0")
+    ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, "cuda:0")
 
     def both():
         nfp.gemm(X, up, lo, nfp.MODE_FP16, out=Y16, workspace=ws)
@@ -117,14 +134,14 @@ def test_replayed_graph_on_a_side_stream_equals_eager_calls(nfp, M):
 
 
 def test_calls_on_two_streams_do_not_interfere(nfp):
-    # the library holds no device state: two streams, each with its own workspace and output,
+    # the library holds no device state of its own: two streams, each with its own workspace and output,
     # run different problems at the same time and get what they get alone
     probs = []
     for j, (M, N, K) in enumerate([(16, 4096 + 8, 14336), (200, 2048 + 24, 1024)]):
         W = workloads.weight_host(N, K, seed=60 + j)
-        up, lo = nfp.decompose(to_dev(W))
+        up, lo = nfp.decompose(to_dev(W), packed=(j == 0))
         X = to_dev(workloads.act_host(M, K, seed=70 + j))
-        ws = torch.empty(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, dtype=torch.uint8, device="cuda:0")
+        ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, "cuda:0")
         alone = (nfp.gemm(X, up, lo, nfp.MODE_FP16, workspace=ws).clone(), nfp.gemm(X, up, None, nfp.MODE_FP8, workspace=ws).clone())
         outs = (torch.empty_like(alone[0]), torch.empty_like(alone[1]))
         probs.append((X, up, lo, ws, alone, outs, torch.cuda.Stream()))
@@ -270,7 +287,7 @@ def test_xcd_grouped_tile_order_changes_nothing(nfp, M, N, K, bm, bn):
     W = workloads.weight_host(N, K, seed=430)
     X = workloads.act_host(M, K, seed=431)
     Xd, Wd = to_dev(X), to_dev(W)
-    up, lo = nfp.decompose(Wd)
+    up, lo = nfp.decompose(Wd, packed=(bm == 256))
     pins = {"large_bm": bm, "large_bn": bn, "large_split": 1}
     outs = {}
     for order in (0, -1):
@@ -316,15 +333,16 @@ def test_one_hot_tokens_return_weights_exactly(nfp):
 def test_fp8_mode_never_reads_the_lower_plane(nfp):
     W = workloads.weight_host(256, 512, seed=5)
     Wd = to_dev(W)
-    up, lo = nfp.decompose(Wd)
-    for M in (8, 200):
-        X = to_dev(workloads.act_host(M, 512, seed=6))
-        a = nfp.gemm(X, up, None, nfp.MODE_FP8)
-        junk = nfp.PackedPlane(lo.N, lo.K, data=torch.full_like(lo.data, 0xAB))
-        b = nfp.gemm(X, up, junk, nfp.MODE_FP8)
-        assert np.array_equal(bits(a), bits(b))
-    with pytest.raises(nfp.NestedFPError):
-        nfp.gemm(X, up, None, nfp.MODE_FP16)
+    for packed in (False, True):
+        up, lo = nfp.decompose(Wd, packed=packed)
+        for M in (8, 200):
+            X = to_dev(workloads.act_host(M, 512, seed=6))
+            a = nfp.gemm(X, up, None, nfp.MODE_FP8)
+            junk = nfp.PackedPlane(lo.N, lo.K, data=torch.full_like(lo.data, 0xAB)) if packed else torch.full_like(lo, 0xAB)
+            b = nfp.gemm(X, up, junk, nfp.MODE_FP8)
+            assert np.array_equal(bits(a), bits(b))
+        with pytest.raises(nfp.NestedFPError):
+            nfp.gemm(X, up, None, nfp.MODE_FP16)
 
 
 def test_static_activation_scale_and_prequantized_entry(nfp):
@@ -341,6 +359,8 @@ def test_static_activation_scale_and_prequantized_entry(nfp):
     y2 = nfp.gemm_fp8_prequantized(Xq_d, s_d, up)
     y3 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
     assert np.array_equal(bits(y2), bits(y3))
+    y4 = nfp.gemm_fp8_prequantized(Xq_d, s_d, nfp.pack_plane(up))
+    assert np.array_equal(bits(y4), bits(y3))
 
 
 def test_strided_activations_and_output(nfp):
@@ -379,9 +399,8 @@ def test_mode_switch_keeps_planes_and_memory(nfp):
         del W
     X = to_dev(workloads.act_host(64, 1024, seed=50))
     out = torch.empty((64, 512), dtype=torch.float16, device="cuda:0")
-    ws = torch.empty(max(nfp.gemm_workspace_size(64, 512, 1024, m) for m in (0, 1)), dtype=torch.uint8,
-                     device="cuda:0")
-    snap = [(u.data.clone(), l.data.clone()) for u, l in layers]
+    ws = nfp.new_workspace(max(nfp.gemm_workspace_size(64, 512, 1024, m) for m in (0, 1)), "cuda:0")
+    snap = [(u.clone(), l.clone()) for u, l in layers]
     ptrs = [(u.data_ptr(), l.data_ptr()) for u, l in layers]
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
@@ -393,7 +412,7 @@ def test_mode_switch_keeps_planes_and_memory(nfp):
     assert torch.cuda.memory_allocated() == before
     assert ptrs == [(u.data_ptr(), l.data_ptr()) for u, l in layers]
     for (u, l), (su, sl) in zip(layers, snap):
-        assert torch.equal(u.data, su) and torch.equal(l.data, sl)
+        assert torch.equal(u, su) and torch.equal(l, sl)
 
 
 @pytest.mark.parametrize("name,M", [("qkv", 16), ("down", 4), ("o", 64), ("gate_up", 1)])
@@ -404,95 +423,97 @@ def test_llama8b_decode_shapes_full_output(nfp, name, M):
     run_both_modes(nfp, X, W, "%s M=%d" % (name, M), check_plain=(name != "gate_up"))
 
 
-@pytest.mark.parametrize("name,M", [("qkv", 2048), ("down", 512), ("gate_up", 8192)])
-def test_llama8b_prefill_shapes_sampled(nfp, name, M):
-    # full-size launch as bench.py times it; oracle evaluated on a seeded sample of outputs
-    N, K = workloads.LLAMA3_8B[name]
-    Wd = workloads.weight_device(N, K, seed=11)
-    Xd = workloads.act_device(M, K, seed=12)
-    up, lo = nfp.decompose(Wd)
-    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
-    # with the same tile shape and K split FP16 mode and the plain FP16 GEMM agree bit for bit
-    pins = {"large_bm": 256, "large_bn": 256, "large_split": 2 if name == "down" else 1}
-    for k, v in pins.items():
-        nfp.tune(k, v)
-    try:
-        assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd))
-    finally:
-        for k in pins:
-            nfp.tune(k, -1)
-    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
-    rows, cols = workloads.sample_indices(M, N, 24, 96, seed=M)
-    Xs = Xd[torch.from_numpy(rows).cuda()].cpu().numpy()
-    Ws = Wd[torch.from_numpy(cols).cuda()].cpu().numpy()
-    ref16 = oracle.gemm_fp16(Xs, Ws)
-    got16 = y16[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
-    assert_gemm_close(got16, ref16, "%s M=%d FP16 sample" % (name, M))
-    up_s, _, bad = oracle.decompose(Ws)
-    assert bad == 0
-    assert np.array_equal(up.unpack()[torch.from_numpy(cols).cuda()].cpu().numpy(), up_s)
-    Xq, s = oracle.quantize_act(Xs)
-    ref8 = oracle.gemm_fp8(Xq, s, up_s)
-    got8 = y8[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy()
-    assert_gemm_close(got8, ref8, "%s M=%d FP8 sample" % (name, M))
-
-
-def _sampled_full_size_check(nfp, N, K, M, sigma, tag, seed):
-    """Full-size launch; planes and both GEMM modes checked on a seeded sample of rows/columns."""
+def _full_size_check(nfp, N, K, Ms, sigma, tag, seed, pin_sets=None):
+    """Full-size launches in the built-in launch shapes (what bench.py times), both plane layouts.
+    Planes: every byte against the oracle.  Both GEMM modes: against the oracle on a structured
+    sample of at least 2^15 outputs per batch size -- complete rows, complete columns and the
+    first and last row / column of the tile bands (helpers.structured_sample); the whole output
+    of FP16 mode bit for bit against the plain FP16 GEMM on packed weights (same kernel minus
+    Alg. 1) and, under pinned launch shapes, against the plain GEMM on row-major weights."""
     Wd = workloads.weight_device(N, K, sigma, seed=seed)
-    Xd = workloads.act_device(M, K, seed=seed + 1)
-    up, lo = nfp.decompose(Wd)
-    y16 = nfp.gemm(Xd, up, lo, nfp.MODE_FP16)
-    # same kernel family and launch shape for both: then FP16 mode and the plain FP16 GEMM agree bit for bit
-    pin_sets = [{"small_max_m": 64, "small_spw": 4}] if M <= 64 else [{"large_bm": 256, "large_bn": 256, "large_split": 1}]
-    if 32 < M <= 64:
-        pin_sets.append({"small_max_m": 0, "large_bm": 64, "large_split": 4})      # 64-token tiles of the tiled kernels
-    for pins in pin_sets:
-        for k, v in pins.items():
-            nfp.tune(k, v)
-        try:
-            assert torch.equal(nfp.gemm(Xd, up, lo, nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd)), \
-                tag + ": FP16 mode differs from plain fp16 under %s" % pins
-        finally:
-            for k in pins:
-                nfp.tune(k, -1)
-    y8 = nfp.gemm(Xd, up, None, nfp.MODE_FP8)
-    rows, cols = workloads.sample_indices(M, N, 16, 64, seed=seed)
-    ri, ci = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
-    Xs, Ws = Xd[ri].cpu().numpy(), Wd[ci].cpu().numpy()
-    up_s, lo_s, bad = oracle.decompose(Ws)
+    W = Wd.cpu().numpy()
+    up_ref, lo_ref, bad = decompose_ref(W)
     assert bad == 0
-    assert np.array_equal(up.unpack()[ci].cpu().numpy(), up_s) and np.array_equal(lo.unpack()[ci].cpu().numpy(), lo_s)
-    assert_gemm_close(y16[ri][:, ci].cpu().numpy(), oracle.gemm_fp16(Xs, Ws), tag + " FP16 sample")
-    Xq, s = oracle.quantize_act(Xs)
-    assert_gemm_close(y8[ri][:, ci].cpu().numpy(), oracle.gemm_fp8(Xq, s, up_s), tag + " FP8 sample")
+    planes = {}
+    for packed in (False, True):
+        up, lo = nfp.decompose(Wd, packed=packed)
+        if packed:
+            assert np.array_equal(up.unpack().cpu().numpy(), up_ref) and np.array_equal(lo.unpack().cpu().numpy(), lo_ref)
+        else:
+            assert np.array_equal(up.cpu().numpy(), up_ref) and np.array_equal(lo.cpu().numpy(), lo_ref)
+        planes[packed] = (up, lo)
+    Wp = nfp.pack_fp16(Wd)
+    for M in Ms:
+        print("  %s M=%d" % (tag, M), flush=True)
+        Xd = workloads.act_device(M, K, seed=seed + 1 + M)
+        X = Xd.cpu().numpy()
+        Xq, sc = oracle.quantize_act(X)
+        y16 = {p: nfp.gemm(Xd, planes[p][0], planes[p][1], nfp.MODE_FP16) for p in planes}
+        y8 = {p: nfp.gemm(Xd, planes[p][0], None, nfp.MODE_FP8) for p in planes}
+        assert torch.equal(y16[False], y16[True]) and torch.equal(y8[False], y8[True]), tag + ": layouts differ"
+        assert torch.equal(nfp.plain_gemm_fp16(Xd, Wp), y16[True]), tag + ": FP16 mode differs from plain FP16 on packed weights"
+        for pins in (pin_sets(M) if pin_sets else []):
+            for k, v in pins.items():
+                nfp.tune(k, v)
+            try:
+                assert torch.equal(nfp.gemm(Xd, planes[False][0], planes[False][1], nfp.MODE_FP16), nfp.plain_gemm_fp16(Xd, Wd)), \
+                    tag + ": FP16 mode differs from plain fp16 under %s" % pins
+            finally:
+                for k in pins:
+                    nfp.tune(k, -1)
+        got16, got8 = y16[False].cpu().numpy(), y8[False].cpu().numpy()
+        total = 0
+        for rows, cols in structured_sample(M, N, seed=seed + M):
+            Xs, Ws = X[rows], W[cols]
+            assert_gemm_close(got16[np.ix_(rows, cols)], oracle.gemm_fp16(Xs, Ws), "%s M=%d FP16 mode" % (tag, M))
+            assert_gemm_close(got8[np.ix_(rows, cols)], oracle.gemm_fp8(Xq[rows], sc[rows], up_ref[cols]),
+                              "%s M=%d FP8 mode" % (tag, M))
+            total += len(rows) * len(cols)
+        assert total >= min(1 << 15, M * N)
 
 
-@pytest.mark.parametrize("name,M", [("qkv", 1), ("down", 16), ("gate_up", 64), ("o", 4096), ("down", 2)])
-def test_llama70b_shapes_sampled(nfp, name, M):
-    # configs[3]: the unsharded 70B linears on one GPU, sigma 0.015
+def _default_pins(M):
+    if M <= 64:
+        pins = [{"small_max_m": 64, "small_spw": 4}]
+        if M > 32:
+            pins.append({"small_max_m": 0, "large_bm": 64, "large_split": 4})     # 64-token tiles of the tiled kernels
+        return pins
+    return [{"large_bm": 256, "large_bn": 256, "large_split": 1}]
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_llama8b_shapes_structured_sample(nfp, name):
+    # configs[1] and configs[2]: decode and prefill batch sizes on the 8B linears
+    N, K = workloads.LLAMA3_8B[name]
+    _full_size_check(nfp, N, K, [1, 16, 64, 512, 2048, 8192], workloads.SIGMA_W_8B, "8B " + name, seed=N % 97,
+                     pin_sets=_default_pins)
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_llama70b_shapes_structured_sample(nfp, name):
+    # configs[3]: the unsharded 70B linears on one GPU, sigma 0.015, decode to prefill
     N, K = workloads.LLAMA3_70B[name]
-    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_70B, "70B %s M=%d" % (name, M), seed=70 + M)
+    _full_size_check(nfp, N, K, [1, 2, 16, 64, 128, 512, 2048, 8192], workloads.SIGMA_W_70B, "70B " + name, seed=70 + N % 89,
+                     pin_sets=_default_pins)
 
 
 @pytest.mark.parametrize("N,K,M", [(40, 32, 70000), (256, 65536, 8), (264, 65536 + 16, 70), (1000, 16, 1000), (4096, 4096, 20000)])
 def test_extreme_aspect_ratios_sampled(nfp, N, K, M):
     # tens of thousands of tokens on a sliver of a layer, the longest rows, the shortest K, a prefill
-    # of 20000 tokens: sampled against the oracle
-    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_8B, "N=%d K=%d M=%d" % (N, K, M), seed=N % 97 + M % 89)
+    # of 20000 tokens
+    _full_size_check(nfp, N, K, [M], workloads.SIGMA_W_8B, "N=%d K=%d" % (N, K), seed=N % 97 + M % 89, pin_sets=_default_pins)
 
 
-@pytest.mark.parametrize("M", [4, 130])
-def test_vocabulary_sized_layer_sampled(nfp, M):
+def test_vocabulary_sized_layer_sampled(nfp):
     # a Llama-3 output projection (128256 x 4096): half a billion weights, a row count that is no
     # multiple of any tile, 8-tile groups of the XCD order plus a tail
-    _sampled_full_size_check(nfp, 128256, 4096, M, workloads.SIGMA_W_8B, "lm_head M=%d" % M, seed=128 + M)
+    _full_size_check(nfp, 128256, 4096, [4, 130], workloads.SIGMA_W_8B, "lm_head", seed=128)
 
 
-@pytest.mark.parametrize("N,K,M", [(28672, 5120, 96), (65536, 5120, 1024), (35840, 5120, 32)])
-def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, M):
+@pytest.mark.parametrize("N,K,Ms", [(28672, 5120, [96]), (65536, 5120, [1024]), (35840, 5120, [32])])
+def test_paper_kernel_benchmark_shapes_sampled(nfp, N, K, Ms):
     # the (N, K) shapes of Sec. 5.2 / Fig. 6, M inside its 32..2048 sweep
-    _sampled_full_size_check(nfp, N, K, M, workloads.SIGMA_W_8B, "N=%d K=%d M=%d" % (N, K, M), seed=N % 89)
+    _full_size_check(nfp, N, K, Ms, workloads.SIGMA_W_8B, "N=%d K=%d" % (N, K), seed=N % 89, pin_sets=_default_pins)
 
 
 @pytest.mark.parametrize("M,N,K,split", [(16, 4096, 4096, -1), (1, 6144, 4096, -1), (5, 304, 2048 + 64, 1),
@@ -504,7 +525,7 @@ def test_fused_activation_quantisation_equals_the_two_kernel_path(nfp, M, N, K, 
     X = workloads.act_host(M, K, seed=M + K)
     X[0, :] = 0                                        # an all-zero token: scale 1
     Xd = to_dev(X)
-    up, _ = nfp.decompose(to_dev(W))
+    up, _ = nfp.decompose(to_dev(W), packed=True)      # the fused kind exists for packed planes
     sc = torch.tensor([0.0123], dtype=torch.float32, device="cuda:0")
     nfp.tune("small_split", split)
     nfp.tune("small_fuse_quant", 1)
@@ -525,3 +546,74 @@ def test_fused_activation_quantisation_equals_the_two_kernel_path(nfp, M, N, K, 
     up_ref, _, _ = oracle.decompose(W)
     assert_gemm_close(fused.view(np.float16), oracle.gemm_fp8(Xq, s, up_ref), "fused FP8 mode")
 
+
+
+@pytest.mark.parametrize("M", [4, 40, 200])
+def test_memory_outside_the_matrix_never_reaches_the_result(nfp, M):
+    # K = 1040 is no multiple of the kernels' 64- and 128-column steps, so the last step of a row
+    # runs past K: into the next row, or into the gap of a strided matrix.  Exception layers may
+    # hold Inf / NaN there (Sec. 4.1 "Handling Exception Layers"), and E4M3 weights passed to the
+    # plain FP8 GEMM may hold NaN codes; neither may touch the other rows' outputs.
+    N, K, ld = 80, 1040, 1104
+    big = workloads.weight_host(N, ld, seed=11)
+    big[:, K:] = np.float16(np.nan)                     # the gap columns of the strided matrix
+    big[17, 0] = np.float16(np.inf)                     # head of the row after row 16
+    big[33, 0:64] = np.float16(np.nan)
+    X = workloads.act_host(M, K, seed=12)
+    Xd = to_dev(X)
+    Wd = to_dev(big)[:, :K]
+    assert Wd.stride(0) == ld
+    y = nfp.plain_gemm_fp16(Xd, Wd).cpu().numpy()
+    ref = oracle.gemm_fp16(X, np.ascontiguousarray(big[:, :K]))
+    clean = np.array([n for n in range(N) if n not in (17, 33)])
+    assert_gemm_close(y[:, clean], ref[:, clean], "plain FP16, strided W with NaN gaps, M=%d" % M)
+    assert not np.isfinite(y[:, [17, 33]]).any()        # the rows that do hold Inf / NaN say so
+    # E4M3 weights: a whole 16-row tile of NaN codes next to clean tiles, both storage orders
+    rng = np.random.default_rng(5)
+    Wq = rng.integers(0, 0x78, size=(48, K), dtype=np.uint8)          # finite codes
+    dirty = Wq.copy()
+    dirty[16:32, :] = 0x7F
+    for packed in (False, True):
+        a, b = to_dev(Wq), to_dev(dirty)
+        if packed:
+            a, b = nfp.pack_plane(a), nfp.pack_plane(b)
+        ya = nfp.plain_gemm_fp8(Xd, a, 2.0 ** -8).cpu().numpy()
+        yb = nfp.plain_gemm_fp8(Xd, b, 2.0 ** -8).cpu().numpy()
+        keep = np.r_[0:16, 32:48]
+        assert np.isfinite(ya).all()
+        assert np.array_equal(ya[:, keep].view(np.uint16), yb[:, keep].view(np.uint16)), "packed=%s" % packed
+        assert np.isnan(yb[:, 16:32]).all()
+
+
+@pytest.mark.parametrize("M,N,K,knobs", [(16, 4096 + 8, 14336, {}), (4, 300, 28672, {}),
+                                         (16, 520, 4096, {"small_split": 4, "small_tiles": 2}),
+                                         (40, 304, 2048 + 64, {"small_split": 3, "small_tiles": 3}),
+                                         (7, 1027, 1024, {"small_split": 8, "small_tiles": 5, "small_spw": 2})])
+def test_split_k_finished_by_the_last_workgroup_equals_the_reduction_launch(nfp, M, N, K, knobs):
+    # a grid-level K split is summed by the last workgroup of each tile column to arrive, in slice
+    # order; the stand-alone reduction launch (knob fused_reduce = 0) gives the same bits, the
+    # arrival counters are back at zero afterwards, and the result matches the oracle
+    W = workloads.weight_host(N, K, seed=N)
+    X = workloads.act_host(M, K, seed=K)
+    Wd, Xd = to_dev(W), to_dev(X)
+    ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + (64 << 20), "cuda:0")
+    for k, v in knobs.items():
+        nfp.tune(k, v)
+    try:
+        for packed in (False, True):
+            up, lo = nfp.decompose(Wd, packed=packed)
+            outs = {}
+            for fused in (-1, 0):
+                nfp.tune("fused_reduce", fused)
+                outs[fused] = [bits(nfp.gemm(Xd, up, lo, nfp.MODE_FP16, workspace=ws)),
+                               bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8, workspace=ws)),
+                               bits(nfp.gemm(Xd, up, lo, nfp.MODE_FP16, workspace=ws))]     # a second call on the same counters
+            nfp.tune("fused_reduce", -1)
+            for a, b in zip(outs[-1], outs[0]):
+                assert np.array_equal(a, b)
+            assert int(ws[:nfp.WORKSPACE_COUNTER_BYTES].count_nonzero()) == 0
+            assert_gemm_close(outs[-1][0].view(np.float16), oracle.gemm_fp16(X, W), "fused split-K, FP16 mode")
+    finally:
+        nfp.tune("fused_reduce", -1)
+        for k in knobs:
+            nfp.tune(k, -1)

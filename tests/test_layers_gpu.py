@@ -18,8 +18,9 @@ def nfp():
     return binding
 
 
+@pytest.mark.parametrize("packed", [False, True], ids=["rowmajor", "packed"])
 @pytest.mark.parametrize("M", [8, 200])
-def test_planted_outlier_makes_an_exception_layer(nfp, M):
+def test_planted_outlier_makes_an_exception_layer(nfp, M, packed):
     N, K = 272, 1040
     W = workloads.weight_host(N, K, seed=5)
     W_bad = W.copy()
@@ -27,7 +28,7 @@ def test_planted_outlier_makes_an_exception_layer(nfp, M):
     W_bad[3, 0] = np.float16(-1.8125)
     X = workloads.act_host(M, K, seed=6)
     Xd = to_dev(X)
-    good, bad = nfp.Layer(to_dev(W)), nfp.Layer(to_dev(W_bad))
+    good, bad = nfp.Layer(to_dev(W), packed=packed), nfp.Layer(to_dev(W_bad), packed=packed)
     assert not good.is_exception and good.out_of_range == 0
     assert bad.is_exception and bad.out_of_range == 2 and bad.upper is None
 
@@ -53,7 +54,7 @@ def test_mixed_stack_switches_only_the_applicable_layers(nfp):
     K = 512
     Ws = [workloads.weight_host(256, K, seed=20 + i) for i in range(4)]
     Ws[2][10, 10] = np.float16(3.0)
-    layers = [nfp.Layer(to_dev(w)) for w in Ws]
+    layers = [nfp.Layer(to_dev(w), packed=(i % 2 == 1)) for i, w in enumerate(Ws)]
     assert [l.is_exception for l in layers] == [False, False, True, False]
     X = workloads.act_host(16, K, seed=9)
     Xd = to_dev(X)
