@@ -338,7 +338,17 @@ small_gemm_kernel(SmallParams p) {
             }
         }
     };
+    // Partial sums of a grid-level K split.  Where the last workgroup to arrive finishes the sum
+    // (p.counters), they are written through to memory and read back past the caches (cache policy
+    // sc0 sc1, system scope): every XCD has an L2 of its own, and the alternative -- a release fence
+    // in every workgroup, which writes back the whole L2, and an acquire fence, which invalidates
+    // it -- made the kernel four times slower (measured).
+    const bool fused = gridDim.y > 1 && p.counters != nullptr;
+    constexpr int kThrough = 1 | 16;                  // buffer cache policy: sc0 | sc1
     const bool part_vec = (p.N & 3) == 0;
+    const int64_t slice_elems = (int64_t)p.M * p.N;
+    const __amdgpu_buffer_rsrc_t rpart = __builtin_amdgcn_make_buffer_rsrc(
+        p.partials, 0, fused ? (uint32_t)(gridDim.y * slice_elems * 4) : 0u, 0x00020000);
     for (int item = wave; item < T * MT; item += waves) {
         const int tile = item / MT, i = item - tile * MT;
         floatx4 sum = slots[((tile * waves) * MT + i) * 64 + lane];
@@ -350,56 +360,73 @@ small_gemm_kernel(SmallParams p) {
         const int n = (tile0 + tile * tstride) * 16 + 4 * g;
         if (m >= p.M || n >= p.N) continue;
         if (gridDim.y > 1) {
-            float *dst = p.partials + ((int64_t)slice * p.M + m) * p.N + n;
-            if (part_vec) {
-                *reinterpret_cast<floatx4 *>(dst) = sum;
+            const int64_t e = ((int64_t)slice * p.M + m) * p.N + n;
+            if (fused) {
+                const uint32_t off = (uint32_t)(e * 4);
+                if (part_vec) {
+                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{__float_as_uint(sum.x), __float_as_uint(sum.y),
+                                                                 __float_as_uint(sum.z), __float_as_uint(sum.w)},
+                                                           rpart, off, 0, kThrough);
+                } else {
+                    const float v[4] = {sum.x, sum.y, sum.z, sum.w};
+                    for (int q = 0; q < 4 && n + q < p.N; ++q)
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[q]), rpart, off + 4 * q, 0, kThrough);
+                }
             } else {
-                float v[4] = {sum.x, sum.y, sum.z, sum.w};
-                for (int q = 0; q < 4 && n + q < p.N; ++q) dst[q] = v[q];
+                float *dst = p.partials + e;
+                if (part_vec) {
+                    *reinterpret_cast<floatx4 *>(dst) = sum;
+                } else {
+                    float v[4] = {sum.x, sum.y, sum.z, sum.w};
+                    for (int q = 0; q < 4 && n + q < p.N; ++q) dst[q] = v[q];
+                }
             }
         } else {
             store_y(sum, m, n);
         }
     }
-    if (gridDim.y == 1 || p.counters == nullptr) return;
+    if (!fused) return;
 
     // ---- grid-level K split finished by the last workgroup to arrive -------------------------
-    // Every workgroup of a tile column publishes its partial sums (release), then takes a ticket;
-    // the one that draws the last ticket (acquire) adds the slices in slice order -- the order of
+    // Every workgroup of a tile column waits until its partial sums have reached memory, then takes
+    // a ticket; the one that draws the last ticket adds the slices in slice order -- the order of
     // the stand-alone reduction kernel, so the result does not depend on who came last -- and
     // leaves the counter at zero for the next launch.  Nobody waits for anybody.
     __shared__ uint32_t ticket;
-    __threadfence();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this lane's write-through stores are done
     __syncthreads();
-    if (threadIdx.x == 0) ticket = atomicAdd(&p.counters[blockIdx.x], 1u);
+    if (threadIdx.x == 0)
+        ticket = __hip_atomic_fetch_add(&p.counters[blockIdx.x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket != gridDim.y - 1) return;
-    __threadfence();
-    const int64_t slice_elems = (int64_t)p.M * p.N;
     for (int item = wave; item < T * MT; item += waves) {
         const int tile = item / MT, i = item - tile * MT;
         const int m = 16 * i + r16;
         const int n = (tile0 + tile * tstride) * 16 + 4 * g;
         if (m >= p.M || n >= p.N) continue;
-        const float *src = p.partials + (int64_t)m * p.N + n;
+        const uint32_t off = (uint32_t)(((int64_t)m * p.N + n) * 4);
+        const uint32_t sstep = (uint32_t)(slice_elems * 4);
         floatx4 sum;
         if (part_vec) {
-            sum = *reinterpret_cast<const floatx4 *>(src);
+            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rpart, off, 0, kThrough);
+            sum = floatx4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
             for (int s2 = 1; s2 < (int)gridDim.y; ++s2) {
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(src + s2 * slice_elems);
-                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                v = __builtin_amdgcn_raw_buffer_load_b128(rpart, off + s2 * sstep, 0, kThrough);
+                sum.x += __uint_as_float(v.x); sum.y += __uint_as_float(v.y);
+                sum.z += __uint_as_float(v.z); sum.w += __uint_as_float(v.w);
             }
         } else {
             float v[4] = {0.f, 0.f, 0.f, 0.f};
             for (int q = 0; q < 4 && n + q < p.N; ++q) {
-                v[q] = src[q];
-                for (int s2 = 1; s2 < (int)gridDim.y; ++s2) v[q] += src[s2 * slice_elems + q];
+                v[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rpart, off + 4 * q, 0, kThrough));
+                for (int s2 = 1; s2 < (int)gridDim.y; ++s2)
+                    v[q] += __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rpart, off + s2 * sstep + 4 * q, 0, kThrough));
             }
             sum = floatx4{v[0], v[1], v[2], v[3]};
         }
         store_y(sum, m, n);
     }
-    if (threadIdx.x == 0) p.counters[blockIdx.x] = 0u;
+    if (threadIdx.x == 0) __hip_atomic_store(&p.counters[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Sums the S split-K partials in slice order, applies the FP8-mode scale, writes fp16.
@@ -606,7 +633,7 @@ int launch_small_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     const unsigned grid_x = (unsigned)((tiles + c.tiles_per_wg - 1) / c.tiles_per_wg);
     // the last workgroup of a tile column sums the K slices itself where there is a counter for it
     const bool fused_reduce = c.split > 1 && a.counters != nullptr && grid_x <= (unsigned)kMaxCounters &&
-                              tuning().fused_reduce != 0;
+                              (int64_t)c.split * a.M * a.N * 4 < ((int64_t)1 << 32) && tuning().fused_reduce != 0;
     p.counters = fused_reduce ? a.counters : nullptr;
     p.k_passes = c.passes;
     p.tile_stride = (tuning().small_interleave != 0 && c.tiles_per_wg > 1) ? (int)grid_x : 1;
