@@ -202,7 +202,10 @@ struct TileStore {
     }
 };
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+// NST: LDS stages.  Two are enough where a K-tile's MFMAs outlast the latency of the next K-tile's
+// loads (256 x 256 tiles) or two workgroups share a CU; a launch with at most one workgroup per CU
+// and smaller tiles takes three or four, so that loads run NST - 1 K-tiles ahead.
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int NST = 2>
 struct LargeKernel {
     static_assert(KIND == kPlainF16 || KIND == kE4M3 || KIND == kE4M3Row, "NestedFP16 has a kernel of its own");
     static constexpr bool FP8 = kind_is_fp8(KIND);
@@ -212,7 +215,8 @@ struct LargeKernel {
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;
     static constexpr int STAGE = (TM + TN) * 128;      // bytes per LDS stage
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int LDS_BYTES = NST * STAGE;
+    static_assert(NST >= 2 && LDS_BYTES <= 160 * 1024, "LDS stages");
     typedef TileStore<KIND, TM, TN, WAVES_M, WAVES_N> Store;
     static_assert(TM * TN * 2 <= LDS_BYTES, "output tile must fit into the operand stages");
 
@@ -384,7 +388,7 @@ struct LargeKernel {
         lds_byte *lds3;
         uint32_t x_lim, w_lim;
         int wave, lane, wm, wn;
-        int kt, cur;
+        int kt, cur, nxt;                               // K-tile, its LDS stage, the next K-tile's
     };
 
     template <bool OLDER, int S, int PAR, int Q>
@@ -392,10 +396,20 @@ struct LargeKernel {
         constexpr bool last = (S == SUBS - 1);
         if constexpr (last && Q == QB) {
             // every read of the current stage has been issued; once all waves are here and their
-            // loads of the next K-tile have landed, the stage is free and the next one complete
-            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            // loads of the next K-tile have landed (those of the NST - 2 K-tiles after it may stay
+            // in flight), the stage is free and the next one complete
+            if constexpr (OLDER) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NST - 2) * DMAS) : "memory");
             else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __syncthreads();
+            if constexpr (NST == 2) {
+                __syncthreads();
+            } else {
+                // a bare barrier: the fence of __syncthreads() would drain the loads in flight.  What
+                // it would order is ordered by the waits above: the next stage's loads have landed,
+                // and every LDS read of the stage that is refilled next has returned.
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         mfma_one<Q>(c.fr[PAR], c.acc);
@@ -403,13 +417,13 @@ struct LargeKernel {
             read_frag<FNB + NB0 + Q / RSTR>(c.fr[PAR], c.lds + c.cur * STAGE, c.wm, c.wn, c.lane, S);
         if constexpr (Q >= TAIL0 && (Q - TAIL0) % TSTR == 0 && (Q - TAIL0) / TSTR < TSLOTS) {
             constexpr int r0 = (Q - TAIL0) / TSTR * RPT;
-            read_frags<r0, (r0 + RPT < NPRE ? r0 + RPT : NPRE)>(c.fr[PAR ^ 1], c.lds + (last ? c.cur ^ 1 : c.cur) * STAGE, c.wm, c.wn,
+            read_frags<r0, (r0 + RPT < NPRE ? r0 + RPT : NPRE)>(c.fr[PAR ^ 1], c.lds + (last ? c.nxt : c.cur) * STAGE, c.wm, c.wn,
                                                                 c.lane, last ? 0 : S + 1);
         }
         if constexpr (last && OLDER && Q >= QB) {
 #pragma unroll
             for (int d = (Q - QB) * DPS; d < (Q - QB + 1) * DPS && d < DMAS; ++d)
-                dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw, c.lds3 + c.cur * STAGE, c.wave, c.kt + 2);
+                dma_one(d, c.dof, c.x_lim, c.w_lim, c.rx, c.rw, c.lds3 + c.cur * STAGE, c.wave, c.kt + NST);
         }
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (Q + 1 < MF) slot<OLDER, S, PAR, Q + 1>(c);
@@ -417,9 +431,12 @@ struct LargeKernel {
 
     template <bool OLDER>
     static __device__ __forceinline__ void k_loop(Ctx &c, int kt_begin, int kt_end) {
+        int cur = 0;
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             c.kt = kt;
-            c.cur = (kt - kt_begin) & 1;
+            c.cur = cur;
+            cur = cur + 1 == NST ? 0 : cur + 1;
+            c.nxt = cur;
             __builtin_amdgcn_sched_barrier(0);
             slot<OLDER, 0, 0, 0>(c);
             slot<OLDER, 1, 1, 0>(c);
@@ -446,16 +463,16 @@ struct LargeKernel {
         const uint32_t x_lim = (uint32_t)p.k_bytes;
         const uint32_t w_lim = PACKED_W ? (uint32_t)p.kblocks : (uint32_t)p.k_bytes;
 
-        // Two LDS stages; tokens and weights go straight from global memory into LDS.
+        // NST LDS stages; tokens and weights go straight from global memory into LDS.
         if (wave < DW) {
 #pragma unroll
-            for (int st = 0; st < 2; ++st)
+            for (int st = 0; st < NST; ++st)
 #pragma unroll
                 for (int i = 0; i < DMAS; ++i)
                     dma_one(i, dof, x_lim, w_lim, rx, rw, lds3 + st * STAGE, wave, kt_begin + st);
         }
         // the loads of K-tile kt_begin (a wave that issued none passes straight through)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMAS) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 1) * DMAS) : "memory");
         __syncthreads();
 
         AccT acc[FNB][FMB];
@@ -466,11 +483,11 @@ struct LargeKernel {
 #pragma unroll
                 for (int q = 0; q < (MB == 32 ? 16 : 4); ++q) acc[i][j][q] = 0.f;
         Frags fr[2];
-        Ctx c{acc, fr, dof, rx, rw, lds, lds3, x_lim, w_lim, wave, lane, wm, wn, kt_begin, 0};
+        Ctx c{acc, fr, dof, rx, rw, lds, lds3, x_lim, w_lim, wave, lane, wm, wn, kt_begin, 0, 0};
         read_frags<0, NPRE>(fr[0], lds, wm, wn, lane, 0);
         if (wave < DW) k_loop<true>(c, kt_begin, kt_end);
         else k_loop<false>(c, kt_begin, kt_end);
-        // the loads of the two K-tiles past the end are still in flight: they must have landed
+        // the loads of the K-tiles past the end are still in flight: they must have landed
         // before the LDS is reused for the output tile or handed back
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (p.row_store && gridDim.y == 1) {
@@ -484,11 +501,11 @@ struct LargeKernel {
 
 };
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int NST>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 large_gemm_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    typedef LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N> Kern;
+    typedef LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N, NST> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -504,7 +521,10 @@ large_gemm_kernel(LargeParams p) {
 // 2 g + s of the 128-byte row, see fp16_chunk_of_slot).  No ds_write, no weight tile in LDS; LDS holds four stages of
 // the token tile only (loads run three K-tiles ahead), and the one barrier per K-tile sits
 // at its end and waits for no LDS read.
-template <int TM, int TN, int WK>
+// DEEP: a ring of eight token stages with the token loads six and the plane loads four K-tiles ahead
+// (tiles of at most 128 tokens, launches that do not fill the chip: there a K-tile's MFMAs are
+// short against the latency of a load) instead of four stages and three / two K-tiles.
+template <int TM, int TN, int WK, bool DEEP = false>
 struct BypassKernel {
     static_assert(WK == kNestedF16 || WK == kNestedF16Row || WK == kPlainF16Packed, "weights that go through registers");
     static constexpr bool MERGE = kind_is_nested(WK);
@@ -517,10 +537,11 @@ struct BypassKernel {
     static constexpr int MF = FMB * FNB;                       // MFMAs per substep
     // (a ring of eight stages with the token loads six and the plane loads three K-tiles ahead was
     // no faster for the 64-token tiles)
-    static constexpr int NST = 4;                              // LDS stages of the token tile
-    static constexpr int XA = 3;                               // token loads run this many K-tiles ahead
-    static constexpr int NRAW = 2;                             // plane blocks are loaded this many K-tiles ahead
+    static constexpr int NST = DEEP ? 8 : 4;                   // LDS stages of the token tile
+    static constexpr int XA = DEEP ? 6 : 3;                    // token loads run this many K-tiles ahead
+    static constexpr int NRAW = DEEP ? 4 : 2;                  // plane blocks are loaded this many K-tiles ahead
     static_assert(XA >= 3 && XA < NST && NRAW <= XA && NRAW >= 2, "the stage being filled is neither the one in use nor the next");
+    static_assert(NST * TM * 128 <= 160 * 1024, "LDS stages");
     static constexpr int STAGE = TM * 128;
     static constexpr int LDS_BYTES = NST * STAGE > TM * TN * 2 ? NST * STAGE : TM * TN * 2;
     static constexpr int XG = TM / 8 / DW;                     // loads per loading wave per K-tile
@@ -752,11 +773,11 @@ struct BypassKernel {
     }
 };
 
-template <int TM, int TN, int WK>
+template <int TM, int TN, int WK, bool DEEP>
 __global__ void __launch_bounds__(512)
 nested_bypass_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    typedef BypassKernel<TM, TN, WK> Kern;
+    typedef BypassKernel<TM, TN, WK, DEEP> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -970,7 +991,7 @@ e4m3_bypass_kernel(LargeParams p) {
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
-struct LargeConfig { int tm, tn, split; };
+struct LargeConfig { int tm, tn, split, deep; };
 
 // Tile shape and K split from a small cost model.  The workgroups are dealt round-robin to the
 // 256 CUs; a workgroup costs a fixed part plus a time per K-tile that depends on the tile shape
@@ -1011,7 +1032,7 @@ static LargeConfig choose_tile64(int cls, int64_t M, int64_t N, int kt) {
     const Tuning &t = tuning();
     const Tile64Cost &tc = kTile64Cost[cls];
     LargeConfig c;
-    c.tm = 64;  c.tn = 128;  c.split = 1;
+    c.tm = 64;  c.tn = 128;  c.split = 1;  c.deep = 0;
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
     double best = 1e30;
     for (int split = 1; split <= 8; split *= 2) {
@@ -1041,6 +1062,7 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;
+    c.deep = 0;
     const int want_m = (t.large_bm == 128 || t.large_bm == 256) ? (int)t.large_bm : 0;
     const int want_n = (t.large_bn == 128 || t.large_bn == 256) ? (int)t.large_bn : want_m;
     const double w_bytes = (double)N * (double)K * (kind_is_fp8(kind) ? 1.0 : 2.0);
@@ -1076,10 +1098,10 @@ size_t large_gemm_partial_bytes(int kind, int64_t M, int64_t N, int64_t K) {
     return c.split > 1 ? (size_t)c.split * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N>
+template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int NST = 2>
 static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N>;
-    constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N>::LDS_BYTES;
+    auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N, NST>;
+    constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N, NST>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1089,10 +1111,10 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
     kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
 
-template <int TM, int TN, int WK>
+template <int TM, int TN, int WK, bool DEEP = false>
 static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = nested_bypass_kernel<TM, TN, WK>;
-    constexpr int lds = BypassKernel<TM, TN, WK>::LDS_BYTES;
+    auto kern = nested_bypass_kernel<TM, TN, WK, DEEP>;
+    constexpr int lds = BypassKernel<TM, TN, WK, DEEP>::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1120,9 +1142,16 @@ static void launch_large_k(const LargeParams &p, const LargeConfig &c, dim3 grid
         if constexpr (KIND == kPlainF16) launch_large_t<KIND, 64, 128, 2, 4>(p, grid, stream);
         else launch_e4m3_bypass<64, 128, KIND == kE4M3Row>(p, grid, stream);
     } else if (c.tm == 256 && c.tn == 256) launch_large_t<KIND, 256, 256, 2, 4>(p, grid, stream);
-    else if (c.tm == 256) launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
-    else if (c.tn == 256) launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
-    else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
+    else if (c.tm == 256) {
+        if (c.deep) launch_large_t<KIND, 256, 128, 4, 2, 3>(p, grid, stream);
+        else launch_large_t<KIND, 256, 128, 4, 2>(p, grid, stream);
+    } else if (c.tn == 256) {
+        if (c.deep) launch_large_t<KIND, 128, 256, 2, 4, 3>(p, grid, stream);
+        else launch_large_t<KIND, 128, 256, 2, 4>(p, grid, stream);
+    } else {
+        if (c.deep) launch_large_t<KIND, 128, 128, 2, 4, 4>(p, grid, stream);
+        else launch_large_t<KIND, 128, 128, 2, 4>(p, grid, stream);
+    }
 }
 
 // weights through registers: NestedFP16 in either storage order, packed FP16
@@ -1131,8 +1160,13 @@ static void launch_nested(const LargeParams &p, const LargeConfig &c, dim3 grid,
     if (c.tm == 64) launch_bypass<64, 128, WK>(p, grid, stream);
     else if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256, WK>(p, grid, stream);
     else if (c.tm == 256) launch_bypass<256, 128, WK>(p, grid, stream);
-    else if (c.tn == 256) launch_bypass<128, 256, WK>(p, grid, stream);
-    else launch_bypass<128, 128, WK>(p, grid, stream);
+    else if (c.tn == 256) {
+        if (c.deep) launch_bypass<128, 256, WK, true>(p, grid, stream);
+        else launch_bypass<128, 256, WK>(p, grid, stream);
+    } else {
+        if (c.deep) launch_bypass<128, 128, WK, true>(p, grid, stream);
+        else launch_bypass<128, 128, WK>(p, grid, stream);
+    }
 }
 
 // The kernels address a tile with 32-bit byte offsets whose bit 31 marks a dead load, so 256 rows
@@ -1147,6 +1181,7 @@ bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw) {
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     if (!large_gemm_supports(kind, a.K, a.ldx, a.ldw)) return kErrShape;
     LargeConfig c = choose_large(kind, a.M, a.N, a.K);
+    if (tuning().large_deep >= 0) c.deep = tuning().large_deep > 0 && c.tm <= 256 && !(c.tm == 256 && c.tn == 256) && c.tm != 64;
     LargeParams p;
     p.X = static_cast<const uint8_t *>(a.X);
     p.x_row_bytes = kind_is_fp8(kind) ? a.ldx : 2 * a.ldx;

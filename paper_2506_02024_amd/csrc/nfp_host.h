@@ -79,6 +79,7 @@ struct Tuning {
     int64_t quant_hw;        // 1: hardware E4M3 convert, 0: integer rounding
     int64_t large_xcd_map;   // 0: tiles in launch order instead of grouped by XCD (tiled kernels)
     int64_t fused_reduce;    // 0: split-K partials are summed by a second launch instead of the last workgroup
+    int64_t large_deep;      // 1 / 0: force / forbid the deeper load pipelines of the tiled kernels (tiles below 256 x 256)
 };
 Tuning &tuning();
 

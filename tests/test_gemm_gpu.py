@@ -186,13 +186,11 @@ def test_decode_launch_shapes(nfp, knobs):
     # every combination of K-steps per wave, grid-level K split and tiles per workgroup
     # (odd and even, more than the layer has) gives the same answer
     W = workloads.weight_host(304, 2048 + 64, seed=21)
-    X = workloads.act_host(16, 2048 + 64, seed=21)
-    for k, v in knobs.items():
-        nfp.tune(k, v)
     try:
-        run_both_modes(nfp, X, W, str(knobs))
-        X2 = workloads.act_host(40, 2048 + 64, seed=22)
-        run_both_modes(nfp, X2, W, str(knobs) + " M=40")
+        for M in (16, 40):
+            for k, v in knobs.items():                 # (the plain-GEMM comparison inside resets the knobs it pins)
+                nfp.tune(k, v)
+            run_both_modes(nfp, workloads.act_host(M, 2048 + 64, seed=21 + M), W, "%s M=%d" % (knobs, M))
     finally:
         for k in knobs:
             nfp.tune(k, -1)
@@ -220,13 +218,20 @@ def test_prefill_sized_batches(nfp, M, N, K):
     {"large_bm": 64, "large_split": 1},       # 64 x 128 tiles: NestedFP16 only, the other kinds ignore it
     {"large_bm": 64, "large_split": 4},
     {"small_max_m": 0},                       # route a decode-sized batch through the tiled kernel
+    # the deeper load pipelines of the tiles below 256 x 256 (three or four LDS stages, eight token stages)
+    {"large_deep": 1, "large_bm": 128, "large_bn": 128, "large_split": 1},
+    {"large_deep": 1, "large_bm": 128, "large_bn": 128, "large_split": 3},
+    {"large_deep": 1, "large_bm": 256, "large_bn": 128, "large_split": 1},
+    {"large_deep": 1, "large_bm": 128, "large_bn": 256, "large_split": 2},
+    {"large_deep": 1, "large_bm": 128, "large_bn": 256, "large_split": 8},
+    {"large_deep": 0, "large_bm": 128, "large_bn": 128, "large_split": 1},
 ])
 def test_prefill_launch_shapes(nfp, knobs):
     W = workloads.weight_host(520, 1040, seed=31)
-    for k, v in knobs.items():
-        nfp.tune(k, v)
     try:
         for M in (24, 300, 777):
+            for k, v in knobs.items():                 # (the plain-GEMM comparison inside resets the knobs it pins)
+                nfp.tune(k, v)
             X = workloads.act_host(M, 1040, seed=M)
             run_both_modes(nfp, X, W, "%s M=%d" % (knobs, M))
     finally:
@@ -617,3 +622,29 @@ def test_split_k_finished_by_the_last_workgroup_equals_the_reduction_launch(nfp,
         nfp.tune("fused_reduce", -1)
         for k in knobs:
             nfp.tune(k, -1)
+
+
+@pytest.mark.parametrize("bm,bn", [(128, 128), (256, 128), (128, 256)])
+def test_deeper_load_pipelines_change_nothing(nfp, bm, bn):
+    # three / four LDS stages (tiled kernels) and eight token stages (register-path kernels): the
+    # same sums in the same order, so the same bits as the two-stage pipelines, on a K long enough
+    # to go round the rings several times and a K of a single tile
+    for M, N, K in ((300, 520, 2064), (129, 260, 64), (513, 1030, 4096)):
+        W = workloads.weight_host(N, K, seed=K)
+        Xd, Wd = to_dev(workloads.act_host(M, K, seed=M)), to_dev(W)
+        planes = {p: nfp.decompose(Wd, packed=p) for p in (False, True)}
+        Wp = nfp.pack_fp16(Wd)
+        outs = {}
+        for deep in (0, 1):
+            for k, v in {"large_bm": bm, "large_bn": bn, "large_split": 1, "large_deep": deep}.items():
+                nfp.tune(k, v)
+            try:
+                outs[deep] = [bits(nfp.gemm(Xd, planes[p][0], planes[p][1], nfp.MODE_FP16)) for p in planes] + \
+                             [bits(nfp.gemm(Xd, planes[p][0], None, nfp.MODE_FP8)) for p in planes] + \
+                             [bits(nfp.plain_gemm_fp16(Xd, Wd)), bits(nfp.plain_gemm_fp16(Xd, Wp))]
+            finally:
+                for k in ("large_bm", "large_bn", "large_split", "large_deep"):
+                    nfp.tune(k, -1)
+        for a, b in zip(outs[0], outs[1]):
+            assert np.array_equal(a, b), (bm, bn, M, N, K)
+        assert_gemm_close(outs[1][0].view(np.float16), oracle.gemm_fp16(Xd.cpu().numpy(), W), "deep pipelines")
