@@ -191,6 +191,21 @@ int nestedfp_gemm_packed(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * nestedfp_gemm for callers that cannot allocate device memory or pass a workspace (code
+ * under HIP graph capture that owns no scratch, tight serving loops, harnesses that forbid
+ * hipMalloc): row-major planes, same arguments without the workspace, same results.  The
+ * scratch is a fixed array inside the library's device image (NESTEDFP_STATIC_SCRATCH_BYTES
+ * per GPU, held until the process ends); a problem whose workspace query exceeds it is
+ * refused with NESTEDFP_ERR_WORKSPACE.  The call itself allocates nothing.  All calls on one
+ * GPU share that array: calls that may overlap in time on one GPU (different streams) race.
+ */
+#define NESTEDFP_STATIC_SCRATCH_BYTES (32u << 20)
+int nestedfp_gemm_static(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
+                         const uint8_t *upper, const uint8_t *lower, int64_t N,
+                         int mode, const float *act_scale,
+                         uint16_t *Y, int64_t ldy, void *stream);
+
+/*
  * Plain baselines of the same kernel family, for the comparison of Sec. 5.2 (NestedFP
  * FP16 mode against an FP16 GEMM that reads ordinary FP16 weights) and its FP8 analogue.
  * plain_gemm_fp16: W is ordinary row-major FP16 [N,K].

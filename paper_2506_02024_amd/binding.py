@@ -72,6 +72,8 @@ def lib():
     for name in ("nestedfp_gemm", "nestedfp_gemm_packed"):
         getattr(L, name).restype = ci
         getattr(L, name).argtypes = [vp, i64, i64, i64, vp, vp, i64, ci, vp, vp, i64, vp, sz, vp]
+    L.nestedfp_gemm_static.restype = ci
+    L.nestedfp_gemm_static.argtypes = [vp, i64, i64, i64, vp, vp, i64, ci, vp, vp, i64, vp]
     L.nestedfp_plain_gemm_fp16.restype = ci
     L.nestedfp_plain_gemm_fp16.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, sz, vp]
     L.nestedfp_plain_gemm_fp16_packed.restype = ci
@@ -323,6 +325,24 @@ def gemm(X, upper, lower, mode, act_scale=None, out=None, workspace=None):
     st = fn(_ptr(X), M, K, ldx, _ptr(upper), _ptr(lower), N, int(mode), _ptr(act_scale), _ptr(out), ldy,
             _ptr(workspace), workspace.numel(), _stream())
     _check(st, "nestedfp_gemm")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def gemm_static(X, upper, lower, mode, out, act_scale=None):
+    """nestedfp_gemm_static: row-major planes, no workspace argument, nothing allocated -- the
+    output tensor is the caller's, the scratch is a fixed array inside the library."""
+    M, K, ldx = _rowmajor(X, "X")
+    N = upper.shape[0]
+    _check_plane(upper, N, K, "upper")
+    if _is_packed(upper):
+        raise ValueError("gemm_static takes row-major planes")
+    _, _, ldy = _rowmajor(out, "out")
+    st = lib().nestedfp_gemm_static(_ptr(X), M, K, ldx, _ptr(upper), _ptr(lower), N, int(mode), _ptr(act_scale),
+                                    _ptr(out), ldy, _stream())
+    _check(st, "nestedfp_gemm_static")
     return out
 
 

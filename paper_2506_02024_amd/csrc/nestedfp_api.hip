@@ -6,6 +6,8 @@
 
 #include <string.h>
 
+#include <mutex>
+
 namespace nfp {
 
 Tuning &tuning() {
@@ -281,6 +283,36 @@ static int plain_fp8_impl(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, 
 
 }  // namespace nfp
 
+// ---- scratch of the entry point that takes no workspace ------------------------------------------
+// A fixed array in the library's device image: every GPU that loads the library holds its own copy
+// at its own address until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address it returns (per device) is what kernels and fills are given.
+static __device__ __align__(256) unsigned char scratch[NESTEDFP_STATIC_SCRATCH_BYTES];
+
+namespace nfp {
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];               // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+// Address of this device's scratch array; on first use its arrival counters are cleared (the image
+// starts zeroed and every call leaves them zero; the fill makes that independent of the loader).
+static int static_scratch(void **out, hipStream_t stream) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kErrHip;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return kErrHip;
+        if (launch_zero_words(static_cast<uint32_t *>(ptr), kMaxCounters, stream) != kOk) return kErrHip;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return kOk;
+}
+
+}  // namespace nfp
+
 using namespace nfp;
 
 extern "C" {
@@ -409,6 +441,26 @@ int nestedfp_gemm_packed(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, c
                          int64_t ldy, void *workspace, size_t workspace_bytes, void *stream) {
     return gemm_impl(X, M, K, ldx, upper, lower, N, NESTEDFP_LAYOUT_PACKED, mode, act_scale, Y, ldy, workspace,
                      workspace_bytes, stream);
+}
+
+int nestedfp_gemm_static(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const uint8_t *upper,
+                         const uint8_t *lower, int64_t N, int mode, const float *act_scale, uint16_t *Y,
+                         int64_t ldy, void *stream) {
+    if (!valid_mode(mode)) return NESTEDFP_ERR_ARG;
+    int st = check_dims(M, N, K);
+    if (st != kOk) return st;
+    if (M == 0 || N == 0) return NESTEDFP_OK;
+    // the scratch this problem needs in this plane layout and mode, against the fixed array
+    const int kind = mode == NESTEDFP_MODE_FP16 ? kNestedF16Row : kE4M3Row;
+    const size_t need = workspace_bytes_for(kind, M, N, K, mode == NESTEDFP_MODE_FP8);
+    if (need > (size_t)NESTEDFP_STATIC_SCRATCH_BYTES) return NESTEDFP_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (need > 0) {
+        st = static_scratch(&ws, static_cast<hipStream_t>(stream));
+        if (st != kOk) return st;
+    }
+    return gemm_impl(X, M, K, ldx, upper, lower, N, NESTEDFP_LAYOUT_ROWMAJOR, mode, act_scale, Y, ldy, ws,
+                     need > 0 ? (size_t)NESTEDFP_STATIC_SCRATCH_BYTES : 0, stream);
 }
 
 int nestedfp_plain_gemm_fp16(const uint16_t *X, int64_t M, int64_t K, int64_t ldx, const uint16_t *W,
