@@ -15,7 +15,6 @@ from .nestedfp_oracle import (  # noqa: F401
     decompose_one,
     reconstruct,
     reconstruct_one,
-    reconstruct_alg1_step,
     count_out_of_range,
     quantize_act,
     gemm_fp16,

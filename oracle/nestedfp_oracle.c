@@ -148,22 +148,6 @@ uint16_t oracle_reconstruct_one(uint8_t upper, uint8_t lower)
     return (uint16_t)((S << 15) | (0 << 14) | (E4 << 10) | (M12 << 8) | lower);
 }
 
-/* Algorithm 1 (Sec. 4.2), one iteration: four weights at once in 32-bit words.
- * Byte j of u/l belongs to weight i+j (little-endian), out[j] is weight i+j. */
-void oracle_reconstruct_alg1_step(uint32_t u, uint32_t l, uint16_t out[4])
-{
-    uint32_t s = u & 0x80808080u;
-    uint32_t sub = (l & 0x80808080u) >> 7;
-    uint32_t u_orig = ((u - sub) >> 1) & 0x3f3f3f3fu;
-    u_orig = u_orig | s;
-    /* the two byte-permutes interleave u_orig (high bytes) with l (low bytes) */
-    for (int j = 0; j < 4; ++j) {
-        uint32_t hi = (u_orig >> (8 * j)) & 0xFFu;
-        uint32_t lo = (l >> (8 * j)) & 0xFFu;
-        out[j] = (uint16_t)((hi << 8) | lo);
-    }
-}
-
 /* Whole-tensor forms.  W is [N,K] with row stride ldw (elements); planes are
  * dense [N,K].  Returns the number of out-of-range words (planes entries for
  * those are written as 0). */

@@ -47,8 +47,6 @@ def _load():
     lib.oracle_decompose_one.argtypes = [c.c_uint16, u8p, u8p]
     lib.oracle_reconstruct_one.restype = c.c_uint16
     lib.oracle_reconstruct_one.argtypes = [c.c_uint8, c.c_uint8]
-    lib.oracle_reconstruct_alg1_step.restype = None
-    lib.oracle_reconstruct_alg1_step.argtypes = [c.c_uint32, c.c_uint32, u16p]
     lib.oracle_decompose.restype = c.c_uint64
     lib.oracle_decompose.argtypes = [u16p, i64, i64, i64, u8p, u8p]
     lib.oracle_count_out_of_range.restype = c.c_uint64
@@ -118,12 +116,6 @@ def decompose_one(bits):
 
 def reconstruct_one(upper, lower):
     return _load().oracle_reconstruct_one(int(upper), int(lower))
-
-
-def reconstruct_alg1_step(u, l):
-    out = (ctypes.c_uint16 * 4)()
-    _load().oracle_reconstruct_alg1_step(int(u), int(l), out)
-    return [int(x) for x in out]
 
 
 # ---- tensors ----------------------------------------------------------------

@@ -1008,6 +1008,17 @@ static const TileCost kTileCost[3][4] = {
     {{1.317, 4.39}, {1.061, 2.10}, {1.089, 2.28}, {0.864, 1.01}},   // E4M3
 };
 static const double kPairSpeedup[3] = {1.58, 1.02, 1.51};
+// The same tile shapes with the deeper load pipeline (three or four LDS stages, one workgroup per
+// CU, no pair speed-up): per K-tile about a quarter cheaper for the kernels whose weights go through
+// LDS, at a higher fixed cost; nothing gained on the register path (NestedFP16), which does not use it.
+// Least-squares fit to a sweep of every shape, split and pipeline depth over M = 128 ... 2048 on six
+// Llama-3 8B / 70B layer shapes.
+static const TileCost kDeepTileCost[3][4] = {
+    {{0, 0}, {0.863, 1.56}, {0.900, 1.71}, {0.585, 2.50}},         // plain FP16
+    {{0, 0}, {0, 0}, {0, 0}, {0, 0}},                               // NestedFP16: not used
+    {{0, 0}, {0.978, 2.96}, {0.938, 2.77}, {0.606, 2.61}},         // E4M3
+};
+static const int kSplits[] = {1, 2, 3, 4, 6, 8};
 
 // split-K cost: the reduction kernel's launch plus its traffic
 static double split_cost(int64_t M, int64_t N, int slices, double launch_us, double bytes_per_us) {
@@ -1070,24 +1081,28 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
         const int bm = kTileShapes[sh][0], bn = kTileShapes[sh][1];
         if (want_m && bm != want_m) continue;
         if (want_n && bn != want_n) continue;
-        const TileCost &tc = kTileCost[cls][sh];
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-        for (int split = 1; split <= 8; split *= 2) {
-            if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
-            else if (split > 1 && split > kt / 4) break;
-            const int per = (kt + split - 1) / split;                     // K-tiles per workgroup
-            const int slices = (kt + per - 1) / per;
-            const int64_t rounds = (tiles * slices + 255) / 256;
-            double time = (double)rounds * (tc.tfix + per * tc.tk);
-            if (sh == 3 && rounds >= 2) time /= kPairSpeedup[cls];
-            // the weights' one pass over the memory bus (slower while the chip is not full)
-            const int64_t wgs = tiles * slices;
-            double mem_floor = w_bytes / (wgs < 512 ? 4.57e6 : 4.44e6);
-            if (wgs < 256) mem_floor *= std::sqrt(256.0 / (double)wgs);
-            if (time < mem_floor) time = mem_floor;
-            if (slices > 1) time += split_cost(M, N, slices, 3.18, 4.44e6);
-            if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split; }
-            if (t.large_split > 0) break;
+        for (int deep = 0; deep < 2; ++deep) {
+            if (deep && (kDeepTileCost[cls][sh].tk == 0.0 || t.large_deep == 0)) continue;
+            if (!deep && t.large_deep > 0 && kDeepTileCost[cls][sh].tk != 0.0) continue;
+            const TileCost &tc = deep ? kDeepTileCost[cls][sh] : kTileCost[cls][sh];
+            for (int split : kSplits) {
+                if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
+                else if (split > 1 && split > kt / 4) break;
+                const int per = (kt + split - 1) / split;                     // K-tiles per workgroup
+                const int slices = (kt + per - 1) / per;
+                const int64_t rounds = (tiles * slices + 255) / 256;
+                double time = (double)rounds * (tc.tfix + per * tc.tk);
+                if (sh == 3 && rounds >= 2 && !deep) time /= kPairSpeedup[cls];
+                // the weights' one pass over the memory bus (slower while the chip is not full)
+                const int64_t wgs = tiles * slices;
+                double mem_floor = w_bytes / (wgs < 512 ? 4.57e6 : 4.44e6);
+                if (wgs < 256) mem_floor *= std::sqrt(256.0 / (double)wgs);
+                if (time < mem_floor) time = mem_floor;
+                if (slices > 1) time += split_cost(M, N, slices, 3.18, 4.44e6);
+                if (time < best) { best = time;  c.tm = bm;  c.tn = bn;  c.split = split;  c.deep = deep; }
+                if (t.large_split > 0) break;
+            }
         }
     }
     return c;
@@ -1181,7 +1196,8 @@ bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw) {
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     if (!large_gemm_supports(kind, a.K, a.ldx, a.ldw)) return kErrShape;
     LargeConfig c = choose_large(kind, a.M, a.N, a.K);
-    if (tuning().large_deep >= 0) c.deep = tuning().large_deep > 0 && c.tm <= 256 && !(c.tm == 256 && c.tn == 256) && c.tm != 64;
+    // the register-path kernels take the deeper pipeline only when it is asked for
+    if (kind_class(kind) == 1) c.deep = tuning().large_deep > 0 && !(c.tm == 256 && c.tn == 256) && c.tm != 64 && c.tm <= 128;
     LargeParams p;
     p.X = static_cast<const uint8_t *>(a.X);
     p.x_row_bytes = kind_is_fp8(kind) ? a.ldx : 2 * a.ldx;

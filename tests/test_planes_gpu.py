@@ -131,3 +131,31 @@ def test_pack_and_unpack_are_inverse_permutations(nfp, N, K):
     Wp = nfp.pack_fp16(Wd)
     want = pack_fp16_ref(W)
     assert np.array_equal(Wp.data[:want.size].cpu().numpy(), want)
+
+
+def test_four_wide_merge_equals_the_per_element_rule_in_every_byte_lane(nfp, packed):
+    # the kernels rebuild four weights per 32-bit word (Sec. 4.2, Alg. 1): no borrow may cross a
+    # byte.  Every in-range word in each of the four byte lanes of a word, next to neighbours
+    # with extreme bytes (zero, largest magnitude of either sign, minus zero, a carry into the
+    # exponent, a subnormal), against the oracle's per-element reconstruction
+    words = workloads.all_fp16_words()
+    ok = np.array([oracle.in_range(int(w)) for w in words])
+    w = words[ok]
+    w = np.concatenate([w, w[:(-w.size) % 4]])                      # a multiple of 4 rows
+    neighbours = [0x0000, 0x3F00, 0xBF00, 0x8000, 0x3BFF, 0x0041]
+    quads = []
+    for lane in range(4):
+        for nb in neighbours:
+            q = np.full((w.size, 4), nb, dtype=np.uint16)
+            q[:, lane] = w
+            quads.append(q)
+    W = np.concatenate(quads).reshape(-1, 16)                        # rows of 16 words = four 32-bit groups
+    up_ref, lo_ref, bad = oracle.decompose(W)
+    assert bad == 0
+    Wd = to_dev(W.view(np.float16))
+    up, lo = nfp.decompose(Wd, packed=packed)
+    assert_plane_equal(up, up_ref)
+    assert_plane_equal(lo, lo_ref)
+    back = bits(nfp.reconstruct(up, lo))
+    assert np.array_equal(back, oracle.reconstruct(up_ref, lo_ref))
+    assert np.array_equal(back, W)
