@@ -110,7 +110,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the NestedFP hot path has no "
-              "collective; see DESIGN.md for how it would shard); --gpus %d is not supported"
+              "collective: column-parallel layers shard the planes by rows, row-parallel ones by K); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 

@@ -1,7 +1,7 @@
 """Shared helpers for the GPU parity tests (comparison rule and host<->device glue)."""
 import numpy as np
 
-REL_TOL = 1e-2   # the benchmark spec: relative tolerance, fp16 output, fp32 accumulation
+REL_TOL = 1e-2   # the build's stated GEMM tolerance: relative, fp16 output, fp32 accumulation
 
 
 def assert_gemm_close(y_gpu, y_ref, what=""):
