@@ -120,6 +120,7 @@ struct TileStore {
     // The caller guarantees that no wave still reads the operand stages.
     static constexpr int OCH = TN * 2 / 16;            // 16-byte chunks per output row
         static constexpr int NV = MB == 32 ? 4 : 1;
+    static __device__ __forceinline__ float scaled(float x, float s) { return kind_is_fp8(KIND) ? scale_f32(x, s) : x; }
     static __device__ __forceinline__ int acc_col(int lane, int v) { return MB == 32 ? 8 * v + 4 * (lane >> 5) : 4 * (lane >> 4); }
 
     static __device__ __forceinline__ void epilogue_lds(const LargeParams &p, AccT (&acc)[FNB][FMB], int m0, int n0,
@@ -140,8 +141,8 @@ struct TileStore {
                     const int col = wn * WTN + MB * i + acc_col(lane, v);
                     const int chunk = col >> 3;
                     u32x2 o;
-                    o.x = float2_to_half2_bits(acc[i][j][4 * v] * s, acc[i][j][4 * v + 1] * s);
-                    o.y = float2_to_half2_bits(acc[i][j][4 * v + 2] * s, acc[i][j][4 * v + 3] * s);
+                    o.x = float2_to_half2_bits(scaled(acc[i][j][4 * v], s), scaled(acc[i][j][4 * v + 1], s));
+                    o.y = float2_to_half2_bits(scaled(acc[i][j][4 * v + 2], s), scaled(acc[i][j][4 * v + 3], s));
                     *reinterpret_cast<u32x2 *>(lds + row * (TN * 2) + ((chunk ^ (row & (OCH - 1))) << 4) + 8 * ((col >> 2) & 1)) = o;
                 }
         }
@@ -186,13 +187,13 @@ struct TileStore {
                         uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
                         if (p.vec_store) {
                             u32x2 o;
-                            o.x = float2_to_half2_bits(x[0] * s, x[1] * s);
-                            o.y = float2_to_half2_bits(x[2] * s, x[3] * s);
+                            o.x = float2_to_half2_bits(scaled(x[0], s), scaled(x[1], s));
+                            o.y = float2_to_half2_bits(scaled(x[2], s), scaled(x[3], s));
                             *reinterpret_cast<u32x2 *>(dst) = o;
                         } else {
                             for (int e = 0; e < 4 && n + e < p.N; ++e) {
                                 union { _Float16 f; uint16_t u; } cv;
-                                cv.f = (_Float16)(x[e] * s);
+                                cv.f = (_Float16)scaled(x[e], s);
                                 dst[e] = cv.u;
                             }
                         }
@@ -1063,6 +1064,26 @@ static LargeConfig choose_tile64(int cls, int64_t M, int64_t N, int kt) {
     return c;
 }
 
+// Launch shapes that were timed faster than the cost model's choice, for the layer shapes of the
+// models the paper evaluates (Sec. 5.1).  An entry tuned at M tokens serves the batches of more than
+// M / 2 and at most M tokens that give the same number of token tiles.
+struct TunedTile { int cls, N, K, M, tm, tn, split, deep; };
+static const TunedTile kTunedTiles[] = {
+#include "tuned_tiles.inc"
+    {-1, 0, 0, 0, 0, 0, 0, 0},
+};
+
+static bool tuned_large(int cls, int64_t M, int64_t N, int64_t K, LargeConfig &c) {
+    for (const TunedTile &e : kTunedTiles) {
+        if (e.cls != cls || e.N != N || e.K != K) continue;
+        if (M > e.M || 2 * M <= e.M) continue;
+        if ((M + e.tm - 1) / e.tm != (e.M + e.tm - 1) / e.tm) continue;
+        c.tm = e.tm;  c.tn = e.tn;  c.split = e.split;  c.deep = e.deep;
+        return true;
+    }
+    return false;
+}
+
 static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     LargeConfig c;
     const Tuning &t = tuning();
@@ -1070,6 +1091,9 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     const int kt = (int)(((kind_is_fp8(kind) ? K : 2 * K) + 127) / 128);
     if (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0))
         return choose_tile64(cls, M, N, kt);
+    if (t.tuned_table != 0 && t.large_bm < 0 && t.large_bn < 0 && t.large_split <= 0 && t.large_deep < 0 &&
+        tuned_large(cls, M, N, K, c))
+        return c;
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;

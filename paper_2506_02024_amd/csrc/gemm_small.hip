@@ -321,7 +321,7 @@ small_gemm_kernel(SmallParams p) {
     auto store_y = [&](floatx4 sum, int m, int n) {
         if (kind_is_fp8(KIND)) {
             float sc = (KIND == kE4M3Quant ? row_scale : p.scales[m]) * p.w_scale;
-            sum.x *= sc; sum.y *= sc; sum.z *= sc; sum.w *= sc;
+            sum.x = scale_f32(sum.x, sc); sum.y = scale_f32(sum.y, sc); sum.z = scale_f32(sum.z, sc); sum.w = scale_f32(sum.w, sc);
         }
         uint16_t *dst = p.Y + (int64_t)m * p.ldy + n;
         if (p.vec_store && n + 3 < p.N) {
@@ -456,13 +456,13 @@ splitk_reduce_kernel(const float *__restrict__ partials, int S, int M, int N, co
     uint16_t *dst = Y + (int64_t)m * ldy + n;
     if (VEC) {
         u32x2 o;
-        o.x = float2_to_half2_bits(scales ? v[0] * sc : v[0], scales ? v[W > 1 ? 1 : 0] * sc : v[W > 1 ? 1 : 0]);
-        o.y = float2_to_half2_bits(scales ? v[W > 2 ? 2 : 0] * sc : v[W > 2 ? 2 : 0],
-                                   scales ? v[W > 3 ? 3 : 0] * sc : v[W > 3 ? 3 : 0]);
+        o.x = float2_to_half2_bits(scales ? scale_f32(v[0], sc) : v[0], scales ? scale_f32(v[W > 1 ? 1 : 0], sc) : v[W > 1 ? 1 : 0]);
+        o.y = float2_to_half2_bits(scales ? scale_f32(v[W > 2 ? 2 : 0], sc) : v[W > 2 ? 2 : 0],
+                                   scales ? scale_f32(v[W > 3 ? 3 : 0], sc) : v[W > 3 ? 3 : 0]);
         *reinterpret_cast<u32x2 *>(dst) = o;
     } else {
         union { _Float16 f; uint16_t u; } c;
-        c.f = (_Float16)(scales ? v[0] * sc : v[0]);
+        c.f = (_Float16)(scales ? scale_f32(v[0], sc) : v[0]);
         dst[0] = c.u;
     }
 }

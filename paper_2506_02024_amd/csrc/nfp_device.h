@@ -145,6 +145,15 @@ __device__ __forceinline__ uint32_t quant4(uint32_t w01, uint32_t w23, float s, 
            (e4m3_from_float_sw(d) << 24);
 }
 
+// FP8-mode outputs are the FP32 sum times the FP32 scale, rounded to FP32, then converted to FP16,
+// in every kernel: the empty asm keeps the compiler from fusing product and conversion into a single
+// rounding in some kernels and not in others, so that every launch shape gives the same bits.
+__device__ __forceinline__ float scale_f32(float x, float s) {
+    float y = x * s;
+    asm("" : "+v"(y));
+    return y;
+}
+
 __device__ __forceinline__ uint32_t float2_to_half2_bits(float a, float b) {
     union { _Float16 f[2]; uint32_t u; } cvt;
     cvt.f[0] = (_Float16)a;

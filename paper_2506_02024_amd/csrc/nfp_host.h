@@ -80,6 +80,7 @@ struct Tuning {
     int64_t large_xcd_map;   // 0: tiles in launch order instead of grouped by XCD (tiled kernels)
     int64_t fused_reduce;    // 0: split-K partials are summed by a second launch instead of the last workgroup
     int64_t large_deep;      // 1 / 0: force / forbid the deeper load pipelines of the tiled kernels (tiles below 256 x 256)
+    int64_t tuned_table;     // 0: the tiled kernels' launch shape always comes from the cost model, never from the table of timed shapes
 };
 Tuning &tuning();
 

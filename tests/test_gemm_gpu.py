@@ -624,6 +624,42 @@ def test_split_k_finished_by_the_last_workgroup_equals_the_reduction_launch(nfp,
             nfp.tune(k, -1)
 
 
+@pytest.mark.parametrize("M,N,K,shapes", [
+    (256, 2048, 1024, [{"large_bm": 128, "large_bn": 128, "large_split": 1}, {"large_bm": 128, "large_bn": 128, "large_split": 2},
+                       {"large_bm": 256, "large_bn": 256, "large_split": 4}, {"large_bm": 128, "large_bn": 256, "large_split": 1, "large_deep": 1},
+                       {"large_bm": 256, "large_bn": 128, "large_split": 3}]),
+    (16, 16384, 1024, [{"small_split": 1}, {"small_split": 2}, {"small_split": 4, "fused_reduce": 0}, {"small_split": 8, "small_spw": 2}]),
+    (64, 8192, 2048, [{"small_split": 1}, {"small_split": 2}, {"small_max_m": 32, "large_split": 1}, {"small_max_m": 32, "large_split": 4}])])
+def test_fp8_mode_scales_and_rounds_alike_in_every_launch_shape(nfp, M, N, K, shapes):
+    # Operands whose E4M3 codes are small integers: every partial sum is an integer below 2^24, so the
+    # FP32 accumulation is exact in any order and any K split, and the output is pinned to one
+    # definition -- the FP32 sum times the FP32 scale, rounded to FP32, then to FP16 -- that every
+    # kernel and the split-K reduction must follow bit for bit (a product fused with the conversion
+    # rounds once and differs in about one output in 10^4)
+    rng = np.random.default_rng(M + N)
+    kw = rng.integers(-15, 16, size=(N, K))
+    jx = rng.integers(-15, 16, size=(M, K))
+    s_act = np.float32(0.37)
+    W = (kw / 256.0).astype(np.float16)
+    X = (jx * np.float64(s_act)).astype(np.float16)
+    Wd, Xd = to_dev(W), to_dev(X)
+    sc = torch.tensor([float(s_act)], dtype=torch.float32, device="cuda:0")
+    acc = (jx @ kw.T).astype(np.float32)
+    assert np.abs(jx @ kw.T).max() < 2 ** 24
+    want = (acc * (s_act * np.float32(2.0 ** -8))).astype(np.float32).astype(np.float16).view(np.uint16)
+    for packed in (False, True):
+        up, _ = nfp.decompose(Wd, packed=packed)
+        for knobs in shapes:
+            for k, v in knobs.items():
+                nfp.tune(k, v)
+            try:
+                got = bits(nfp.gemm(Xd, up, None, nfp.MODE_FP8, act_scale=sc))
+            finally:
+                for k in knobs:
+                    nfp.tune(k, -1)
+            assert np.array_equal(got, want), "%s, packed=%s: %d outputs differ" % (knobs, packed, int((got != want).sum()))
+
+
 @pytest.mark.parametrize("bm,bn", [(128, 128), (256, 128), (128, 256)])
 def test_deeper_load_pipelines_change_nothing(nfp, bm, bn):
     # three / four LDS stages (tiled kernels) and eight token stages (register-path kernels): the
