@@ -174,7 +174,8 @@ int nestedfp_workspace_init(void *workspace, size_t workspace_bytes, void *strea
  *   FP8 mode: quantises X per token (or with *act_scale, device float, if non-NULL),
  *     multiplies E4M3 activations by the upper plane read as E4M3, fp32 accumulation,
  *     scales by scale[m] * 2^-8 (Sec. 4.1: the upper plane is the weight times 2^8),
- *     fp16 output.  `lower` is never read and may be NULL.
+ *     fp16 output: the FP32 sum times the FP32 scale is rounded to FP32, then to FP16, in
+ *     every kernel and launch shape.  `lower` is never read and may be NULL.
  * workspace must hold at least nestedfp_gemm_workspace_size(M,N,K,mode) bytes.
  * nestedfp_gemm takes row-major planes, nestedfp_gemm_packed packed ones; same results bit
  * for bit.
