@@ -11,7 +11,7 @@
 namespace nfp {
 
 Tuning &tuning() {
-    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1, -1, -1, -1, -1};
+    static Tuning t = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, 1, -1, -1, -1, -1, -1};
     return t;
 }
 
@@ -562,7 +562,7 @@ int nestedfp_probe_mfma(const void *operands, int fp8, int iters, uint32_t *sink
 
 static const char *const kKnobs[] = {"small_max_m", "small_split", "small_spw", "small_tiles", "small_interleave",
                                      "large_split", "large_bm", "large_bn", "large_epilogue", "small_fuse_quant", "quant_hw", "large_xcd_map",
-                                     "fused_reduce", "large_deep", "tuned_table", nullptr};
+                                     "fused_reduce", "large_deep", "tuned_table", "quant_onepass", nullptr};
 
 const char *nestedfp_tune_name(int index) {
     if (index < 0 || index >= (int)(sizeof(kKnobs) / sizeof(kKnobs[0]))) return nullptr;
@@ -588,6 +588,7 @@ int nestedfp_tune(const char *knob, int64_t value) {
     else if (!strcmp(knob, "fused_reduce")) t.fused_reduce = value;
     else if (!strcmp(knob, "large_deep")) t.large_deep = value;
     else if (!strcmp(knob, "tuned_table")) t.tuned_table = value;
+    else if (!strcmp(knob, "quant_onepass")) t.quant_onepass = value;
     else return NESTEDFP_ERR_ARG;
     return NESTEDFP_OK;
 }

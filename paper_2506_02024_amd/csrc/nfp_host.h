@@ -81,6 +81,7 @@ struct Tuning {
     int64_t fused_reduce;    // 0: split-K partials are summed by a second launch instead of the last workgroup
     int64_t large_deep;      // 1 / 0: force / forbid the deeper load pipelines of the tiled kernels (tiles below 256 x 256)
     int64_t tuned_table;     // 0: the tiled kernels' launch shape always comes from the cost model, never from the table of timed shapes
+    int64_t quant_onepass;   // 1 / 0: force / forbid the single-pass activation quantisation (rows kept in registers) where it fits
 };
 Tuning &tuning();
 

@@ -58,7 +58,7 @@ quantize_act_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
 // Single-pass variant for rows that fit in registers (K <= 32768): every lane keeps its
 // 16-byte chunks between the maximum and the conversion, so the row is read once and the
 // kernel is one load latency shorter -- what matters for decode-sized batches, where this
-// kernel is pure latency.
+// kernel is pure latency, and for long rows, whose second read no longer comes from the cache.
 template <int CPT, bool HW>
 __global__ void __launch_bounds__(1024)
 quantize_act_onepass_kernel(const uint16_t *__restrict__ X, int64_t K, int64_t ldx,
@@ -121,8 +121,11 @@ int launch_quantize_act(const uint16_t *X, int64_t M, int64_t K, int64_t ldx,
                         const float *static_scale, uint8_t *Xq, float *scales, hipStream_t stream) {
     bool hw = tuning().quant_hw != 0;
     const int64_t chunks = K / 8;
-    if (M <= 256 && chunks <= 4096) {
-        // decode-sized: one pass, as many lanes as the row has chunks (up to 1024, 4 chunks each)
+    const int64_t onepass = tuning().quant_onepass;
+    // one pass for decode-sized batches (latency) and for long rows at any batch (measured at 8192
+    // tokens: 5.1-5.4 TB/s against 3.9 for K = 14336 / 28672, equal at K = 8192, 4 % behind at 4096)
+    if (chunks <= 4096 && (onepass > 0 || (onepass < 0 && (M <= 256 || chunks >= 1024)))) {
+        // as many lanes as the row has chunks (up to 1024, 4 chunks each)
         int cpt = chunks <= 1024 ? 1 : (chunks <= 2048 ? 2 : 4);
         int threads = (int)(((chunks + cpt - 1) / cpt + 63) / 64 * 64);
         if (cpt == 1) launch_onepass<1>(hw, threads, X, M, K, ldx, static_scale, Xq, scales, stream);

@@ -36,6 +36,24 @@ def test_gaussian_rows(nfp, hw, M, K):
     assert np.array_equal(Xq, Xq_ref)
 
 
+@pytest.mark.parametrize("M,K", [(300, 8208), (520, 14336), (260, 4096), (3, 32768), (270, 32784)])
+def test_single_pass_and_two_pass_kernels_agree_with_the_oracle(nfp, M, K):
+    # rows kept in registers between the maximum and the conversion (decode-sized batches and long
+    # rows) or read twice (the rest; rows beyond 32768 columns always): forced either way
+    X = workloads.act_host(M, K, seed=K)
+    X[1] = 0
+    X[2, K - 1] = np.float16(-65504.0)
+    Xq_ref, s_ref = oracle.quantize_act(X)
+    for onepass in (1, 0, -1):
+        nfp.tune("quant_onepass", onepass)
+        try:
+            Xq, s = nfp.quantize_act(to_dev(X))
+        finally:
+            nfp.tune("quant_onepass", -1)
+        assert np.array_equal(s.cpu().numpy(), s_ref), onepass
+        assert np.array_equal(Xq.cpu().numpy(), Xq_ref), onepass
+
+
 @pytest.mark.parametrize("hw", [1, 0])
 def test_every_finite_half_under_several_row_scales(nfp, hw):
     # each row holds every finite FP16 word whose magnitude does not exceed the row's maximum;
