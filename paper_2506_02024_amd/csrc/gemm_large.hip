@@ -1141,11 +1141,11 @@ template <int KIND, int TM, int TN, int WAVES_M, int WAVES_N, int NST = 2>
 static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) {
     auto kern = large_gemm_kernel<KIND, TM, TN, WAVES_M, WAVES_N, NST>;
     constexpr int lds = LargeKernel<KIND, TM, TN, WAVES_M, WAVES_N, NST>::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
@@ -1154,10 +1154,10 @@ template <int TM, int TN, int WK, bool DEEP = false>
 static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
     auto kern = nested_bypass_kernel<TM, TN, WK, DEEP>;
     constexpr int lds = BypassKernel<TM, TN, WK, DEEP>::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     kern<<<grid, 512, lds, stream>>>(p);
 }
@@ -1166,10 +1166,10 @@ template <int TM, int TN, bool ROWMAJOR>
 static void launch_e4m3_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
     auto kern = e4m3_bypass_kernel<TM, TN, ROWMAJOR>;
     constexpr int lds = E4m3BypassKernel<TM, TN, ROWMAJOR>::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     kern<<<grid, 512, lds, stream>>>(p);
 }

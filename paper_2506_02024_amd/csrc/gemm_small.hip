@@ -565,13 +565,13 @@ static void launch_small_t(const SmallParams &p, const SmallConfig &c, dim3 grid
     size_t lds = (size_t)((c.tiles_per_wg + 1) & ~1) * c.waves * MT * 64 * sizeof(floatx4);
     auto kern1 = small_gemm_kernel<KIND, MT, SPW, false>;
     auto kernp = small_gemm_kernel<KIND, MT, SPW, true>;
-    static bool attr_set = false;                    // once per instantiation
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};                    // once per instantiation
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern1),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernp),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     if (c.passes > 1) kernp<<<grid, c.waves * 64, lds, stream>>>(p);
     else kern1<<<grid, c.waves * 64, lds, stream>>>(p);
@@ -582,11 +582,11 @@ static void launch_small_quant(const SmallParams &p, const SmallConfig &c, dim3 
     size_t lds = (size_t)((c.tiles_per_wg + 1) & ~1) * c.waves * 64 * sizeof(floatx4);
     auto k2 = small_gemm_kernel<kE4M3Quant, 1, 2, false>;
     auto k4 = small_gemm_kernel<kE4M3Quant, 1, 4, false>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     if (c.spw == 2) k2<<<grid, c.waves * 64, lds, stream>>>(p);
     else k4<<<grid, c.waves * 64, lds, stream>>>(p);

@@ -156,6 +156,44 @@ def test_calls_on_two_streams_do_not_interfere(nfp):
         assert torch.equal(outs[0], alone[0]) and torch.equal(outs[1], alone[1])
 
 
+def test_calls_from_two_host_threads(nfp):
+    # the entry points may be called from several host threads at once (own stream, own workspace,
+    # nobody changing a tuning knob meanwhile): each thread gets what it gets alone
+    import threading
+
+    probs = []
+    for j, (M, N, K) in enumerate([(16, 2048 + 8, 4096), (130, 1024 + 24, 2048)]):
+        W = workloads.weight_host(N, K, seed=80 + j)
+        up, lo = nfp.decompose(to_dev(W), packed=(j == 1))
+        X = to_dev(workloads.act_host(M, K, seed=90 + j))
+        ws = nfp.new_workspace(max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)) + 256, "cuda:0")
+        alone = (nfp.gemm(X, up, lo, nfp.MODE_FP16, workspace=ws).clone(), nfp.gemm(X, up, None, nfp.MODE_FP8, workspace=ws).clone())
+        probs.append((X, up, lo, ws, alone, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(X, up, lo, ws, alone, st):
+        try:
+            with torch.cuda.stream(st):
+                out16, out8 = torch.empty_like(alone[0]), torch.empty_like(alone[1])
+                for rep in range(40):
+                    nfp.gemm(X, up, lo, nfp.MODE_FP16, out=out16, workspace=ws)
+                    nfp.gemm(X, up, None, nfp.MODE_FP8, out=out8, workspace=ws)
+                st.synchronize()
+                if not (torch.equal(out16, alone[0]) and torch.equal(out8, alone[1])):
+                    errors.append("results differ")
+        except Exception as e:                          # noqa: BLE001 - reported below
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=pr) for pr in probs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+
+
 def test_empty_batch_and_empty_layer(nfp):
     # M = 0 and N = 0 are legal and launch nothing: the output keeps what it held
     K = 64
