@@ -43,6 +43,7 @@ def parse():
                     help="plane storage the timed step runs on (the other one is reported under extra)")
     ap.add_argument("--bursts", type=int, default=7, help="repetitions per comparison (median is reported)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the compute-bound extras")
+    ap.add_argument("--no-vendor", action="store_true", help="leave the vendor library's GEMMs out of the compute-bound extras")
     ap.add_argument("--no-70b", action="store_true", help="skip the Llama-3-70B subset (configs[3])")
     ap.add_argument("--no-mode-switch", action="store_true", help="skip the mode-alternation run (configs[4])")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -330,7 +331,7 @@ def main():
         del src, dst
     del replay, legs
     if not args.no_prefill:
-        extra["prefill"] = prefill_extras(torch, nfp, workloads, stack, timer, dev, args.bursts)
+        extra["prefill"] = prefill_extras(torch, nfp, workloads, stack, timer, dev, args.bursts, vendor=not args.no_vendor)
     if not args.no_mode_switch:
         extra["mode_switch_steps"] = mode_switch_extras(torch, nfp, workloads, stack, L, dev)
     if args.switch_demo:
@@ -423,10 +424,13 @@ def achievable_rates(torch, nfp, workloads, stack, timer, dev):
     return out
 
 
-def prefill_extras(torch, nfp, workloads, stack, timer, dev, bursts):
+def prefill_extras(torch, nfp, workloads, stack, timer, dev, bursts, vendor=True):
     """Compute-bound regime (configs[2]): the same four linears at M in {512, 2048, 8192}; both
     modes, both plane layouts and the plain baselines, interleaved; layers rotated so that the
-    weights are cold."""
+    weights are cold.  With `vendor`, the vendor library's GEMMs (torch.mm and torch._scaled_mm,
+    i.e. hipBLASLt) run in the same interleaving on the same operands, as context for what this
+    chip sustains: they are no part of the path, and the FP8 one reads the row-major upper plane
+    as the E4M3 tensor it is, activations quantised beforehand, unit scales."""
     shapes = workloads.LLAMA3_8B
     out = {}
     n_layers = len(stack) // 4
@@ -454,6 +458,19 @@ def prefill_extras(torch, nfp, workloads, stack, timer, dev, bursts):
                 # the FP8-mode GEMM launch alone: activations quantised beforehand (outside the timing)
                 "fp8_prequantized/packed": lambda i: nfp.gemm_fp8_prequantized(Xq, sq, ent(i)["packed"][0], out=Yb, workspace=ws),
             }
+            if vendor:
+                calls["vendor_fp16/rowmajor"] = lambda i: torch.mm(X, ent(i)["W"].t(), out=Yb)
+                try:
+                    one = torch.ones((), dtype=torch.float32, device=dev)
+                    Xq8 = Xq.view(torch.float8_e4m3fn)
+
+                    def vendor_fp8(i):
+                        torch._scaled_mm(Xq8, ent(i)["rowmajor"][0].view(torch.float8_e4m3fn).t(), scale_a=one, scale_b=one,
+                                         out_dtype=torch.float16)
+                    vendor_fp8(0)
+                    calls["vendor_fp8/rowmajor"] = vendor_fp8
+                except Exception:                       # noqa: BLE001 - context only: left out where the library refuses
+                    pass
             launches = 50 if M <= 2048 else 20
             res = {}
             for key, ts in timer.run(calls, launches, bursts).items():
