@@ -1089,11 +1089,11 @@ static LargeConfig choose_large(int kind, int64_t M, int64_t N, int64_t K) {
     const Tuning &t = tuning();
     const int cls = kind_class(kind);                  // cost tables: plain FP16 through LDS, FP16 through registers, E4M3
     const int kt = (int)(((kind_is_fp8(kind) ? K : 2 * K) + 127) / 128);
-    if (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0))
-        return choose_tile64(cls, M, N, kt);
     if (t.tuned_table != 0 && t.large_bm < 0 && t.large_bn < 0 && t.large_split <= 0 && t.large_deep < 0 &&
         tuned_large(cls, M, N, K, c))
         return c;
+    if (t.large_bm == 64 || (M <= 64 && t.large_bm < 0 && t.large_bn < 0))
+        return choose_tile64(cls, M, N, kt);
     double best = 1e30;
     c.tm = c.tn = 256;
     c.split = 1;

@@ -7,9 +7,11 @@ The tiled kernels pick tile shape, K split and pipeline depth from a small cost 
 within a few per cent of the best choice on average, but off by 10-30 % at some points of the
 ridge between the memory-bound and the compute-bound regime (M = 128 ... 512).  This script times
 every legal choice through the tuning knobs -- on the layer shapes of the models the paper evaluates
-(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 128 ... 2048, for the three
+(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 64 ... 2048, for the three
 classes of weights (FP16 row-major, FP16 through registers = NestedFP planes, E4M3) -- and records a
-choice only where it beats the model's by more than the margin.  Other shapes keep the model.
+choice only where it beats the model's by more than the margin.  At M = 64 the layers that the
+library routes to its 64-token tiles are timed over the K split alone (on the others the knobs
+change nothing and nothing is recorded).  Other shapes keep the model.
 Rebuild the library after running it.
 """
 import argparse
@@ -27,7 +29,7 @@ MODEL_SHAPES = {
     "phi-4-14b": [(7680, 5120), (5120, 5120), (35840, 5120), (5120, 17920)],
     "mistral-small-24b": [(6144, 5120), (5120, 4096), (65536, 5120), (5120, 32768)],
 }
-M_POINTS = (128, 256, 512, 1024, 2048)
+M_POINTS = (64, 128, 256, 512, 1024, 2048)      # 64: the 64-token tiles, where only the K split is open
 TILES = ((256, 256), (256, 128), (128, 256), (128, 128))
 SPLITS = (1, 2, 3, 4, 6, 8)
 KNOBS = ("large_bm", "large_bn", "large_split", "large_deep")
@@ -89,11 +91,11 @@ def main():
                     t_model = timeit(fns)
                     best = (t_model, None)
                     kt = (K if cls == 2 else 2 * K) // 128
-                    for bm, bn in TILES:
+                    for bm, bn in (TILES if M > 64 else ((64, 128),)):
                         for sp in SPLITS:
                             if sp > 1 and sp > kt // 4:
                                 continue
-                            for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 else (0, 1)):
+                            for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 or M <= 64 else (0, 1)):
                                 for k, v in zip(KNOBS, (bm, bn, sp, deep)):
                                     nfp.tune(k, v)
                                 try:
