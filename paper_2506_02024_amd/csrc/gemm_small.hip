@@ -17,6 +17,8 @@
 // chunk order is the lane order, so that every load of a wave is one contiguous kilobyte.
 // Columns past K and rows past N are never multiplied: their loads are sent out of the buffer's
 // range and return zero, whatever the memory behind them holds.
+#include <algorithm>
+
 #include "nfp_device.h"
 #include "nfp_host.h"
 
@@ -536,13 +538,29 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
         c.waves = max_waves;
         c.passes = (slices + split * max_waves - 1) / (split * max_waves);
     }
-    // one workgroup per CU where the layer is large enough, otherwise one tile each
-    int64_t per = (tiles * c.split + 255) / 256;
-    if (per >= 6) per = 8;        // measured: fewer, longer workgroups win once the layer is large
+    // Tiles per workgroup.  A workgroup keeps a kilobyte of partial sums per tile and wave in LDS (an
+    // even number of slots, 128 KB at most).  The launch runs in rounds of one workgroup per CU and is
+    // bound by the weight stream, which 224 workgroups fill; with fewer each one gets faster, but only
+    // up to about twice as fast on an empty chip.  A round of R workgroups therefore costs its tiles
+    // times R / 256 from 224 workgroups on and 0.875 (1 - 0.43 (224 - R) / 224) below (fitted to
+    // timings of 1 ... 12 tiles per workgroup on eight layer shapes), plus half a tile for its ramp and
+    // tail.  Cheapest wins, the larger count on a tie (fewer workgroups fetch the activations).
+    const int slots_max = 128 / (c.waves * c.mt);
+    int per_max = slots_max & ~1;                      // (an odd count takes a spare slot)
+    if (per_max < 1) per_max = 1;
+    if (per_max > 16) per_max = 16;
+    int64_t per = 1;
+    double best = 1e30;
+    for (int cand = 1; cand <= per_max; ++cand) {
+        const int64_t wgs = ((tiles + cand - 1) / cand) * c.split;
+        const int64_t full = wgs / 256, rem = wgs % 256;
+        const double part = rem >= 224 ? (double)rem / 256.0 : 0.875 * (1.0 - 0.43 * (double)(224 - rem) / 224.0);
+        double cost = (double)cand * ((double)full + (rem ? part : 0.0)) + 0.5 * (double)(full + (rem ? 1 : 0));
+        if (cost <= best) { best = cost;  per = cand; }
+    }
     if (pair_slices && t.small_split <= 0) per = 2 * ((tiles + 255) / 256);
     if (t.small_tiles > 0) per = t.small_tiles;
-    const int tmax = 128 / (max_waves * c.mt) > 8 ? 8 : 128 / (max_waves * c.mt);   // LDS slots <= 128 KB
-    if (per > tmax) per = tmax;
+    if (per > per_max) per = per_max;
     if (per < 1) per = 1;
     c.tiles_per_wg = (int)per;
     return c;
