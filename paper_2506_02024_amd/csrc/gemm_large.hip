@@ -1047,15 +1047,20 @@ static LargeConfig choose_tile64(int cls, int64_t M, int64_t N, int kt) {
     c.tm = 64;  c.tn = 128;  c.split = 1;  c.deep = 0;
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
     double best = 1e30;
-    for (int split = 1; split <= 8; split *= 2) {
+    for (int split : {1, 2, 3, 4, 6, 8}) {
         if (t.large_split > 0) split = (int)(t.large_split < kt ? t.large_split : kt);
         else if (split > 1 && split > kt / 4) break;
         const int per = (kt + split - 1) / split;
         const int slices = (kt + per - 1) / per;
         const int64_t wgs = tiles * slices;
-        double time = (double)((wgs + tc.slots - 1) / tc.slots) * (tc.tfix + per * tc.tk);
+        const int64_t rounds = (wgs + tc.slots - 1) / tc.slots;
+        double time = (double)rounds * (tc.tfix + per * tc.tk);
         double floor_t = (double)N * (double)kt * 128.0 / (wgs < 512 ? tc.rate : tc.rate512);
         if (wgs < 256) floor_t *= std::pow(256.0 / (double)wgs, tc.few);
+        // the weight stream is shared per CU: workgroups beyond one per CU that do not make a whole
+        // further round leave most CUs waiting for a few (measured: 320 workgroups take 1.3-1.5 times
+        // as long as 240 with the same bytes)
+        if (wgs > 256) floor_t *= (double)(((wgs + 255) / 256) * 256) / (double)wgs;
         if (time < floor_t) time = floor_t;
         if (slices > 1) time += split_cost(M, N, slices, 4.56, 4.24e6);
         if (time < best) { best = time;  c.split = split; }

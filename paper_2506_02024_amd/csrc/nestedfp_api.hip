@@ -39,16 +39,18 @@ static bool route_small(int kind, int64_t M, int64_t N, int64_t K, int64_t ldw) 
     if (!use_small_gemm(M) || !small_gemm_supports(kind, M, N, K, ldw)) return false;
     if (tuning().small_max_m >= 0) return true;
     const int cls = kind_class(kind);
-    // measured: with three or four token tiles per wave the streaming kernel falls behind the
-    // tiled NestedFP kernel (whose weights bypass LDS) on the widest layers (gate/up projections)
-    if (cls == 1 && M > 32 && N >= 16384) return false;
-    // and from 49 tokens on everywhere but on the smallest layers (64-token tiles, split along K)
-    if (cls == 1 && M > 48 && (N > 4096 || K > 4096)) return false;
-    // the plain FP16 kernels: the same from 49 tokens on, and from 33 on where both N and K are large
-    if (cls == 0 && ((M > 48 && (N > 4096 || K > 4096)) || (M > 32 && N >= 8192 && K >= 8192))) return false;
-    // E4M3 weights: where the layer is large enough for the 64-token tiles to pay, from 33 tokens on
-    // on the widest layers, from 49 on those with a long K
-    if (cls == 2 && ((M > 32 && N >= 16384) || (M > 48 && K >= 14336))) return false;
+    // Timed on the 18 layer shapes of the paper's five models at 12 ... 64 tokens, all three classes:
+    // with three or four token tiles per wave (33 tokens and more) the streaming kernel is behind
+    // the 64-token tiles of the tiled kernels (split along K) on every shape, by 9-97 %;
+    if (M > 32) return false;
+    // with two token tiles (17 ... 32 tokens) it is behind by 5-30 % except on the smallest layers
+    // (and, for plain row-major FP16 weights, on layers of 4096 rows); up to 16 tokens it stays
+    const int64_t weights = N * K;
+    if (M > 16) {
+        if (cls == 1 && weights >= ((int64_t)20 << 20)) return false;
+        if (cls == 2 && weights >= ((int64_t)50 << 20)) return false;
+        if (cls == 0 && N >= 5120) return false;
+    }
     return true;
 }
 

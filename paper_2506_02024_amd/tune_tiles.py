@@ -7,10 +7,10 @@ The tiled kernels pick tile shape, K split and pipeline depth from a small cost 
 within a few per cent of the best choice on average, but off by 10-30 % at some points of the
 ridge between the memory-bound and the compute-bound regime (M = 128 ... 512).  This script times
 every legal choice through the tuning knobs -- on the layer shapes of the models the paper evaluates
-(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 64 ... 2048, for the three
+(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 32 ... 2048, for the three
 classes of weights (FP16 row-major, FP16 through registers = NestedFP planes, E4M3) -- and records a
-choice only where it beats the model's by more than the margin.  At M = 64 the layers that the
-library routes to its 64-token tiles are timed over the K split alone (on the others the knobs
+choice only where it beats the model's by more than the margin.  At M = 32 and 64 the layers that
+the library routes to its 64-token tiles are timed over the K split alone (on the others the knobs
 change nothing and nothing is recorded).  Other shapes keep the model.
 Rebuild the library after running it.
 """
@@ -29,7 +29,7 @@ MODEL_SHAPES = {
     "phi-4-14b": [(7680, 5120), (5120, 5120), (35840, 5120), (5120, 17920)],
     "mistral-small-24b": [(6144, 5120), (5120, 4096), (65536, 5120), (5120, 32768)],
 }
-M_POINTS = (64, 128, 256, 512, 1024, 2048)      # 64: the 64-token tiles, where only the K split is open
+M_POINTS = (32, 64, 128, 256, 512, 1024, 2048)  # 32, 64: the 64-token tiles, where only the K split is open
 TILES = ((256, 256), (256, 128), (128, 256), (128, 128))
 SPLITS = (1, 2, 3, 4, 6, 8)
 KNOBS = ("large_bm", "large_bn", "large_split", "large_deep")
@@ -56,6 +56,7 @@ def main():
     def timeit(fns, launches=8, bursts=3):
         # fns: the same call on different copies of the weights, taken in turn so that no copy is
         # still in the memory-side cache when its turn comes again
+        launches = max(launches, len(fns))
         for f in fns:
             f()
         torch.cuda.synchronize()
@@ -73,7 +74,9 @@ def main():
     rows = []
     t0 = time.time()
     for N, K in shapes:
-        copies = max(1, min(8, -(-600_000_000 // (2 * N * K))))
+        # enough copies that even the E4M3 plane alone (N*K bytes per call) cycles through more than
+        # four times the 256 MB memory-side cache
+        copies = max(2, min(64, -(-1_200_000_000 // (N * K))))
         Ws = [workloads.weight_device(N, K, 0.02, seed=i) for i in range(copies)]
         planes = [nfp.decompose(W, packed=True) for W in Ws]
         for M in M_POINTS:
