@@ -94,11 +94,12 @@ def main():
                     t_model = timeit(fns)
                     best = (t_model, None)
                     kt = (K if cls == 2 else 2 * K) // 128
-                    for bm, bn in (TILES if M > 64 else ((64, 128),)):
+                    # (the 64-token tiles also compete at 128 and 256 tokens, as two and four token tiles)
+                    for bm, bn in (((64, 128),) if M <= 64 else (TILES + ((64, 128),) if M <= 256 else TILES)):
                         for sp in SPLITS:
                             if sp > 1 and sp > kt // 4:
                                 continue
-                            for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 or M <= 64 else (0, 1)):
+                            for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 or bm == 64 else (0, 1)):
                                 for k, v in zip(KNOBS, (bm, bn, sp, deep)):
                                     nfp.tune(k, v)
                                 try:

@@ -540,6 +540,15 @@ def test_llama70b_shapes_structured_sample(nfp, name):
                      pin_sets=_default_pins)
 
 
+@pytest.mark.parametrize("N,K,Ms", [(4096, 4096, [17, 24, 33, 48, 100, 128, 200, 256]), (6144, 4096, [20, 40, 96, 250]),
+                                    (5120, 14336, [12, 17, 32, 40, 128])])
+def test_batches_between_the_kernel_families_structured_sample(nfp, N, K, Ms):
+    # 17 ... 256 tokens: where the built-in choice moves from the streaming kernel to the 64-token tiles
+    # (by class and layer size) and where the table of timed launch shapes puts 64-token tiles under
+    # batches of 128 and 256 tokens on small layers
+    _full_size_check(nfp, N, K, Ms, workloads.SIGMA_W_8B, "N=%d K=%d" % (N, K), seed=N % 83, pin_sets=_default_pins)
+
+
 @pytest.mark.parametrize("N,K,M", [(40, 32, 70000), (256, 65536, 8), (264, 65536 + 16, 70), (1000, 16, 1000), (4096, 4096, 20000)])
 def test_extreme_aspect_ratios_sampled(nfp, N, K, M):
     # tens of thousands of tokens on a sliver of a layer, the longest rows, the shortest K, a prefill
