@@ -486,10 +486,27 @@ int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, con
 // ---- host-side configuration ---------------------------------------------------------
 struct SmallConfig { int mt, spw, waves, split, passes, tiles_per_wg; };
 
+// Launch shapes of the streaming kernel that were timed faster than the rules below choose, on the
+// layer shapes of the models the paper evaluates (Sec. 5.1), for batches of up to 16 tokens.
+struct TunedSmall { int cls, N, K, spw, split, tiles; };
+static const TunedSmall kTunedSmall[] = {
+#include "tuned_small.inc"
+    {-1, 0, 0, 0, 0, 0},
+};
+
 static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const Tuning &t = tuning();
     SmallConfig c;
     c.mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    // knobs first; with none set, the table of timed shapes; otherwise the rules
+    int64_t k_spw = t.small_spw, k_split = t.small_split, k_tiles = t.small_tiles;
+    if (k_spw <= 0 && k_split <= 0 && k_tiles <= 0 && t.tuned_table != 0 && c.mt == 1) {
+        for (const TunedSmall &e : kTunedSmall)
+            if (e.cls == kind_class(kind) && e.N == N && e.K == K) {
+                k_spw = e.spw;  k_split = e.split;  k_tiles = e.tiles;
+                break;
+            }
+    }
     const bool fp8 = kind_is_fp8(kind), nested = kind_class(kind) == 1;
     const int kstep = fp8 ? 128 : 64;
     const int steps = (int)((K + kstep - 1) / kstep);
@@ -497,7 +514,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     // wave (512 contiguous bytes of each row), 8 waves (measured: 8-10 % faster than 4 x 16);
     // the packed planes are contiguous per tile whatever the slice and gain nothing from it.
     const bool can_long = (kind == kPlainF16 || kind == kNestedF16Row) && M <= 16 && (K + 63) / 64 >= 64;
-    const bool long_slices = can_long && (t.small_spw == 8 || (kind == kPlainF16 && t.small_spw <= 0));
+    const bool long_slices = can_long && (k_spw == 8 || (kind == kPlainF16 && k_spw <= 0));
     const int max_waves = (c.mt == 4 || long_slices) ? 8 : 16;     // four token tiles need 256 VGPRs per wave
     const int64_t tiles = (N + 15) / 16;
     // K-steps per wave: 2 with several token tiles (their activations need the registers) and
@@ -506,7 +523,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     c.spw = 4;
     if ((steps + 3) / 4 < 16 && steps >= 2) c.spw = 2;
     if (tiles >= 1024 && !nested) c.spw = 2;
-    if ((t.small_spw == 2 || t.small_spw == 4)) c.spw = (int)t.small_spw;
+    if (k_spw == 2 || k_spw == 4) c.spw = (int)k_spw;
     if (c.mt > 1) c.spw = 2;
     if (long_slices) c.spw = 8;
     const int slices = (steps + c.spw - 1) / c.spw;               // wave-sized K slices
@@ -529,7 +546,7 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
     const bool pair_slices = !fp8 && c.mt == 1 && rounds == 1 && tiles >= 256 && tiles <= 512 && slices >= 2 &&
                              t.fused_reduce != 0;
     if (pair_slices) split = 2;
-    if (t.small_split > 0) split = (int)t.small_split;
+    if (k_split > 0) split = (int)k_split;
     if (split > slices) split = slices;
     c.split = split;
     c.passes = (rounds + split - 1) / split;
@@ -558,8 +575,8 @@ static SmallConfig choose_small(int kind, int64_t M, int64_t N, int64_t K) {
         double cost = (double)cand * ((double)full + (rem ? part : 0.0)) + 0.5 * (double)(full + (rem ? 1 : 0));
         if (cost <= best) { best = cost;  per = cand; }
     }
-    if (pair_slices && t.small_split <= 0) per = 2 * ((tiles + 255) / 256);
-    if (t.small_tiles > 0) per = t.small_tiles;
+    if (pair_slices && k_split <= 0) per = 2 * ((tiles + 255) / 256);
+    if (k_tiles > 0) per = k_tiles;
     if (per > per_max) per = per_max;
     if (per < 1) per = 1;
     c.tiles_per_wg = (int)per;
