@@ -8,7 +8,7 @@ The tiled kernels pick tile shape, K split and pipeline depth from a small cost 
 within a few per cent of the best choice on average, but off by 10-30 % at some points of the
 ridge between the memory-bound and the compute-bound regime (M = 128 ... 512).  This script times
 every legal choice through the tuning knobs -- on the layer shapes of the models the paper evaluates
-(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 32 ... 2048, for the three
+(Sec. 5.1: Llama 3.1 8B / 70B, Mistral Nemo, Phi-4, Mistral Small), at M = 32 ... 8192, for the three
 classes of weights (FP16 row-major, FP16 through registers = NestedFP planes, E4M3) -- and records a
 choice only where it beats the model's by more than the margin.  At M = 32 and 64 the layers that
 the library routes to its 64-token tiles are timed over the K split alone (on the others the knobs
@@ -33,7 +33,8 @@ MODEL_SHAPES = {
     "phi-4-14b": [(7680, 5120), (5120, 5120), (35840, 5120), (5120, 17920)],
     "mistral-small-24b": [(6144, 5120), (5120, 4096), (65536, 5120), (5120, 32768)],
 }
-M_POINTS = (32, 64, 128, 256, 512, 1024, 2048)  # 32, 64: the 64-token tiles, where only the K split is open
+M_POINTS = (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192)  # 32, 64: the 64-token tiles, where only the K split is open;
+# 4096, 8192: no K split (the chip is full)
 TILES = ((256, 256), (256, 128), (128, 256), (128, 128))
 SPLITS = (1, 2, 3, 4, 6, 8)
 KNOBS = ("large_bm", "large_bn", "large_split", "large_deep")
@@ -171,7 +172,9 @@ def main():
         for M in M_POINTS:
             X = workloads.act_device(M, K, seed=2)
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
-            ws = nfp.new_workspace(8 * M * N * 4 + M * K + 4 * M + (1 << 20), dev)
+            # room for any split that is tried (up to 8 below 4096 tokens, the built-in choice above)
+            ws = nfp.new_workspace(max((8 if M < 4096 else 0) * M * N * 4 + M * K + 4 * M,
+                                       max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1))) + (1 << 20), dev)
             calls = {
                 0: [lambda W=W: nfp.plain_gemm_fp16(X, W, out=Y, workspace=ws) for W in Ws],
                 1: [lambda p=p: nfp.gemm(X, p[0], p[1], nfp.MODE_FP16, out=Y, workspace=ws) for p in planes],
@@ -185,7 +188,7 @@ def main():
                     kt = (K if cls == 2 else 2 * K) // 128
                     # (the 64-token tiles also compete at 128 and 256 tokens, as two and four token tiles)
                     for bm, bn in (((64, 128),) if M <= 64 else (TILES + ((64, 128),) if M <= 256 else TILES)):
-                        for sp in SPLITS:
+                        for sp in (SPLITS if M < 4096 else (1,)):
                             if sp > 1 and sp > kt // 4:
                                 continue
                             for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 or bm == 64 else (0, 1)):
