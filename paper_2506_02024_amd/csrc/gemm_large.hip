@@ -1071,7 +1071,7 @@ static LargeConfig choose_tile64(int cls, int64_t M, int64_t N, int kt) {
 
 // Launch shapes that were timed faster than the cost model's choice, for the layer shapes of the
 // models the paper evaluates (Sec. 5.1).  An entry tuned at M tokens serves the batches of more than
-// M / 2 and at most M tokens that give the same number of token tiles.
+// 3 M / 4 (M / 2 up to 64 tokens) and at most M tokens that give the same number of token tiles.
 struct TunedTile { int cls, N, K, M, tm, tn, split, deep; };
 static const TunedTile kTunedTiles[] = {
 #include "tuned_tiles.inc"
@@ -1081,7 +1081,9 @@ static const TunedTile kTunedTiles[] = {
 static bool tuned_large(int cls, int64_t M, int64_t N, int64_t K, LargeConfig &c) {
     for (const TunedTile &e : kTunedTiles) {
         if (e.cls != cls || e.N != N || e.K != K) continue;
-        if (M > e.M || 2 * M <= e.M) continue;
+        // (batches of up to 64 tokens are one 64-token tile whatever their size; above, a shape timed
+        // at M tokens is trusted down to three quarters of M)
+        if (M > e.M || (e.M <= 64 ? 2 * M <= e.M : 4 * M <= 3 * e.M)) continue;
         if ((M + e.tm - 1) / e.tm != (e.M + e.tm - 1) / e.tm) continue;
         c.tm = e.tm;  c.tn = e.tn;  c.split = e.split;  c.deep = e.deep;
         return true;

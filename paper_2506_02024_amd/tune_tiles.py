@@ -33,7 +33,7 @@ MODEL_SHAPES = {
     "phi-4-14b": [(7680, 5120), (5120, 5120), (35840, 5120), (5120, 17920)],
     "mistral-small-24b": [(6144, 5120), (5120, 4096), (65536, 5120), (5120, 32768)],
 }
-M_POINTS = (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192)  # 32, 64: the 64-token tiles, where only the K split is open;
+M_POINTS = (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 4096, 8192)  # 32, 64: the 64-token tiles, where only the K split is open;
 # 4096, 8192: no K split (the chip is full)
 TILES = ((256, 256), (256, 128), (128, 256), (128, 128))
 SPLITS = (1, 2, 3, 4, 6, 8)
@@ -173,8 +173,12 @@ def main():
             X = workloads.act_device(M, K, seed=2)
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
             # room for any split that is tried (up to 8 below 4096 tokens, the built-in choice above)
-            ws = nfp.new_workspace(max((8 if M < 4096 else 0) * M * N * 4 + M * K + 4 * M,
-                                       max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1))) + (1 << 20), dev)
+            need = (8 if M < 4096 else 0) * M * N * 4 + M * K + 4 * M
+            for table in (-1, 0):                       # with and without the table that is compiled in now
+                nfp.tune("tuned_table", table)
+                need = max(need, max(nfp.gemm_workspace_size(M, N, K, m) for m in (0, 1)))
+            nfp.tune("tuned_table", -1)
+            ws = nfp.new_workspace(need + (1 << 20), dev)
             calls = {
                 0: [lambda W=W: nfp.plain_gemm_fp16(X, W, out=Y, workspace=ws) for W in Ws],
                 1: [lambda p=p: nfp.gemm(X, p[0], p[1], nfp.MODE_FP16, out=Y, workspace=ws) for p in planes],

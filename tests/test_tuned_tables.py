@@ -21,7 +21,7 @@ def test_tiled_kernel_table_holds_legal_launch_shapes():
     for cls, N, K, M, tm, tn, split, deep in rows("tuned_tiles.inc"):
         assert cls in (0, 1, 2)
         assert N > 0 and K > 0 and K % 16 == 0
-        assert M in (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192)
+        assert M in (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 4096, 8192)
         assert (tm, tn) in ((64, 128), (128, 128), (128, 256), (256, 128), (256, 256))
         assert split in (1, 2, 3, 4, 6, 8)
         if tm == 64:
