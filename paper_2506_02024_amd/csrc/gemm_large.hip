@@ -1227,8 +1227,9 @@ bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw) {
 int launch_large_gemm(int kind, const GemmArgs &a, hipStream_t stream) {
     if (!large_gemm_supports(kind, a.K, a.ldx, a.ldw)) return kErrShape;
     LargeConfig c = choose_large(kind, a.M, a.N, a.K);
-    // the register-path kernels take the deeper pipeline only when it is asked for
-    if (kind_class(kind) == 1) c.deep = tuning().large_deep > 0 && !(c.tm == 256 && c.tn == 256) && c.tm != 64 && c.tm <= 128;
+    // the register-path kernels take the deeper pipeline only where it is asked for (knob) or was
+    // timed faster (table), and only on the tiles of 128 tokens
+    if (kind_class(kind) == 1) c.deep = (tuning().large_deep > 0 || (c.deep && tuning().large_deep != 0)) && c.tm == 128;
     LargeParams p;
     p.X = static_cast<const uint8_t *>(a.X);
     p.x_row_bytes = kind_is_fp8(kind) ? a.ldx : 2 * a.ldx;

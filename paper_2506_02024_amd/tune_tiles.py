@@ -195,7 +195,7 @@ def main():
                         for sp in (SPLITS if M < 4096 else (1,)):
                             if sp > 1 and sp > kt // 4:
                                 continue
-                            for deep in ((0,) if (bm, bn) == (256, 256) or cls == 1 or bm == 64 else (0, 1)):
+                            for deep in ((0,) if (bm, bn) == (256, 256) or bm == 64 or (cls == 1 and bm != 128) else (0, 1)):
                                 for k, v in zip(KNOBS, (bm, bn, sp, deep)):
                                     nfp.tune(k, v)
                                 try:

@@ -29,7 +29,7 @@ def test_tiled_kernel_table_holds_legal_launch_shapes():
         else:
             assert M > 64                                 # batches of up to 64 tokens take 64-token tiles only
         if deep:
-            assert cls in (0, 2) and (tm, tn) != (256, 256)   # the kernels whose weights go through LDS, smaller tiles
+            assert (tm, tn) != (256, 256) and (cls != 1 or tm == 128)   # smaller tiles; the register path on 128 tokens only
         kt = (K if cls == 2 else 2 * K) // 128
         assert split == 1 or split <= kt // 4
         assert (cls, N, K, M) not in seen                 # one entry per problem
