@@ -632,7 +632,8 @@ def switch_demo_extras(torch, nfp, workloads, stack, layout, dev):
     rng = np.random.default_rng(7)
     choices = np.array([16, 32, 64, 128, 256, 512, 1024, 2048, 4096])
     # mostly small decode steps with bursts of large prefill-heavy steps
-    seq = [int(choices[min(8, int(abs(rng.normal(0, 1.6)) + (4 if rng.random() < 0.25 else 0)))]) for _ in range(48)]
+    # (a burst is 1024 tokens or more: the policy's threshold is crossed by about one step in six)
+    seq = [int(choices[min(8, int(abs(rng.normal(0, 1.6)) + (6 if rng.random() < 0.25 else 0)))]) for _ in range(48)]
     bufs = {M: _stack_buffers(torch, nfp, workloads, M, dev) for M in sorted(set(seq))}
     res = {}
     for policy in ("always_fp16", "always_fp8", "threshold_1024"):
