@@ -194,6 +194,21 @@ def test_calls_from_two_host_threads(nfp):
     assert not errors, errors
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_against_the_oracle(nfp, seed):
+    # eight seeded problems per case: M in 1 ... 300 (all kernel families and the batch sizes where the
+    # built-in choice moves between them), N in 1 ... 700, K any multiple of 16 up to 3072, both
+    # modes, both plane layouts, the plain baselines -- everything run_both_modes checks
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(8):
+        M = int(rng.choice([1, 2, 7, 16, 17, 24, 31, 32, 33, 47, 48, 64, 65, 100, 128, 129, 200, 256, 257, 300]))
+        N = int(rng.integers(1, 701))
+        K = 16 * int(rng.integers(1, 193))
+        W = workloads.weight_host(N, K, seed=int(rng.integers(1 << 30)))
+        X = workloads.act_host(M, K, seed=int(rng.integers(1 << 30)))
+        run_both_modes(nfp, X, W, "random M=%d N=%d K=%d" % (M, N, K))
+
+
 def test_empty_batch_and_empty_layer(nfp):
     # M = 0 and N = 0 are legal and launch nothing: the output keeps what it held
     K = 64
