@@ -456,10 +456,12 @@ def select_mode(tokens, threshold=1024):
     return int(lib().nestedfp_select_mode(int(tokens), int(threshold)))
 
 
-def probe_stream_read(buf):
-    """Launches the read-only streaming probe over `buf` (uint8 device tensor, a multiple of 64 KiB)."""
-    sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
-    st = lib().nestedfp_probe_stream_read(_ptr(buf), buf.numel(), _ptr(sink), _stream())
+def probe_stream_read(buf, sink=None):
+    """Launches the read-only streaming probe over `buf` (device tensor of a multiple of 64 KiB);
+    `sink`: an int32 device tensor to reuse (e.g. under graph capture), else one is made."""
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    st = lib().nestedfp_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream())
     _check(st, "nestedfp_probe_stream_read")
 
 
