@@ -295,7 +295,8 @@ def main():
         "fp8_mode": {"ms": t_fp8 * 1e3, "GBps": step_bytes["fp8"] / t_fp8 / 1e9,
                      "TFLOPs": step_flops / t_fp8 / 1e12,
                      "frac_hbm": step_bytes["fp8"] / t_fp8 / 1e9 / HBM_PEAK_GBPS,
-                     "frac_of_stream_read": step_bytes["fp8"] / t_fp8 / 1e9 / achievable["hbm_GBps"]},
+                     "frac_of_stream_read": step_bytes["fp8"] / t_fp8 / 1e9 / achievable["hbm_GBps"],
+                     "frac_of_stream_read_cut_like_the_step": step_bytes["fp8"] / t_fp8 / 1e9 / achievable["hbm_GBps_cut_like_the_fp8_step"]},
         "legs_interleaved": legs_out,
         "ratios": ratios,
         "achievable": achievable,
@@ -402,20 +403,25 @@ def achievable_rates(torch, nfp, workloads, stack, timer, dev):
     del bufs
     # the same read stream cut like the decode step: one launch per linear over that linear's FP16
     # weights (2NK bytes, what FP16 mode streams), all launches of the stack in one graph
+    # and over that linear's upper plane alone (NK bytes, what FP8 mode streams)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
-    reads = [e["W"] for e in stack if (e["W"].numel() * 2) % 65536 == 0]
+    cut = {}
+    for key, field in (("fp16", "W"), ("fp8", "rowmajor")):
+        reads = [e[field] if key == "fp16" else e[field][0] for e in stack]
+        reads = [w for w in reads if (w.numel() * w.element_size()) % 65536 == 0]
 
-    def read_stack():
-        for w in reads:
-            nfp.probe_stream_read(w, sink)
-    read_stack()
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
+        def read_stack():
+            for w in reads:
+                nfp.probe_stream_read(w, sink)
         read_stack()
-    ts = timer.run({"read": lambda i: g.replay()}, 1, 5)["read"]
-    hbm_cut = sum(w.numel() * 2 for w in reads) / statistics.median(ts) / 1e9
-    del g
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            read_stack()
+        ts = timer.run({"read": lambda i: g.replay()}, 1, 5)["read"]
+        cut[key] = sum(w.numel() * w.element_size() for w in reads) / statistics.median(ts) / 1e9
+        n_reads = len(reads)
+        del g
     # operand blocks: 8 x 8 KB = weights, activations, weights, ... (see nestedfp_probe_mfma)
     w16 = stack[0]["W"].reshape(-1)[:16384].view(torch.uint8)
     x16 = workloads.act_device(4, 4096, seed=3).reshape(-1)[:16384].view(torch.uint8)
@@ -428,9 +434,10 @@ def achievable_rates(torch, nfp, workloads, stack, timer, dev):
                       for i in range(4) for s in (0, 1)]).contiguous()
     out = {"hbm_GBps": hbm, "hbm_frac_of_peak": hbm / HBM_PEAK_GBPS,
            "hbm_probe": "read-only kernel, 8 x 128-bit loads per lane, 1 GiB per launch, 4 buffers rotated",
-           "hbm_GBps_cut_like_the_step": hbm_cut,
-           "hbm_probe_cut_like_the_step": "the same kernel, one launch per linear of the stack over its 2NK bytes of FP16 weights, "
-                                          "%d launches replayed as one graph" % len(reads)}
+           "hbm_GBps_cut_like_the_step": cut["fp16"],
+           "hbm_GBps_cut_like_the_fp8_step": cut["fp8"],
+           "hbm_probe_cut_like_the_step": "the same kernel, one launch per linear of the stack over its 2NK bytes of FP16 weights "
+                                          "(FP8 step: its NK bytes of upper plane), %d launches replayed as one graph" % n_reads}
     for key, ops, fp8 in (("fp16", ops16, 0), ("fp8", ops8, 1)):
         iters = 4000
         flops = [0.0]
