@@ -530,6 +530,9 @@ struct BypassKernel {
     static_assert(WK == kNestedF16 || WK == kNestedF16Row || WK == kPlainF16Packed, "weights that go through registers");
     static constexpr bool MERGE = kind_is_nested(WK);
     static constexpr bool ROWMAJOR = WK == kNestedF16Row;
+    // 64-token tiles read every weight once per launch: packed blocks (whole lines per instruction) are
+    // marked non-temporal, as in the streaming kernel
+    static constexpr int POLICY = (!ROWMAJOR && TM == 64) ? 2 : 0;
     static constexpr int BLOCK_BYTES = 1024 * kind_elem_bytes(WK);   // packed kinds: one 16 x 64 block
     typedef TileStore<kNestedF16, TM, TN, 1, 8> Store;
     static constexpr int DW = 4;                               // waves that issue the token loads
@@ -583,9 +586,9 @@ struct BypassKernel {
 #pragma unroll
         for (int i = 0; i < FNB; ++i) {
             const uint32_t off = (c.w_off + (uint32_t)i * c.w_istep + (uint32_t)kt * (ROWMAJOR ? 64u : (uint32_t)BLOCK_BYTES)) | kill;
-            r.u[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off, 0, 0);
-            if (MERGE) r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, off, 0, 0);
-            else r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off + 1024u, 0, 0);
+            r.u[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off, 0, POLICY);
+            if (MERGE) r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw1, off, 0, POLICY);
+            else r.l[i] = __builtin_amdgcn_raw_buffer_load_b128(c.rw0, off + 1024u, 0, POLICY);
         }
     }
 
@@ -806,6 +809,7 @@ struct E4m3BypassKernel {
     static_assert(XA >= 3 && XA < NST && NRAW <= XA, "the stage being filled is neither the one in use nor the next");
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
+    static constexpr int POLICY = (!ROWMAJOR && TM == 64) ? 2 : 0;   // packed blocks, read once per launch: non-temporal
     struct Raw { intx4 u[FNB][2]; };                           // one K-tile of the wave's plane blocks
     struct Tok { intx4 q[FMB][2]; };                           // one K-tile of token fragments
 
@@ -829,7 +833,7 @@ struct E4m3BypassKernel {
 #pragma unroll
             for (int i = 0; i < FNB; ++i)
                 r.u[i][h] = __builtin_bit_cast(intx4, __builtin_amdgcn_raw_buffer_load_b128(
-                    c.rw, (c.w_off + (uint32_t)i * c.w_istep + (uint32_t)(2 * kt + h) * (ROWMAJOR ? 64u : 1024u)) | kill, 0, 0));
+                    c.rw, (c.w_off + (uint32_t)i * c.w_istep + (uint32_t)(2 * kt + h) * (ROWMAJOR ? 64u : 1024u)) | kill, 0, POLICY));
         }
     }
 

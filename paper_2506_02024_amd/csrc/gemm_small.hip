@@ -74,6 +74,15 @@ template <int KIND> struct WLayout {
     // the second 16 bytes of a lane's step, relative to the first (NestedFP: the other plane, same offset)
     static constexpr int SECOND = kind_is_nested(KIND) ? 0
                                   : (KIND == kPlainF16 ? 16 : (PACKED ? 1024 : 64));
+    // Cache policy of the weight loads.  Every weight is read once per launch.  Packed kinds fetch whole
+    // 128-byte lines (a contiguous kilobyte per instruction) and mark them non-temporal (nt, bit 1),
+    // so that they pass through L2 without displacing the activations and partial sums: the decode step
+    // runs 5-8 % faster.  Row-major kinds take 64-byte pieces of a line, the other half follows in a
+    // later instruction, and the same hint makes them 4-12 % slower (measured), so they keep the default.
+#ifndef NFP_SMALL_POLICY
+#define NFP_SMALL_POLICY 2
+#endif
+    static constexpr int POLICY = PACKED ? NFP_SMALL_POLICY : 0;
 };
 
 // Weights of K-step `S` of the wave's slice.  The whole offset is in the range-checked VGPR part of
@@ -84,8 +93,8 @@ __device__ __forceinline__ void load_w(WItem &r, __amdgpu_buffer_rsrc_t r0, __am
                                        uint32_t voff, bool va, bool vb) {
     typedef WLayout<KIND> L;
     const uint32_t oa = va ? voff : kDead, ob = vb ? voff : kDead;
-    r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, oa + S * L::STEP, 0, 0);
-    r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, ob + S * L::STEP + L::SECOND, 0, 0);
+    r.a = __builtin_amdgcn_raw_buffer_load_b128(r0, oa + S * L::STEP, 0, L::POLICY);
+    r.b = __builtin_amdgcn_raw_buffer_load_b128(r1, ob + S * L::STEP + L::SECOND, 0, L::POLICY);
 }
 
 // Activations of one K-step for 16 tokens (32 bytes per lane); zero outside M and K.
