@@ -525,14 +525,16 @@ large_gemm_kernel(LargeParams p) {
 // DEEP: a ring of eight token stages with the token loads six and the plane loads four K-tiles ahead
 // (tiles of at most 128 tokens, launches that do not fill the chip: there a K-tile's MFMAs are
 // short against the latency of a load) instead of four stages and three / two K-tiles.
-template <int TM, int TN, int WK, bool DEEP = false>
+template <int TM, int TN, int WK, bool DEEP = false, bool NT = false>
 struct BypassKernel {
     static_assert(WK == kNestedF16 || WK == kNestedF16Row || WK == kPlainF16Packed, "weights that go through registers");
     static constexpr bool MERGE = kind_is_nested(WK);
     static constexpr bool ROWMAJOR = WK == kNestedF16Row;
-    // 64-token tiles read every weight once per launch: packed blocks (whole lines per instruction) are
-    // marked non-temporal, as in the streaming kernel
-    static constexpr int POLICY = (!ROWMAJOR && TM == 64) ? 2 : 0;
+    // NT: the launch has one token tile, so every weight is read once; packed blocks (whole lines per
+    // instruction) are then marked non-temporal, as in the streaming kernel.  The 64-token tiles always
+    // are; the 128-token tiles on the large layers (timed: 6-10 % faster from about 100 Mi weights on at
+    // M = 96 and 128, a few per cent slower on the small ones).
+    static constexpr int POLICY = (!ROWMAJOR && (NT || TM == 64)) ? 2 : 0;
     static constexpr int BLOCK_BYTES = 1024 * kind_elem_bytes(WK);   // packed kinds: one 16 x 64 block
     typedef TileStore<kNestedF16, TM, TN, 1, 8> Store;
     static constexpr int DW = 4;                               // waves that issue the token loads
@@ -777,11 +779,11 @@ struct BypassKernel {
     }
 };
 
-template <int TM, int TN, int WK, bool DEEP>
+template <int TM, int TN, int WK, bool DEEP, bool NT>
 __global__ void __launch_bounds__(512)
 nested_bypass_kernel(LargeParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    typedef BypassKernel<TM, TN, WK, DEEP> Kern;
+    typedef BypassKernel<TM, TN, WK, DEEP, NT> Kern;
     Kern::run(p, lds_raw, (typename Kern::lds_byte *)lds_raw);
 }
 
@@ -1161,10 +1163,10 @@ static void launch_large_t(const LargeParams &p, dim3 grid, hipStream_t stream) 
     kern<<<grid, 64 * WAVES_M * WAVES_N, lds, stream>>>(p);
 }
 
-template <int TM, int TN, int WK, bool DEEP = false>
+template <int TM, int TN, int WK, bool DEEP = false, bool NT = false>
 static void launch_bypass(const LargeParams &p, dim3 grid, hipStream_t stream) {
-    auto kern = nested_bypass_kernel<TM, TN, WK, DEEP>;
-    constexpr int lds = BypassKernel<TM, TN, WK, DEEP>::LDS_BYTES;
+    auto kern = nested_bypass_kernel<TM, TN, WK, DEEP, NT>;
+    constexpr int lds = BypassKernel<TM, TN, WK, DEEP, NT>::LDS_BYTES;
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -1210,12 +1212,27 @@ static void launch_nested(const LargeParams &p, const LargeConfig &c, dim3 grid,
     if (c.tm == 64) launch_bypass<64, 128, WK>(p, grid, stream);
     else if (c.tm == 256 && c.tn == 256) launch_bypass<256, 256, WK>(p, grid, stream);
     else if (c.tm == 256) launch_bypass<256, 128, WK>(p, grid, stream);
-    else if (c.tn == 256) {
-        if (c.deep) launch_bypass<128, 256, WK, true>(p, grid, stream);
-        else launch_bypass<128, 256, WK>(p, grid, stream);
-    } else {
-        if (c.deep) launch_bypass<128, 128, WK, true>(p, grid, stream);
-        else launch_bypass<128, 128, WK>(p, grid, stream);
+    else {
+        // one token tile over a large packed layer: weights marked non-temporal (see BypassKernel)
+        if constexpr (WK != kNestedF16Row) {
+            if (p.tiles_m == 1 && (int64_t)p.N * p.K >= ((int64_t)100 << 20)) {
+                if (c.tn == 256) {
+                    if (c.deep) launch_bypass<128, 256, WK, true, true>(p, grid, stream);
+                    else launch_bypass<128, 256, WK, false, true>(p, grid, stream);
+                } else {
+                    if (c.deep) launch_bypass<128, 128, WK, true, true>(p, grid, stream);
+                    else launch_bypass<128, 128, WK, false, true>(p, grid, stream);
+                }
+                return;
+            }
+        }
+        if (c.tn == 256) {
+            if (c.deep) launch_bypass<128, 256, WK, true>(p, grid, stream);
+            else launch_bypass<128, 256, WK>(p, grid, stream);
+        } else {
+            if (c.deep) launch_bypass<128, 128, WK, true>(p, grid, stream);
+            else launch_bypass<128, 128, WK>(p, grid, stream);
+        }
     }
 }
 
