@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--skip-small", action="store_true")
     ap.add_argument("--shapes", nargs="*", default=None, help="N,K pairs instead of the built-in model shapes")
     ap.add_argument("--margin", type=float, default=0.03)
+    ap.add_argument("--m-points", nargs="*", type=int, default=None,
+                    help="batch sizes of the tiled section instead of the built-in list (to re-time a part of the table)")
     ap.add_argument("--log", default=None, help="write every timing as JSON lines")
     args = ap.parse_args()
 
@@ -169,7 +171,7 @@ def main():
         copies = max(2, min(64, -(-1_200_000_000 // (N * K))))
         Ws = [workloads.weight_device(N, K, 0.02, seed=i) for i in range(copies)]
         planes = [nfp.decompose(W, packed=True) for W in Ws]
-        for M in M_POINTS:
+        for M in (args.m_points or M_POINTS):
             X = workloads.act_device(M, K, seed=2)
             Y = torch.empty((M, N), dtype=torch.float16, device=dev)
             # room for any split that is tried (up to 8 below 4096 tokens, the built-in choice above)
