@@ -294,12 +294,16 @@ int nestedfp_select_mode(int64_t tokens, int64_t threshold);
  * probe_stream_read: every wave reads `bytes` (a multiple of 65536) of `src` once with 128-bit
  *   loads, many in flight, and keeps nothing (a checksum of a few lanes goes to *sink, device,
  *   4 bytes): the rate a weight stream can reach at best.
+ * probe_stream_read_sparse: the same read (`bytes` a multiple of 131072) with 16 KB per wave and at
+ *   most 8 waves per CU; fewer, longer-lived waves read faster than the many small workgroups of the
+ *   probe above, so this is the higher of the two rates.
  * probe_mfma: `iters` rounds of dependent-free MFMAs on operands filled from `operands`
  *   (device, at least 65536 bytes, the caller's choice of bit patterns) on every CU;
  *   fp8 = 0: v_mfma_f32_16x16x32_f16, fp8 = 1: v_mfma_f32_16x16x128_f8f6f4.  *flops_host
  *   receives the flops one call performs.  Results go to *sink (device, 4 bytes).
  */
 int nestedfp_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+int nestedfp_probe_stream_read_sparse(const void *src, size_t bytes, uint32_t *sink, void *stream);
 int nestedfp_probe_mfma(const void *operands, int fp8, int iters, uint32_t *sink,
                         double *flops_host, void *stream);
 

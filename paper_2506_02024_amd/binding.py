@@ -89,6 +89,8 @@ def lib():
     L.nestedfp_select_mode.argtypes = [i64, i64]
     L.nestedfp_probe_stream_read.restype = ci
     L.nestedfp_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    L.nestedfp_probe_stream_read_sparse.restype = ci
+    L.nestedfp_probe_stream_read_sparse.argtypes = [vp, sz, vp, vp]
     L.nestedfp_probe_mfma.restype = ci
     L.nestedfp_probe_mfma.argtypes = [vp, ci, ci, vp, c.POINTER(c.c_double), vp]
     L.nestedfp_linear_workspace_size.restype = sz
@@ -456,12 +458,14 @@ def select_mode(tokens, threshold=1024):
     return int(lib().nestedfp_select_mode(int(tokens), int(threshold)))
 
 
-def probe_stream_read(buf, sink=None):
-    """Launches the read-only streaming probe over `buf` (device tensor of a multiple of 64 KiB);
-    `sink`: an int32 device tensor to reuse (e.g. under graph capture), else one is made."""
+def probe_stream_read(buf, sink=None, sparse=False):
+    """Launches the read-only streaming probe over `buf` (device tensor of a multiple of 64 KiB; 128 KiB
+    for the variant with few waves per CU, `sparse`); `sink`: an int32 device tensor to reuse (e.g.
+    under graph capture), else one is made."""
     if sink is None:
         sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
-    st = lib().nestedfp_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream())
+    fn = lib().nestedfp_probe_stream_read_sparse if sparse else lib().nestedfp_probe_stream_read
+    st = fn(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream())
     _check(st, "nestedfp_probe_stream_read")
 
 

@@ -556,6 +556,12 @@ int nestedfp_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, vo
     return launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream));
 }
 
+int nestedfp_probe_stream_read_sparse(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+    if (src == nullptr || sink == nullptr) return NESTEDFP_ERR_ARG;
+    if (bytes == 0 || (bytes & 131071) != 0 || !aligned(src, 16) || bytes / 131072 > 0x7fffffffu) return NESTEDFP_ERR_SHAPE;
+    return launch_probe_stream_read_sparse(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 int nestedfp_probe_mfma(const void *operands, int fp8, int iters, uint32_t *sink, double *flops_host, void *stream) {
     if (operands == nullptr || sink == nullptr || iters <= 0) return NESTEDFP_ERR_ARG;
     if (!aligned(operands, 16)) return NESTEDFP_ERR_SHAPE;

@@ -114,6 +114,7 @@ int launch_splitk_reduce(const float *partials, int S, int64_t M, int64_t N, con
 
 bool large_gemm_supports(int kind, int64_t K, int64_t ldx, int64_t ldw);
 int launch_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
+int launch_probe_stream_read_sparse(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
 int launch_probe_mfma(const void *operands, int fp8, int iters, uint32_t *sink, double *flops_host,
                       hipStream_t stream);
 

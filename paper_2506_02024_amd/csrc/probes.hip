@@ -23,6 +23,36 @@ stream_read_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ sink)
     if (x == 0x9e3779b9u && lane == 63) *sink = x;
 }
 
+// The same read with 16 KB per wave and at most one workgroup of 8 waves per CU (a dynamic LDS
+// allocation of 160 KB that nothing touches keeps a second one out).  The kernel above is held back by
+// the turnover of its many small workgroups, not by memory: fewer and longer-lived waves read faster.
+__global__ void __launch_bounds__(512)
+stream_read_sparse_kernel(const uint8_t *__restrict__ src, uint32_t *__restrict__ sink) {
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const u32x4 *p = reinterpret_cast<const u32x4 *>(src + wave * 16384 + lane * 16);
+    u32x4 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = __builtin_nontemporal_load(p + i * 64);
+    uint32_t x = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+    if (x == 0x9e3779b9u && lane == 63) *sink = x;
+}
+
+int launch_probe_stream_read_sparse(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream) {
+    constexpr int lds = 160 * 1024;
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(stream_read_sparse_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set.store(true, std::memory_order_release);
+    }
+    // bytes is a multiple of 131072: whole workgroups of 8 waves x 16 KB
+    stream_read_sparse_kernel<<<(unsigned)(bytes / 131072), 512, lds, stream>>>(static_cast<const uint8_t *>(src), sink);
+    return hip_ok(hipGetLastError());
+}
+
 int launch_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream) {
     const size_t waves = bytes / 8192;                 // bytes is a multiple of 65536: whole workgroups of 8 waves
     stream_read_kernel<<<(unsigned)(waves / 8), 512, 0, stream>>>(static_cast<const uint8_t *>(src), sink);

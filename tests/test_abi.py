@@ -110,6 +110,8 @@ def test_argument_errors_are_reported_before_any_launch(L):
     # measurement probes reject bad arguments
     assert L.nestedfp_probe_stream_read(P(0), 65536, fake, P(0)) == 1
     assert L.nestedfp_probe_stream_read(fake, 1000, fake, P(0)) == 2
+    assert L.nestedfp_probe_stream_read_sparse(P(0), 131072, fake, P(0)) == 1
+    assert L.nestedfp_probe_stream_read_sparse(fake, 65536, fake, P(0)) == 2
     assert L.nestedfp_probe_mfma(fake, 0, 0, fake, None, P(0)) == 1
     # tuning hook
     assert L.nestedfp_tune(b"no_such_knob", 1) == 1
