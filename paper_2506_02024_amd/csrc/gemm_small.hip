@@ -155,8 +155,21 @@ struct FetchTile {
     static __device__ __forceinline__ void run(WItem (&w)[SPW], __amdgpu_buffer_rsrc_t r0,
                                                __amdgpu_buffer_rsrc_t r1, uint32_t voff,
                                                const bool (&va)[SPW], const bool (&vb)[SPW]) {
-        load_w<KIND, S>(w[S], r0, r1, voff, va[S], vb[S]);
-        FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff, va, vb);
+        if constexpr (KIND == kNestedF16 && S == 0) {
+            // packed planes: the tile's blocks of the upper plane first, then those of the lower plane,
+            // two runs of consecutive kilobytes instead of an alternation between two distant arrays
+            // (about 1 % on the decode step, timed against the plain kernel of the same run as control)
+            typedef WLayout<KIND> L;
+#pragma unroll
+            for (int q = 0; q < SPW; ++q)
+                w[q].a = __builtin_amdgcn_raw_buffer_load_b128(r0, (va[q] ? voff : kDead) + q * L::STEP, 0, L::POLICY);
+#pragma unroll
+            for (int q = 0; q < SPW; ++q)
+                w[q].b = __builtin_amdgcn_raw_buffer_load_b128(r1, (vb[q] ? voff : kDead) + q * L::STEP + L::SECOND, 0, L::POLICY);
+        } else {
+            load_w<KIND, S>(w[S], r0, r1, voff, va[S], vb[S]);
+            FetchTile<KIND, SPW, S + 1>::run(w, r0, r1, voff, va, vb);
+        }
     }
 };
 template <int KIND, int SPW>
